@@ -1,0 +1,110 @@
+"""Pins for the CPU checker's pair scorer (no GPU): closed forms, special cases
+that reduce to plain sums, and a black-box float64 library MLP."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+
+INF = synth.INFEASIBLE
+
+
+def _zero_params(F, H):
+    return {"W1": np.zeros((H, 2 * F), np.float32), "b1": np.zeros(H, np.float32),
+            "W2": np.zeros((H, H), np.float32), "b2": np.zeros(H, np.float32),
+            "W3": np.zeros(H, np.float32), "b3": np.zeros(1, np.float32)}
+
+
+def test_all_zero_predictor_gives_half_scale(orc):
+    F, H, S = 8, 16, 2 ** 20
+    x_on = synth.uniform_features(1, 0, 12, F) * np.float32(0.4)
+    x_off = synth.uniform_features(1, 1, 20, F) * np.float32(0.4)
+    sig, W = orc.score_pairs(x_on, x_off, _zero_params(F, H), S)
+    assert (sig == np.float32(0.5)).all() and (W == S // 2).all()
+
+
+def test_identity_network_reduces_to_feature_sums(orc):
+    # W1 = [I | I], W2 = I, W3 = 1, no biases, non-negative features:
+    # z = sum_k (x_u[k] + x_v[k]); an operand swap or a dropped half of layer 1 changes it
+    F = H = 8
+    p = _zero_params(F, H)
+    p["W1"][:, :F] = np.eye(F); p["W1"][:, F:] = np.eye(F)
+    p["W2"][:] = np.eye(H); p["W3"][:] = 1.0
+    x_on = synth.uniform_features(2, 0, 9, F) * np.float32(0.3)
+    x_off = synth.uniform_features(2, 1, 14, F) * np.float32(0.3)
+    sig, _ = orc.score_pairs(x_on, x_off, p, 2 ** 20)
+    z = x_on.astype(np.float64).sum(1)[:, None] + x_off.astype(np.float64).sum(1)[None, :]
+    np.testing.assert_allclose(sig, (1 / (1 + np.exp(-z))).astype(np.float32), rtol=1e-7)
+
+
+def test_online_and_offline_halves_are_not_interchangeable(orc):
+    # layer 1 reads the online features through columns [0,F) and the offline ones through [F,2F)
+    F, H = 4, 4
+    p = _zero_params(F, H)
+    p["W1"][0, 0] = 1.0          # only online feature 0 feeds unit 0
+    p["W2"][0, 0] = 1.0; p["W3"][0] = 1.0
+    x_on = np.array([[0.25, 0, 0, 0]], np.float32); x_off = np.array([[0.75, 0, 0, 0]], np.float32)
+    sig, _ = orc.score_pairs(x_on, x_off, p, 2 ** 20, mem_limit=2.0)
+    assert sig[0, 0] == np.float32(1 / (1 + np.exp(-0.25)))
+
+
+def test_dead_relu_leaves_bias_path(orc):
+    F, H = 6, 10
+    p = synth.predictor_params(3, F, H)
+    p["W1"] = -np.abs(p["W1"]); p["b1"] = -np.abs(p["b1"])      # h1 == 0 for non-negative inputs
+    x_on = synth.uniform_features(3, 0, 5, F); x_off = synth.uniform_features(3, 1, 7, F)
+    sig, _ = orc.score_pairs(x_on, x_off, p, 2 ** 20)
+    z = float(p["b3"][0]) + float((p["W3"].astype(np.float64) * np.maximum(p["b2"].astype(np.float64), 0)).sum())
+    np.testing.assert_allclose(sig, np.float32(1 / (1 + np.exp(-z))), rtol=1e-7)
+
+
+@pytest.mark.parametrize("cfg", ["C1", "C3"])
+def test_matches_black_box_float64_mlp(orc, cfg):
+    r = synth.scheduling_round(cfg, 5, n=48, m=80)
+    p, F = r["params"], r["cfg"].F
+    sig, W = orc.score_pairs(r["x_on"], r["x_off"], p, r["cfg"].scale)
+    lin1 = torch.nn.Linear(2 * F, r["cfg"].H, dtype=torch.float64)
+    lin2 = torch.nn.Linear(r["cfg"].H, r["cfg"].H, dtype=torch.float64)
+    lin3 = torch.nn.Linear(r["cfg"].H, 1, dtype=torch.float64)
+    with torch.no_grad():
+        lin1.weight.copy_(torch.from_numpy(p["W1"]).double()); lin1.bias.copy_(torch.from_numpy(p["b1"]).double())
+        lin2.weight.copy_(torch.from_numpy(p["W2"]).double()); lin2.bias.copy_(torch.from_numpy(p["b2"]).double())
+        lin3.weight.copy_(torch.from_numpy(p["W3"]).double()[None, :]); lin3.bias.copy_(torch.from_numpy(p["b3"]).double())
+        net = torch.nn.Sequential(lin1, torch.nn.ReLU(), lin2, torch.nn.ReLU(), lin3, torch.nn.Sigmoid())
+        xo = torch.from_numpy(r["x_on"]).double(); xf = torch.from_numpy(r["x_off"]).double()
+        pairs = torch.cat([xo[:, None, :].expand(-1, xf.shape[0], -1), xf[None, :, :].expand(xo.shape[0], -1, -1)], dim=2)
+        ref = net(pairs)[..., 0].numpy()
+    np.testing.assert_allclose(sig.astype(np.float64), ref, rtol=1e-7)
+    # float32 evaluation of the same loops stays within float32 noise of the wide one
+    sig32, _ = orc.score_pairs(r["x_on"], r["x_off"], p, r["cfg"].scale, wide=False)
+    assert np.max(np.abs(sig32 - sig) / sig) < 5e-6
+
+
+def test_quantisation_and_mask_rule(orc):
+    r = synth.scheduling_round("C1", 9)
+    S = r["cfg"].scale
+    sig, W = orc.score_pairs(r["x_on"], r["x_off"], r["params"], S)
+    mem = r["x_on"][:, 0][:, None] + r["x_off"][:, 0][None, :]          # one float32 addition
+    assert mem.dtype == np.float32
+    masked = mem > np.float32(1.0)
+    assert ((W == INF) == masked).all()
+    q = np.rint(sig * np.float32(S)).astype(np.int64)                   # float32 product, half-to-even
+    assert (W[~masked] == q[~masked]).all()
+    assert W[~masked].min() >= 0 and W[~masked].max() <= S
+    # equality with the limit is feasible
+    x_on = np.array([[0.5] + [0.0] * 15], np.float32); x_off = np.array([[0.5] + [0.0] * 15], np.float32)
+    assert orc.score_pairs(x_on, x_off, r["params"], S)[1][0, 0] != INF
+    # few-level scale
+    _, W8 = orc.score_pairs(r["x_on"], r["x_off"], r["params"], 255.0)
+    assert set(np.unique(W8[~masked])) <= set(range(256))
+    assert (W8[~masked] == np.rint(sig * np.float32(255.0)).astype(np.int64)[~masked]).all()
+
+
+def test_uniform_mask_fraction_matches_closed_form():
+    # features U(0,1) scaled by c: P(c(a+b) > 1) = (2 - 1/c)^2 / 2 for 1/2 <= c <= 1
+    for target in (0.10, 0.25):
+        r = synth.scheduling_round(synth.RoundConfig("t", 1500, 1500, 4, 8, 1.0, "uniform", target), 2)
+        c = r["mem_scale"]
+        assert abs((2 - 1 / c) ** 2 / 2 - target) < 0.01
+        realised = ((r["x_on"][:, 0][:, None] + r["x_off"][:, 0][None, :]) > np.float32(1)).mean()
+        assert abs(realised - target) < 2e-3
