@@ -1,0 +1,177 @@
+/*
+ * muxmatch - the data-parallel core of matching-based GPU-sharing scheduling
+ * on one AMD MI355X (gfx950).
+ *
+ * One scheduling round (paper: Section "Matching-based scheduling", Algorithm
+ * "Scheduling algorithm") builds a bipartite graph between n online and m
+ * offline workloads whose edge (u, v) carries the predicted normalised
+ * throughput of v when it shares a GPU with u, and then takes the maximum
+ * weighted matching of that graph as the sharing plan.  This library does the
+ * two heavy steps on the GPU:
+ *
+ *   mf_score_pairs       every edge weight, from the speed-predictor MLP
+ *   mf_solve_assignment  the maximum-weight matching, with a proof of optimality
+ *   mf_check_certificate re-verifies such a proof on the device
+ *   mf_schedule_round    the two steps back to back (one call per round)
+ *
+ * Conventions shared by every call
+ *   - Pointers named d_* are DEVICE pointers (HIP global memory on the device
+ *     the context was created for); pointers named h_* are HOST pointers.
+ *   - The caller owns every buffer it passes.  The library allocates nothing
+ *     in these calls (all scratch lives in the context, sized at mf_create),
+ *     never frees a caller buffer and keeps no caller pointer after return.
+ *   - Matrices are row-major.  The weight matrix W has n rows (online) and m
+ *     columns (offline) of int32 with a row pitch of ldw elements (ldw >= m,
+ *     ldw a multiple of 4 and d_W 16-byte aligned).  An entry equal to
+ *     MF_INFEASIBLE means "this pair must not share a GPU"; every other entry
+ *     is a weight in [0, 2^30].
+ *   - Work is enqueued on the stream given to mf_create.  A call that is
+ *     handed a non-NULL h_res waits for its own work and fills *h_res; with
+ *     h_res == NULL mf_score_pairs returns without waiting.  The solver
+ *     always waits (it steers its iteration from the host).
+ *   - Return value: MF_OK (0) or a negative MF_ERR_* code; nothing is thrown
+ *     across this boundary.  On error the output buffers are unspecified.
+ *   - A context may be used by one thread at a time.
+ */
+#ifndef MUXMATCH_H
+#define MUXMATCH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MF_INFEASIBLE INT32_MIN
+
+enum {
+    MF_OK = 0,
+    MF_ERR_ARG = -1,            /* null pointer, non-positive size, bad pitch or alignment   */
+    MF_ERR_SHAPE = -2,          /* n > m, or a size beyond what the context was created for  */
+    MF_ERR_HIP = -3,            /* a HIP runtime call failed (see mf_last_hip_error)         */
+    MF_ERR_NOT_CONVERGED = -4,  /* the solver hit its round limit                            */
+    MF_ERR_CERT = -5,           /* the optimality certificate did not verify                 */
+    MF_ERR_RANGE = -6           /* weights too large for exact arithmetic at this n          */
+};
+
+typedef struct mf_ctx mf_ctx;
+
+/*
+ * The speed predictor P of the scheduling algorithm: an MLP with two hidden
+ * layers of width H over the concatenated features [online ; offline] of a
+ * pair (paper: Section "Matching-based scheduling" for the inputs and the
+ * regression target; Section "Implementation" for the shape).  Hidden
+ * activations are ReLU; the output goes through a logistic function and is
+ * quantised to round-half-even(sigma * scale) as int32.
+ * A pair whose memory fractions add up (one float32 addition) to more than
+ * mem_limit is infeasible: feature index mem_feature of each side is that
+ * fraction (paper: Section "Implementation", the offline memory quota).
+ * All parameter pointers are DEVICE pointers to float32, row-major.
+ */
+typedef struct {
+    int32_t F;                  /* features per workload (1..256)                       */
+    int32_t H;                  /* hidden width: 64 or 128                              */
+    float   scale;              /* S > 0; weights land in [0, S], S <= 2^30             */
+    int32_t mem_feature;        /* 0 <= mem_feature < F                                 */
+    float   mem_limit;          /* e.g. 1.0f                                            */
+    const float *d_W1;          /* [H][2F]: columns [0,F) online, [F,2F) offline        */
+    const float *d_b1;          /* [H]                                                  */
+    const float *d_W2;          /* [H][H]                                               */
+    const float *d_b2;          /* [H]                                                  */
+    const float *d_W3;          /* [H]                                                  */
+    const float *d_b3;          /* [1]                                                  */
+} mf_predictor;
+
+/* Filled on the host by the solving calls. */
+typedef struct {
+    int64_t primal;             /* P: sum of matched weights (weight units)             */
+    int64_t dual;               /* D: sum u + sum v (1/K weight units)                  */
+    int64_t K;                  /* dual scale, K = n + 1                                */
+    int64_t min_reduced_cost;   /* min over feasible (i,j) of u_i + v_j - K*W_ij        */
+    int64_t rounds;             /* bidding rounds run (forward + reverse)               */
+    int64_t bids;               /* row/column scans performed by bidding rounds         */
+    int64_t bytes_scanned;      /* weight-matrix bytes those scans read                 */
+    int32_t matched;            /* rows with a partner                                  */
+    int32_t phases;             /* epsilon-scaling phases                               */
+    int32_t cert_ok;            /* 1: matching valid, duals feasible, 0 <= D - K*P < K  */
+    int32_t status;             /* same code the call returned                          */
+    float   ms_solve;           /* device time of the auction (HIP events)              */
+    float   ms_certify;         /* device time of dual extraction + certificate         */
+} mf_result;
+
+/*
+ * Creates a context bound to HIP device `device` and to `hip_stream` (a
+ * hipStream_t passed as void*, NULL = the default stream).  Allocates all
+ * scratch for problems up to max_n x max_m (max_n <= max_m <= 2^20 - 2):
+ * layer-1 projections, a transposed copy of the weight matrix
+ * (4*max_n*max_m bytes) and O(max_n + max_m) solver state.
+ * Fails with MF_ERR_HIP when no such device exists or memory runs out.
+ */
+int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m);
+int mf_destroy(mf_ctx *ctx);
+
+/*
+ * Edge-building loop of the scheduling algorithm: for every pair (i, j)
+ *   d_W[i*ldw + j] = quantised predictor output, or MF_INFEASIBLE.
+ * d_on is [n][F], d_off is [m][F] float32 (device).  If d_sigma is not NULL
+ * it must hold n*m floats and receives the unquantised score of every pair
+ * (pitch m).  Padding columns [m, ldw) are left untouched.
+ */
+int mf_score_pairs(mf_ctx *ctx, const mf_predictor *pred,
+                   const float *d_on, int n, const float *d_off, int m,
+                   int32_t *d_W, int64_t ldw, float *d_sigma);
+
+/*
+ * GetMatching of the scheduling algorithm: a maximum-weight matching of the
+ * bipartite graph given by d_W (n <= m).  A matching is a set of feasible
+ * pairs using each row and each column at most once; it need not be perfect.
+ * Outputs (device): d_row2col[n] (partner column, -1 = none) and integral
+ * duals d_u[n], d_v[m] in units of 1/K of a weight unit that satisfy
+ *   u, v >= 0,  u_i + v_j >= K*W_ij on every feasible pair,
+ *   0 <= sum u + sum v - K * (matched weight) < K,
+ * which by LP duality proves the matching optimal.  The certificate is
+ * evaluated on the device and reported in *h_res (host, required).
+ * The optimum weight is unique; which optimal matching is returned is not.
+ */
+int mf_solve_assignment(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
+                        int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
+
+/*
+ * Evaluates the certificate above for caller-supplied (row2col, u, v, K) on
+ * the device: fills primal, dual, K, min_reduced_cost, matched and cert_ok of
+ * *h_res.  Returns MF_OK when the check ran (look at cert_ok), an error code
+ * when it could not.
+ */
+int mf_check_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
+                         const int32_t *d_row2col, const int64_t *d_u, const int64_t *d_v,
+                         int64_t K, mf_result *h_res);
+
+/*
+ * One scheduling round: mf_score_pairs into d_W, then mf_solve_assignment on
+ * it.  Returns MF_ERR_CERT if the certificate does not verify.
+ */
+int mf_schedule_round(mf_ctx *ctx, const mf_predictor *pred,
+                      const float *d_on, int n, const float *d_off, int m,
+                      int32_t *d_W, int64_t ldw,
+                      int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
+
+/* Solver knobs (defaults: theta = 8, max_rounds = 4,000,000). */
+int mf_set_option(mf_ctx *ctx, const char *name, int64_t value);
+
+/*
+ * Device time, in milliseconds, of the kernels the last call on this context
+ * launched, by stage: what[0] layer-1 projections, [1] pair scoring,
+ * [2] bidding kernels, [3] settle/bookkeeping kernels, [4] transposition,
+ * [5] dual extraction, [6] certificate, [7] launches of the pair-scoring
+ * kernel, [8] launches of bidding kernels.  Measured with HIP events on the
+ * context's stream; entries of stages that did not run are 0.
+ */
+int mf_last_timings(mf_ctx *ctx, float what[16]);
+
+const char *mf_strerror(int code);
+const char *mf_last_hip_error(mf_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MUXMATCH_H */

@@ -1,0 +1,167 @@
+"""Thin ctypes binding over libmuxmatch.so: argument marshalling only.
+
+Every step of the scheduling round runs inside the library's HIP kernels;
+torch is used here for device buffers and the stream handle, nothing else.
+There is no CPU fallback: if the shared library is missing, importing this
+module raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmuxmatch.so")
+
+INFEASIBLE = -2147483648
+OK, ERR_ARG, ERR_SHAPE, ERR_HIP, ERR_NOT_CONVERGED, ERR_CERT, ERR_RANGE = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = ["mf_create", "mf_destroy", "mf_score_pairs", "mf_solve_assignment",
+           "mf_check_certificate", "mf_schedule_round", "mf_set_option", "mf_last_timings",
+           "mf_strerror", "mf_last_hip_error"]
+
+TIMING_NAMES = ["projections_ms", "pair_scoring_ms", "bulk_bid_ms", "bulk_bid_launches",
+                "transpose_ms", "duals_ms", "certificate_ms", "auction_ms", "bulk_bid_bytes"]
+
+
+class Predictor(C.Structure):
+    _fields_ = [("F", C.c_int32), ("H", C.c_int32), ("scale", C.c_float),
+                ("mem_feature", C.c_int32), ("mem_limit", C.c_float),
+                ("d_W1", C.c_void_p), ("d_b1", C.c_void_p), ("d_W2", C.c_void_p),
+                ("d_b2", C.c_void_p), ("d_W3", C.c_void_p), ("d_b3", C.c_void_p)]
+
+
+class Result(C.Structure):
+    _fields_ = [("primal", C.c_int64), ("dual", C.c_int64), ("K", C.c_int64),
+                ("min_reduced_cost", C.c_int64), ("rounds", C.c_int64), ("bids", C.c_int64),
+                ("bytes_scanned", C.c_int64), ("matched", C.c_int32), ("phases", C.c_int32),
+                ("cert_ok", C.c_int32), ("status", C.c_int32), ("ms_solve", C.c_float),
+                ("ms_certify", C.c_float)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+def load_library():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2303_13803_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
+    lib.mf_create.argtypes = [C.POINTER(vp), i32, vp, i32, i32]
+    lib.mf_destroy.argtypes = [vp]
+    lib.mf_score_pairs.argtypes = [vp, C.POINTER(Predictor), vp, i32, vp, i32, vp, i64, vp]
+    lib.mf_solve_assignment.argtypes = [vp, vp, i32, i32, i64, vp, vp, vp, C.POINTER(Result)]
+    lib.mf_check_certificate.argtypes = [vp, vp, i32, i32, i64, vp, vp, vp, i64, C.POINTER(Result)]
+    lib.mf_schedule_round.argtypes = [vp, C.POINTER(Predictor), vp, i32, vp, i32, vp, i64, vp, vp, vp,
+                                      C.POINTER(Result)]
+    lib.mf_set_option.argtypes = [vp, C.c_char_p, i64]
+    lib.mf_last_timings.argtypes = [vp, C.POINTER(C.c_float * 16)]
+    lib.mf_strerror.argtypes = [i32]
+    lib.mf_strerror.restype = C.c_char_p
+    lib.mf_last_hip_error.argtypes = [vp]
+    lib.mf_last_hip_error.restype = C.c_char_p
+    for name in EXPORTS:
+        if name not in ("mf_strerror", "mf_last_hip_error"):
+            getattr(lib, name).restype = i32
+    return lib
+
+
+_lib = load_library()
+
+
+class MuxmatchError(RuntimeError):
+    def __init__(self, code, detail=""):
+        self.code = code
+        super().__init__(f"muxmatch error {code}: {_lib.mf_strerror(code).decode()} {detail}".strip())
+
+
+def _ptr(t, dtype):
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"expected a contiguous device tensor of {dtype}")
+    return t.data_ptr()
+
+
+class Context:
+    """Owns the library's scratch for problems up to max_n x max_m on one device."""
+
+    def __init__(self, max_n, max_m, device=0, stream=None):
+        self.device = int(device)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        handle = C.c_void_p()
+        rc = _lib.mf_create(C.byref(handle), self.device, C.c_void_p(self.stream.cuda_stream),
+                            int(max_n), int(max_m))
+        if rc != OK:
+            raise MuxmatchError(rc)
+        self._h = handle
+        self._keep = None
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.mf_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def _check(self, rc, allow=()):
+        if rc != OK and rc not in allow:
+            detail = _lib.mf_last_hip_error(self._h).decode() if rc == ERR_HIP else ""
+            raise MuxmatchError(rc, detail)
+        return rc
+
+    def predictor(self, params, scale, mem_feature=0, mem_limit=1.0):
+        """params: dict of float32 device tensors W1 [H,2F], b1, W2 [H,H], b2, W3 [H], b3 [1]."""
+        H = params["b1"].numel()
+        F = params["W1"].shape[1] // 2
+        p = Predictor(F, H, float(scale), int(mem_feature), float(mem_limit),
+                      *[_ptr(params[k], torch.float32) for k in ("W1", "b1", "W2", "b2", "W3", "b3")])
+        p._keep = params
+        return p
+
+    def set_option(self, name, value):
+        self._check(_lib.mf_set_option(self._h, name.encode(), int(value)))
+
+    def score_pairs(self, pred, x_on, x_off, W, sigma=None):
+        n, m = x_on.shape[0], x_off.shape[0]
+        self._check(_lib.mf_score_pairs(self._h, C.byref(pred), _ptr(x_on, torch.float32), n,
+                                        _ptr(x_off, torch.float32), m, _ptr(W, torch.int32),
+                                        W.stride(0), _ptr(sigma, torch.float32)))
+
+    def solve_assignment(self, W, n, m, row2col, u, v, allow_cert_failure=False):
+        res = Result()
+        rc = _lib.mf_solve_assignment(self._h, _ptr(W, torch.int32), n, m, W.stride(0),
+                                      _ptr(row2col, torch.int32), _ptr(u, torch.int64),
+                                      _ptr(v, torch.int64), C.byref(res))
+        self._check(rc, allow=(ERR_CERT,) if allow_cert_failure else ())
+        return res
+
+    def check_certificate(self, W, n, m, row2col, u, v, K):
+        res = Result()
+        self._check(_lib.mf_check_certificate(self._h, _ptr(W, torch.int32), n, m, W.stride(0),
+                                              _ptr(row2col, torch.int32), _ptr(u, torch.int64),
+                                              _ptr(v, torch.int64), int(K), C.byref(res)))
+        return res
+
+    def schedule_round(self, pred, x_on, x_off, W, row2col, u, v):
+        n, m = x_on.shape[0], x_off.shape[0]
+        res = Result()
+        self._check(_lib.mf_schedule_round(self._h, C.byref(pred), _ptr(x_on, torch.float32), n,
+                                           _ptr(x_off, torch.float32), m, _ptr(W, torch.int32),
+                                           W.stride(0), _ptr(row2col, torch.int32),
+                                           _ptr(u, torch.int64), _ptr(v, torch.int64), C.byref(res)))
+        return res
+
+    def last_timings(self):
+        arr = (C.c_float * 16)()
+        self._check(_lib.mf_last_timings(self._h, C.byref(arr)))
+        return {name: float(arr[i]) for i, name in enumerate(TIMING_NAMES)}
+
+
+def strerror(code):
+    return _lib.mf_strerror(int(code)).decode()
+
+
+def raw_library():
+    return _lib

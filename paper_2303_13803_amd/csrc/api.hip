@@ -1,0 +1,234 @@
+// C entry points: argument checks, context life cycle, stage timing.
+#include "internal.h"
+#include <stdlib.h>
+#include <string.h>
+#include <new>
+
+namespace {
+
+template <typename T> hipError_t dev_alloc(T **p, size_t count)
+{
+    return hipMalloc((void **)p, count * sizeof(T));
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+int check_matrix(const mf_ctx *ctx, const void *d_W, int n, int m, int64_t ldw)
+{
+    if (!ctx || !d_W || n <= 0 || m <= 0 || ldw < m || (ldw & 3) || !aligned16(d_W)) return MF_ERR_ARG;
+    if (n > m || n > ctx->max_n || m > ctx->max_m) return MF_ERR_SHAPE;
+    return MF_OK;
+}
+
+int check_predictor(const mf_predictor *p)
+{
+    if (!p || !p->d_W1 || !p->d_b1 || !p->d_W2 || !p->d_b2 || !p->d_W3 || !p->d_b3) return MF_ERR_ARG;
+    if (p->F < 1 || p->F > 256 || (p->H != 64 && p->H != 128)) return MF_ERR_ARG;
+    if (!(p->scale > 0.0f) || p->scale > 1073741824.0f) return MF_ERR_ARG;
+    if (p->mem_feature < 0 || p->mem_feature >= p->F) return MF_ERR_ARG;
+    if (!aligned16(p->d_W2) || !aligned16(p->d_b2) || !aligned16(p->d_W3)) return MF_ERR_ARG;
+    return MF_OK;
+}
+
+void clear_timings(mf_ctx *ctx)
+{
+    memset(ctx->timings, 0, sizeof(ctx->timings));
+    ctx->score_pending = false;
+}
+
+int finish_score_timing(mf_ctx *ctx)
+{
+    MF_HIP(hipStreamSynchronize(ctx->stream));
+    float a = 0.0f, b = 0.0f;
+    MF_HIP(hipEventElapsedTime(&a, ctx->ev[0], ctx->ev[1]));
+    MF_HIP(hipEventElapsedTime(&b, ctx->ev[1], ctx->ev[2]));
+    ctx->timings[T_PROJ] = a;
+    ctx->timings[T_PAIR] = b;
+    ctx->score_pending = false;
+    return MF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
+{
+    if (!out || max_n <= 0 || max_m <= 0 || max_n > max_m || max_m > MF_MAX_DIM) return MF_ERR_ARG;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return MF_ERR_HIP;
+    if (hipSetDevice(device) != hipSuccess) return MF_ERR_HIP;
+    mf_ctx *ctx = new (std::nothrow) mf_ctx();
+    if (!ctx) return MF_ERR_HIP;
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->device = device;
+    ctx->stream = (hipStream_t)hip_stream;
+    ctx->max_n = max_n;
+    ctx->max_m = max_m;
+    ctx->theta = 8;
+    ctx->max_rounds = 4000000;
+    const size_t nm = (size_t)max_m;                      // max_m >= max_n
+    const size_t ldt = ((size_t)max_n + 3) & ~(size_t)3;
+    hipError_t e = hipSuccess;
+#define TRY(x) do { if (e == hipSuccess) e = (x); } while (0)
+    TRY(dev_alloc(&ctx->proj_on, (size_t)max_n * 128));
+    TRY(dev_alloc(&ctx->proj_off, (size_t)max_m * 128));
+    TRY(dev_alloc(&ctx->mem_on, (size_t)max_n));
+    TRY(dev_alloc(&ctx->mem_off, (size_t)max_m));
+    TRY(dev_alloc(&ctx->wt, (size_t)max_m * ldt));
+    TRY(dev_alloc(&ctx->price, (size_t)max_m + 8));
+    TRY(dev_alloc(&ctx->profit, (size_t)max_n + 8));
+    TRY(dev_alloc(&ctx->colword, (size_t)max_m));
+    TRY(dev_alloc(&ctx->roword, (size_t)max_n));
+    TRY(dev_alloc(&ctx->row2col, (size_t)max_n));
+    TRY(dev_alloc(&ctx->col2row, (size_t)max_m));
+    TRY(dev_alloc(&ctx->tent_tgt, nm));
+    TRY(dev_alloc(&ctx->tent_keep, nm));
+    TRY(dev_alloc(&ctx->list[0], nm));
+    TRY(dev_alloc(&ctx->list[1], nm));
+    TRY(dev_alloc(&ctx->cnt, 2));
+    TRY(dev_alloc(&ctx->colmark, (size_t)max_m));
+    TRY(dev_alloc(&ctx->stats, 1));
+    TRY(dev_alloc(&ctx->cert, 1));
+    TRY(hipHostMalloc((void **)&ctx->h_cnt, 2 * sizeof(int)));
+    TRY(hipHostMalloc((void **)&ctx->h_stats, sizeof(mf_device_stats)));
+    TRY(hipHostMalloc((void **)&ctx->h_cert, sizeof(mf_cert_out)));
+    for (int i = 0; i < 8; ++i) TRY(hipEventCreate(&ctx->ev[i]));
+#undef TRY
+    if (e != hipSuccess) {
+        ctx->hip_error = e;
+        mf_destroy(ctx);
+        return MF_ERR_HIP;
+    }
+    *out = ctx;
+    return MF_OK;
+}
+
+int mf_destroy(mf_ctx *ctx)
+{
+    if (!ctx) return MF_ERR_ARG;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->wt, ctx->price,
+                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->tent_tgt,
+                   ctx->tent_keep, ctx->list[0], ctx->list[1], ctx->cnt, ctx->colmark, ctx->stats,
+                   ctx->cert};
+    for (void *p : dev) if (p) (void)hipFree(p);
+    if (ctx->h_cnt) (void)hipHostFree(ctx->h_cnt);
+    if (ctx->h_stats) (void)hipHostFree(ctx->h_stats);
+    if (ctx->h_cert) (void)hipHostFree(ctx->h_cert);
+    for (int i = 0; i < 8; ++i) if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+    delete ctx;
+    return MF_OK;
+}
+
+int mf_score_pairs(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, int n,
+                   const float *d_off, int m, int32_t *d_W, int64_t ldw, float *d_sigma)
+{
+    if (!ctx || !d_on || !d_off || !d_W || n <= 0 || m <= 0 || ldw < m) return MF_ERR_ARG;
+    int rc = check_predictor(pred);
+    if (rc != MF_OK) return rc;
+    if (n > ctx->max_n || m > ctx->max_m) return MF_ERR_SHAPE;
+    MF_HIP(hipSetDevice(ctx->device));
+    clear_timings(ctx);
+    return mf_launch_score(ctx, pred, d_on, n, d_off, m, d_W, ldw, d_sigma);
+}
+
+int mf_solve_assignment(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
+                        int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res)
+{
+    if (!d_row2col || !d_u || !d_v || !h_res) return MF_ERR_ARG;
+    int rc = check_matrix(ctx, d_W, n, m, ldw);
+    if (rc != MF_OK) return rc;
+    MF_HIP(hipSetDevice(ctx->device));
+    clear_timings(ctx);
+    memset(h_res, 0, sizeof(*h_res));
+    rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res);
+    h_res->status = rc;
+    return rc;
+}
+
+int mf_check_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
+                         const int32_t *d_row2col, const int64_t *d_u, const int64_t *d_v,
+                         int64_t K, mf_result *h_res)
+{
+    if (!d_row2col || !d_u || !d_v || !h_res || K < 1) return MF_ERR_ARG;
+    int rc = check_matrix(ctx, d_W, n, m, ldw);
+    if (rc != MF_OK) return rc;
+    MF_HIP(hipSetDevice(ctx->device));
+    clear_timings(ctx);
+    memset(h_res, 0, sizeof(*h_res));
+    MF_HIP(hipEventRecord(ctx->ev[5], ctx->stream));
+    rc = mf_run_certificate(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, K, h_res);
+    if (rc == MF_OK) {
+        MF_HIP(hipEventRecord(ctx->ev[6], ctx->stream));
+        MF_HIP(hipStreamSynchronize(ctx->stream));
+        MF_HIP(hipEventElapsedTime(&ctx->timings[T_CERT], ctx->ev[5], ctx->ev[6]));
+        h_res->ms_certify = ctx->timings[T_CERT];
+    }
+    h_res->status = rc;
+    return rc;
+}
+
+int mf_schedule_round(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, int n,
+                      const float *d_off, int m, int32_t *d_W, int64_t ldw,
+                      int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res)
+{
+    if (!d_on || !d_off || !d_row2col || !d_u || !d_v || !h_res) return MF_ERR_ARG;
+    int rc = check_matrix(ctx, d_W, n, m, ldw);
+    if (rc != MF_OK) return rc;
+    rc = check_predictor(pred);
+    if (rc != MF_OK) return rc;
+    MF_HIP(hipSetDevice(ctx->device));
+    clear_timings(ctx);
+    memset(h_res, 0, sizeof(*h_res));
+    rc = mf_launch_score(ctx, pred, d_on, n, d_off, m, d_W, ldw, nullptr);
+    if (rc == MF_OK) rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res);
+    if (rc == MF_OK || rc == MF_ERR_CERT) {
+        int rt = finish_score_timing(ctx);
+        if (rt != MF_OK) rc = rt;
+    }
+    h_res->status = rc;
+    return rc;
+}
+
+int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
+{
+    if (!ctx || !name) return MF_ERR_ARG;
+    if (!strcmp(name, "theta")) { if (value < 2 || value > 1024) return MF_ERR_ARG; ctx->theta = value; return MF_OK; }
+    if (!strcmp(name, "max_rounds")) { if (value < 1) return MF_ERR_ARG; ctx->max_rounds = value; return MF_OK; }
+    return MF_ERR_ARG;
+}
+
+int mf_last_timings(mf_ctx *ctx, float what[16])
+{
+    if (!ctx || !what) return MF_ERR_ARG;
+    if (ctx->score_pending) {           // a bare mf_score_pairs does not wait for its events
+        int rc = finish_score_timing(ctx);
+        if (rc != MF_OK) return rc;
+    }
+    memcpy(what, ctx->timings, sizeof(float) * 16);
+    return MF_OK;
+}
+
+const char *mf_strerror(int code)
+{
+    switch (code) {
+    case MF_OK: return "ok";
+    case MF_ERR_ARG: return "bad argument (null pointer, non-positive size, pitch or alignment)";
+    case MF_ERR_SHAPE: return "shape not supported (n > m, or larger than the context)";
+    case MF_ERR_HIP: return "HIP runtime error";
+    case MF_ERR_NOT_CONVERGED: return "round limit reached before the auction finished";
+    case MF_ERR_CERT: return "optimality certificate did not verify";
+    case MF_ERR_RANGE: return "weights too large for exact arithmetic at this size";
+    default: return "unknown error";
+    }
+}
+
+const char *mf_last_hip_error(mf_ctx *ctx)
+{
+    return ctx ? hipGetErrorString(ctx->hip_error) : "no context";
+}
+
+}  // extern "C"

@@ -1,0 +1,83 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "muxmatch.h"
+
+#define MF_HIP(call)                                                            \
+    do {                                                                        \
+        hipError_t e_ = (call);                                                 \
+        if (e_ != hipSuccess) {                                                 \
+            ctx->hip_error = e_;                                                \
+            return MF_ERR_HIP;                                                  \
+        }                                                                       \
+    } while (0)
+
+// A dual value and the index of the workload holding the other end share one
+// 64-bit word so that a single atomicMax both raises the dual and records
+// who raised it: word = dual << MF_ID_BITS | (id + 1), id + 1 == 0 meaning "nobody".
+#define MF_ID_BITS 20
+#define MF_ID_MASK ((1ull << MF_ID_BITS) - 1ull)
+#define MF_MAX_DIM ((1 << MF_ID_BITS) - 2)
+#define MF_MAX_DUAL (1ll << 43)
+
+enum { T_PROJ = 0, T_PAIR, T_BID_BULK, T_BID_BULK_LAUNCHES, T_TRANSPOSE, T_DUALS, T_CERT, T_SOLVE,
+       T_BID_BULK_BYTES, T_COUNT = 16 };
+
+struct mf_device_stats {            // lives in device memory, cleared per solve
+    unsigned long long rounds;
+    unsigned long long bids;
+    unsigned long long bytes;
+    int max_weight;
+    int pad;
+};
+
+struct mf_cert_out {                // lives in device memory, cleared per check
+    long long primal;
+    long long dual;
+    long long min_rc;
+    int matched;
+    int flags;                      // bit0 bad index/duplicate, bit1 infeasible pair, bit2 negative dual
+};
+
+struct mf_ctx {
+    int device;
+    hipStream_t stream;
+    int max_n, max_m;
+    hipError_t hip_error;
+    // scoring scratch
+    float *proj_on, *proj_off;      // [max_n][H], [max_m][H]
+    float *mem_on, *mem_off;        // [max_n], [max_m]
+    // solver scratch
+    int32_t *wt;                    // transposed weights [max_m][ldt]
+    double *price, *profit;         // [max_m+4], [max_n+4]: exact integers held in doubles
+    unsigned long long *colword, *roword;
+    int *row2col, *col2row;
+    int *tent_tgt;                  // [max(max_n,max_m)]
+    double *tent_keep;
+    int *list[2];
+    int *cnt;                       // [2]
+    int *colmark;                   // [max_m]
+    mf_device_stats *stats;
+    mf_cert_out *cert;
+    // pinned host mirrors
+    int *h_cnt;
+    mf_device_stats *h_stats;
+    mf_cert_out *h_cert;
+    // options
+    int64_t theta, max_rounds;
+    // timing
+    hipEvent_t ev[8];
+    float timings[T_COUNT];
+    bool score_pending;             // score events recorded but not yet read
+};
+
+// score.hip
+int mf_launch_score(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, int n,
+                    const float *d_off, int m, int32_t *d_W, int64_t ldw, float *d_sigma);
+// auction.hip
+int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
+                  int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
+int mf_run_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
+                       const int32_t *d_row2col, const int64_t *d_u, const int64_t *d_v,
+                       int64_t K, mf_result *h_res);

@@ -1,0 +1,199 @@
+// Edge weights for every online x offline pair (paper: Algorithm "Scheduling
+// algorithm", the loop that calls CalcNormTput and AddEdge; Section
+// "Matching-based scheduling" for the predictor's inputs and output).
+//
+// The predictor is an MLP 2F -> H -> H -> 1 over [online ; offline] features.
+// Its first layer is linear in the concatenation, so it splits exactly into a
+// per-online and a per-offline projection that are computed once per workload:
+//     W1 [x_u ; x_v] + b1 = (W1[:, :F] x_u + b1) + (W1[:, F:] x_v).
+// The pair kernel then only adds the two projections, applies ReLU, and runs
+// the H x H hidden layer on the matrix cores with pairs along the N axis of
+// the MFMA tile, so each lane ends up owning whole pairs and the output layer,
+// logistic, quantisation and memory-fit mask run in registers before one
+// coalesced int32 store.
+#include "internal.h"
+#include <math.h>
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+__global__ void project_kernel(const float *__restrict__ X, int rows, int F,
+                               const float *__restrict__ W1, int col_off,
+                               const float *__restrict__ bias, int H, float *__restrict__ P,
+                               int mem_feature, float *__restrict__ mem)
+{
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)rows * H) return;
+    int r = (int)(idx / H), k = (int)(idx % H);
+    const float *x = X + (size_t)r * F;
+    const float *w = W1 + (size_t)k * 2 * F + col_off;
+    float s = bias ? bias[k] : 0.0f;
+    for (int t = 0; t < F; ++t) s = fmaf(x[t], w[t], s);
+    P[idx] = s;
+    if (k == 0) mem[r] = x[mem_feature];
+}
+
+constexpr int PAIR_THREADS = 512;   // 8 wavefronts: two per SIMD share one LDS copy of W2
+constexpr int PAIR_WAVES = PAIR_THREADS / 64;
+constexpr int PAIR_COLS = PAIR_WAVES * 32;
+
+template <int H> struct PairShape {
+    static constexpr int ROWS = 64;                        // online rows per workgroup
+    static constexpr int KS = H / 2;                       // k-steps of the 32x32x2 tile
+    static constexpr int MB = H / 32;                      // 32-row blocks of the hidden layer
+    static constexpr size_t LDS_BYTES = sizeof(float) * ((size_t)H * H + (size_t)ROWS * H + 2 * H);
+};
+
+// One wavefront owns 32 offline columns (lane & 31) and walks down the online
+// rows of the tile.  v_mfma_f32_32x32x2_f32 computes D[32x32] += A[32x2] B[2x32]
+// with lane l supplying A[l%32][l/32] and B[l/32][l%32]; we let the two k
+// slots of step s be hidden features s and H/2 + s, so each half-wave streams
+// a contiguous half of the projections.  Accumulator register r of lane l is
+// D[8*(r/4) + 4*(l/32) + r%4][l%32].
+template <int H>
+__global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
+    const float *__restrict__ P_on, const float *__restrict__ P_off,
+    const float *__restrict__ W2, const float *__restrict__ b2, const float *__restrict__ W3,
+    const float *__restrict__ b3, const float *__restrict__ mem_on,
+    const float *__restrict__ mem_off, int n, int m, float scale, float mem_limit,
+    int32_t *__restrict__ W, int64_t ldw, float *__restrict__ sigma)
+{
+    using S = PairShape<H>;
+    constexpr int KS = S::KS, MB = S::MB, ROWS = S::ROWS, Q = KS / 4;
+    extern __shared__ float4 lds4[];
+    float4 *a_lds = lds4;                                  // [MB][Q][64] float4: MFMA A operand order
+    float *pon_lds = (float *)(lds4) + H * H;              // [ROWS][H]
+    float *b2_lds = pon_lds + ROWS * H;
+    float *w3_lds = b2_lds + H;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hh = lane >> 5, nn = lane & 31;
+    const int row0 = blockIdx.y * ROWS;
+    const int nrows = min(ROWS, n - row0);
+    const int j0 = (blockIdx.x * PAIR_WAVES + wave) * 32;
+
+    for (int idx = tid; idx < MB * Q * 64; idx += PAIR_THREADS) {
+        int ln = idx & 63, s4 = (idx >> 6) % Q, mb = idx / (64 * Q);
+        a_lds[idx] = *(const float4 *)(W2 + (size_t)(mb * 32 + (ln & 31)) * H + (ln >> 5) * KS + s4 * 4);
+    }
+    for (int idx = tid; idx < nrows * (H / 4); idx += PAIR_THREADS)
+        ((float4 *)pon_lds)[idx] = ((const float4 *)(P_on + (size_t)row0 * H))[idx];
+    if (tid < H) { b2_lds[tid] = b2[tid]; w3_lds[tid] = W3[tid]; }
+    __syncthreads();
+    if (j0 >= m) return;
+
+    const int j = j0 + nn;
+    const int jc = min(j, m - 1);
+    float poff[KS];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        float4 t = *(const float4 *)(P_off + (size_t)jc * H + hh * KS + q * 4);
+        poff[4 * q] = t.x; poff[4 * q + 1] = t.y; poff[4 * q + 2] = t.z; poff[4 * q + 3] = t.w;
+    }
+    const float moff = mem_off[jc];
+    const float bias3 = b3[0];
+
+    for (int r = 0; r < nrows; ++r) {
+        // W2 does not fit in registers next to the accumulators: keep its loads inside the row loop
+        asm volatile("" ::: "memory");
+        floatx16 acc[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float4 bv = *(const float4 *)(b2_lds + mb * 32 + 8 * g + 4 * hh);
+                acc[mb][4 * g] = bv.x; acc[mb][4 * g + 1] = bv.y;
+                acc[mb][4 * g + 2] = bv.z; acc[mb][4 * g + 3] = bv.w;
+            }
+        const float *pon = pon_lds + r * H + hh * KS;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            float4 pv = *(const float4 *)(pon + 4 * q);
+            float h1[4];
+            h1[0] = fmaxf(pv.x + poff[4 * q], 0.0f);
+            h1[1] = fmaxf(pv.y + poff[4 * q + 1], 0.0f);
+            h1[2] = fmaxf(pv.z + poff[4 * q + 2], 0.0f);
+            h1[3] = fmaxf(pv.w + poff[4 * q + 3], 0.0f);
+            float4 av[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) av[mb] = a_lds[(mb * Q + q) * 64 + lane];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].x, h1[0], acc[mb], 0, 0, 0);
+                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].y, h1[1], acc[mb], 0, 0, 0);
+                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].z, h1[2], acc[mb], 0, 0, 0);
+                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].w, h1[3], acc[mb], 0, 0, 0);
+            }
+        }
+        // output layer on this lane's 16*MB hidden units, then add the other half-wave's
+        float zp = 0.0f;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float4 wv = *(const float4 *)(w3_lds + mb * 32 + 8 * g + 4 * hh);
+                zp = fmaf(wv.x, fmaxf(acc[mb][4 * g], 0.0f), zp);
+                zp = fmaf(wv.y, fmaxf(acc[mb][4 * g + 1], 0.0f), zp);
+                zp = fmaf(wv.z, fmaxf(acc[mb][4 * g + 2], 0.0f), zp);
+                zp = fmaf(wv.w, fmaxf(acc[mb][4 * g + 3], 0.0f), zp);
+            }
+        const float z = zp + __shfl_xor(zp, 32) + bias3;
+        const float sg = 1.0f / (1.0f + expf(-z));
+        if (hh == 0 && j < m) {
+            const int i = row0 + r;
+            float q = rintf(sg * scale);
+            q = fminf(fmaxf(q, 0.0f), scale);
+            int32_t w = (int32_t)q;
+            const float memsum = mem_on[i] + moff;
+            if (memsum > mem_limit) w = MF_INFEASIBLE;
+            W[(size_t)i * ldw + j] = w;
+            if (sigma) sigma[(size_t)i * m + j] = sg;
+        }
+    }
+}
+
+template <int H>
+int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
+                float *d_sigma)
+{
+    using S = PairShape<H>;
+    static bool configured = false;
+    if (!configured) {
+        MF_HIP(hipFuncSetAttribute((const void *)pair_mlp_kernel<H>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS_BYTES));
+        configured = true;
+    }
+    dim3 grid((m + PAIR_COLS - 1) / PAIR_COLS, (n + S::ROWS - 1) / S::ROWS);
+    hipLaunchKernelGGL(pair_mlp_kernel<H>, grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
+                       ctx->proj_on, ctx->proj_off, p->d_W2, p->d_b2, p->d_W3, p->d_b3,
+                       ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma);
+    MF_HIP(hipGetLastError());
+    return MF_OK;
+}
+
+}  // namespace
+
+int mf_launch_score(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int n,
+                    const float *d_off, int m, int32_t *d_W, int64_t ldw, float *d_sigma)
+{
+    const int H = p->H, F = p->F;
+    MF_HIP(hipEventRecord(ctx->ev[0], ctx->stream));
+    {
+        long tot = (long)n * H;
+        hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
+                           d_on, n, F, p->d_W1, 0, p->d_b1, H, ctx->proj_on, p->mem_feature, ctx->mem_on);
+        tot = (long)m * H;
+        hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
+                           d_off, m, F, p->d_W1, F, (const float *)nullptr, H, ctx->proj_off,
+                           p->mem_feature, ctx->mem_off);
+        MF_HIP(hipGetLastError());
+    }
+    MF_HIP(hipEventRecord(ctx->ev[1], ctx->stream));
+    int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, d_W, ldw, d_sigma)
+                       : launch_pair<128>(ctx, p, n, m, d_W, ldw, d_sigma);
+    if (rc != MF_OK) return rc;
+    MF_HIP(hipEventRecord(ctx->ev[2], ctx->stream));
+    ctx->score_pending = true;
+    return MF_OK;
+}

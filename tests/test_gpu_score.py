@@ -1,0 +1,111 @@
+"""GPU parity: mf_score_pairs against the CPU checker, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from gpu_util import dev, dev_params, empty_matrix, weight_tolerance
+
+pytestmark = pytest.mark.gpu
+INF = synth.INFEASIBLE
+
+
+@pytest.fixture(scope="module")
+def mm():
+    import paper_2303_13803_amd as mm
+    return mm
+
+
+def _score_on_gpu(mm, ctx, r, scale=None, want_sigma=True):
+    n, m = r["n"], r["m"]
+    scale = r["cfg"].scale if scale is None else scale
+    params = dev_params(r["params"])
+    pred = ctx.predictor(params, scale)
+    x_on, x_off = dev(r["x_on"]), dev(r["x_off"])
+    W = empty_matrix(n, m)
+    sigma = torch.empty((n, m), dtype=torch.float32, device="cuda") if want_sigma else None
+    ctx.score_pairs(pred, x_on, x_off, W, sigma)
+    torch.cuda.synchronize()
+    Wh = W.cpu().numpy()
+    assert (Wh[:, m:] == -7).all()                     # pitch padding untouched
+    return Wh[:, :m], (sigma.cpu().numpy() if want_sigma else None)
+
+
+def _compare(orc, r, Wg, sg, scale=None):
+    scale = r["cfg"].scale if scale is None else scale
+    sig, W = orc.score_pairs(r["x_on"], r["x_off"], r["params"], scale)
+    assert ((Wg == INF) == (W == INF)).all(), "mask bits differ"
+    rel = np.abs(sg.astype(np.float64) - sig) / sig
+    assert rel.max() <= 1e-5, f"score relative error {rel.max():.3e}"
+    ok = W != INF
+    dw = np.abs(Wg[ok].astype(np.int64) - W[ok].astype(np.int64))
+    assert dw.max() <= weight_tolerance(scale), f"weight difference {dw.max()}"
+    # the GPU's own quantisation of its own score is exact
+    q = np.clip(np.rint(sg * np.float32(scale)), 0, scale).astype(np.int64)
+    assert (Wg[ok] == q[ok]).all()
+    return rel.max()
+
+
+@pytest.mark.parametrize("cfg,n,m", [("C1", None, None), ("C2", None, None), ("C1", 1, 1), ("C1", 3, 5),
+                                     ("C2", 130, 517), ("C3", 150, 700), ("C4", 97, 1031),
+                                     ("C5", 64, 300), ("C3", 65, 257)])
+def test_scores_match_checker(mm, orc, cfg, n, m):
+    r = synth.scheduling_round(cfg, 1, n=n, m=m)
+    ctx = mm.Context(r["n"], max(r["m"], r["n"]))
+    Wg, sg = _score_on_gpu(mm, ctx, r)
+    _compare(orc, r, Wg, sg)
+    ctx.close()
+
+
+def test_scores_other_seeds_and_scales(mm, orc):
+    ctx = mm.Context(300, 600)
+    for seed in (2, 3):
+        for scale in (255.0, float(2 ** 24)):
+            r = synth.scheduling_round("C3", seed, n=200, m=333)
+            Wg, sg = _score_on_gpu(mm, ctx, r, scale)
+            _compare(orc, r, Wg, sg, scale)
+    ctx.close()
+
+
+def test_closed_form_predictors(mm):
+    # zero network: every feasible weight is exactly S/2
+    F, H, S = 16, 64, float(2 ** 20)
+    zero = {"W1": np.zeros((H, 2 * F), np.float32), "b1": np.zeros(H, np.float32),
+            "W2": np.zeros((H, H), np.float32), "b2": np.zeros(H, np.float32),
+            "W3": np.zeros(H, np.float32), "b3": np.zeros(1, np.float32)}
+    x_on = synth.uniform_features(1, 0, 70, F); x_off = synth.uniform_features(1, 1, 90, F)
+    ctx = mm.Context(70, 90)
+    W = empty_matrix(70, 90)
+    ctx.score_pairs(ctx.predictor(dev_params(zero), S), dev(x_on), dev(x_off), W)
+    Wh = W.cpu().numpy()[:, :90]
+    masked = (x_on[:, 0][:, None] + x_off[:, 0][None, :]) > np.float32(1)
+    assert (Wh[masked] == INF).all() and (Wh[~masked] == 2 ** 19).all()
+    # identity network: z is the plain sum of all features of both workloads
+    H = F = 64
+    ident = {"W1": np.concatenate([np.eye(F), np.eye(F)], 1).astype(np.float32), "b1": np.zeros(H, np.float32),
+             "W2": np.eye(H, dtype=np.float32), "b2": np.zeros(H, np.float32),
+             "W3": np.ones(H, np.float32), "b3": np.zeros(1, np.float32)}
+    x_on = synth.uniform_features(2, 0, 40, F) * np.float32(0.05)
+    x_off = synth.uniform_features(2, 1, 50, F) * np.float32(0.05)
+    W = empty_matrix(40, 50); sg = torch.empty((40, 50), dtype=torch.float32, device="cuda")
+    ctx.score_pairs(ctx.predictor(dev_params(ident), S, mem_limit=4.0), dev(x_on), dev(x_off), W, sg)
+    z = x_on.astype(np.float64).sum(1)[:, None] + x_off.astype(np.float64).sum(1)[None, :]
+    np.testing.assert_allclose(sg.cpu().numpy(), 1 / (1 + np.exp(-z)), rtol=1e-5)
+    ctx.close()
+
+
+def test_argument_errors(mm):
+    ctx = mm.Context(8, 8)
+    r = synth.scheduling_round("C1", 1, n=8, m=8)
+    params = dev_params(r["params"])
+    x_on, x_off = dev(r["x_on"]), dev(r["x_off"])
+    W = empty_matrix(8, 8)
+    bad = ctx.predictor(params, 2.0 ** 20); bad.H = 48
+    with pytest.raises(mm.MuxmatchError) as e:
+        ctx.score_pairs(bad, x_on, x_off, W)
+    assert e.value.code == mm.ERR_ARG
+    big = synth.scheduling_round("C1", 1, n=9, m=9)
+    with pytest.raises(mm.MuxmatchError) as e:
+        ctx.score_pairs(ctx.predictor(params, 2.0 ** 20), dev(big["x_on"]), dev(big["x_off"]), empty_matrix(9, 9))
+    assert e.value.code == mm.ERR_SHAPE
+    ctx.close()
