@@ -51,6 +51,7 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=192)
     ap.add_argument("--cpu-block", type=int, default=1536)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--opt", action="append", default=[], help="solver option name=value (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: the scheduling round is a single-device kernel path "
@@ -68,6 +69,9 @@ def main():
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     ctx = mm.Context(n, m, device=0)
     params = {k: dev(v) for k, v in r["params"].items()}
+    for kv in args.opt:
+        name, value = kv.split("=")
+        ctx.set_option(name, int(value))
     pred = ctx.predictor(params, cfg.scale)
     x_on, x_off = dev(r["x_on"]), dev(r["x_off"])
     ld = (m + 3) // 4 * 4
@@ -115,7 +119,7 @@ def main():
         "stage_ms": {k: avg[k] for k in ("projections_ms", "pair_scoring_ms", "transpose_ms", "auction_ms",
                                          "duals_ms", "certificate_ms")},
         "auction": {"phases": res.phases, "rounds": res.rounds, "bids": res.bids,
-                    "bytes_scanned": res.bytes_scanned, "matched": res.matched,
+                    "bytes_scanned": res.bytes_scanned, "chain_bids": res.chain_bids, "chain_depth": res.chain_depth, "chain_retries": res.chain_retries, "matched": res.matched,
                     "primal": res.primal, "cert_ok": res.cert_ok},
         "roofline": {"bound": "mfma", "kernel": "pair_mlp_kernel", "achieved": achieved / 1e12,
                      "peak": MFMA_FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_FP32_PEAK,

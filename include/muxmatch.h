@@ -88,9 +88,12 @@ typedef struct {
     int64_t dual;               /* D: sum u + sum v (1/K weight units)                  */
     int64_t K;                  /* dual scale, K = n + 1                                */
     int64_t min_reduced_cost;   /* min over feasible (i,j) of u_i + v_j - K*W_ij        */
-    int64_t rounds;             /* bidding rounds run (forward + reverse)               */
-    int64_t bids;               /* row/column scans performed by bidding rounds         */
+    int64_t rounds;             /* bidding kernels run (forward + reverse)              */
+    int64_t bids;               /* bids evaluated: each scans one row or column         */
     int64_t bytes_scanned;      /* weight-matrix bytes those scans read                 */
+    int64_t chain_bids;         /* bids evaluated by the chain-following kernels        */
+    int64_t chain_depth;        /* longest per-workgroup bid sequence, summed over them */
+    int64_t chain_retries;      /* chain bids that lost and were redone                 */
     int32_t matched;            /* rows with a partner                                  */
     int32_t phases;             /* epsilon-scaling phases                               */
     int32_t cert_ok;            /* 1: matching valid, duals feasible, 0 <= D - K*P < K  */
@@ -155,7 +158,10 @@ int mf_schedule_round(mf_ctx *ctx, const mf_predictor *pred,
                       int32_t *d_W, int64_t ldw,
                       int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
 
-/* Solver knobs (defaults: theta = 8, max_rounds = 4,000,000). */
+/* Solver knobs: "theta" (epsilon divisor per phase, default 8), "max_rounds" (limit on
+ * evaluated bids, default 4,000,000,000), "tail_max" (bidder count at or below which one
+ * kernel follows the remaining eviction chains to their end, default 512), "chain_grid"
+ * (workgroups of that kernel, default 256). */
 int mf_set_option(mf_ctx *ctx, const char *name, int64_t value);
 
 /*

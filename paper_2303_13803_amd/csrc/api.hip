@@ -67,7 +67,9 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->max_n = max_n;
     ctx->max_m = max_m;
     ctx->theta = 8;
-    ctx->max_rounds = 4000000;
+    ctx->max_rounds = 4000000000ll;
+    ctx->tail_max = 512;
+    ctx->chain_grid = 256;
     const size_t nm = (size_t)max_m;                      // max_m >= max_n
     const size_t ldt = ((size_t)max_n + 3) & ~(size_t)3;
     hipError_t e = hipSuccess;
@@ -83,15 +85,11 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->roword, (size_t)max_n));
     TRY(dev_alloc(&ctx->row2col, (size_t)max_n));
     TRY(dev_alloc(&ctx->col2row, (size_t)max_m));
-    TRY(dev_alloc(&ctx->tent_tgt, nm));
-    TRY(dev_alloc(&ctx->tent_keep, nm));
     TRY(dev_alloc(&ctx->list[0], nm));
     TRY(dev_alloc(&ctx->list[1], nm));
-    TRY(dev_alloc(&ctx->cnt, 2));
     TRY(dev_alloc(&ctx->colmark, (size_t)max_m));
     TRY(dev_alloc(&ctx->stats, 1));
     TRY(dev_alloc(&ctx->cert, 1));
-    TRY(hipHostMalloc((void **)&ctx->h_cnt, 2 * sizeof(int)));
     TRY(hipHostMalloc((void **)&ctx->h_stats, sizeof(mf_device_stats)));
     TRY(hipHostMalloc((void **)&ctx->h_cert, sizeof(mf_cert_out)));
     for (int i = 0; i < 8; ++i) TRY(hipEventCreate(&ctx->ev[i]));
@@ -111,11 +109,9 @@ int mf_destroy(mf_ctx *ctx)
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->wt, ctx->price,
-                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->tent_tgt,
-                   ctx->tent_keep, ctx->list[0], ctx->list[1], ctx->cnt, ctx->colmark, ctx->stats,
+                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
-    if (ctx->h_cnt) (void)hipHostFree(ctx->h_cnt);
     if (ctx->h_stats) (void)hipHostFree(ctx->h_stats);
     if (ctx->h_cert) (void)hipHostFree(ctx->h_cert);
     for (int i = 0; i < 8; ++i) if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
@@ -197,6 +193,8 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
 {
     if (!ctx || !name) return MF_ERR_ARG;
     if (!strcmp(name, "theta")) { if (value < 2 || value > 1024) return MF_ERR_ARG; ctx->theta = value; return MF_OK; }
+    if (!strcmp(name, "tail_max")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->tail_max = (int)value; return MF_OK; }
+    if (!strcmp(name, "chain_grid")) { if (value < 1 || value > 4096) return MF_ERR_ARG; ctx->chain_grid = (int)value; return MF_OK; }
     if (!strcmp(name, "max_rounds")) { if (value < 1) return MF_ERR_ARG; ctx->max_rounds = value; return MF_OK; }
     return MF_ERR_ARG;
 }

@@ -43,167 +43,306 @@ __device__ inline double word_dual(unsigned long long w) { return (double)(long 
 __device__ inline int word_id(unsigned long long w) { return (int)(w & MF_ID_MASK) - 1; }
 
 struct Top2 {
-    double b1, b2;
-    int idx;
+    double b1, b2;      // best and second-best value
+    int idx, w;         // position and weight of the best
 };
 
-__device__ inline void top2_push(Top2 &t, double val, int j)
+__device__ inline void top2_push(Top2 &t, double val, int j, int w)
 {
+    const bool gt = val > t.b1;
     t.b2 = fmax(t.b2, fmin(val, t.b1));
-    t.idx = val > t.b1 ? j : t.idx;
+    t.idx = gt ? j : t.idx;
+    t.w = gt ? w : t.w;
     t.b1 = fmax(t.b1, val);
 }
 
-__device__ inline void top2_merge(Top2 &t, double ob1, double ob2, int oidx)
+__device__ inline void top2_merge(Top2 &t, const Top2 &o)
 {
-    const double nb2 = fmax(fmax(t.b2, ob2), fmin(t.b1, ob1));
-    const bool take = (ob1 > t.b1) || (ob1 == t.b1 && oidx < t.idx);
-    t.idx = take ? oidx : t.idx;
-    t.b1 = fmax(t.b1, ob1);
+    const double nb2 = fmax(fmax(t.b2, o.b2), fmin(t.b1, o.b1));
+    const bool take = (o.b1 > t.b1) || (o.b1 == t.b1 && o.idx < t.idx);
+    t.idx = take ? o.idx : t.idx;
+    t.w = take ? o.w : t.w;
+    t.b1 = fmax(t.b1, o.b1);
     t.b2 = nb2;
 }
 
-// Scans line `A[0..len)` against `dual[0..len)` and leaves, in every thread of
-// the block, the best and second-best value of K*w - dual and the smallest
-// index attaining the best.  `A` is 16-byte aligned and padded to a multiple
-// of four entries; `dual` likewise.
-__device__ inline Top2 scan_line(const int32_t *__restrict__ A, const double *__restrict__ dual,
-                                 int len, double Kd, Top2 *red)
+__device__ inline Top2 top2_shuffle_xor(const Top2 &t, int off)
 {
-    Top2 t{NEG_HUGE, NEG_HUGE, 0x7fffffff};
-    for (int j = threadIdx.x * 4; j < len; j += BID_THREADS * 4) {
-        const int4 w = *(const int4 *)(A + j);
-        const double2 p01 = *(const double2 *)(dual + j);
-        const double2 p23 = *(const double2 *)(dual + j + 2);
-        double v0 = fma(Kd, (double)w.x, -p01.x);
-        double v1 = fma(Kd, (double)w.y, -p01.y);
-        double v2 = fma(Kd, (double)w.z, -p23.x);
-        double v3 = fma(Kd, (double)w.w, -p23.y);
-        if (j + 3 >= len) {
-            if (j + 1 >= len) v1 = NEG_HUGE;
-            if (j + 2 >= len) v2 = NEG_HUGE;
-            v3 = NEG_HUGE;
-        }
-        top2_push(t, v0, j);
-        top2_push(t, v1, j + 1);
-        top2_push(t, v2, j + 2);
-        top2_push(t, v3, j + 3);
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const double ob1 = __shfl_xor(t.b1, off);
-        const double ob2 = __shfl_xor(t.b2, off);
-        const int oidx = __shfl_xor(t.idx, off);
-        top2_merge(t, ob1, ob2, oidx);
-    }
-    const int wave = threadIdx.x >> 6;
-    __syncthreads();                       // protect `red` from the previous line
-    if ((threadIdx.x & 63) == 0) red[wave] = t;
-    __syncthreads();
-    Top2 r = red[0];
-#pragma unroll
-    for (int wv = 1; wv < BID_THREADS / 64; ++wv) top2_merge(r, red[wv].b1, red[wv].b2, red[wv].idx);
-    return r;
+    Top2 o;
+    o.b1 = __shfl_xor(t.b1, off);
+    o.b2 = __shfl_xor(t.b2, off);
+    o.idx = __shfl_xor(t.idx, off);
+    o.w = __shfl_xor(t.w, off);
+    return o;
 }
 
-// One bidding round for the side whose members are listed in `list`.
-//   A          that side's lines of the weight matrix (W for rows, W^T for columns)
-//   other_dual duals of the opposite side (read), otherword their packed (dual, holder)
-//   own_*      this side's dual, packed word and partner index
-// A bidder whose best value is at most eps rests with dual 0.  Otherwise it
-// offers the opposite workload the highest dual at which that workload is
-// still within eps of the bidder's best alternative.
-__global__ __launch_bounds__(BID_THREADS) void bid_kernel(
-    const int32_t *__restrict__ A, int64_t pitch, int len, const double *__restrict__ other_dual,
-    unsigned long long *__restrict__ otherword, double *__restrict__ own_dual,
-    unsigned long long *__restrict__ ownword, int *__restrict__ own2other,
-    int *__restrict__ tent_tgt, double *__restrict__ tent_keep, const int *__restrict__ list,
-    int *__restrict__ cnt, int cur, double eps, double Kd, mf_device_stats *stats)
+struct SideArgs {
+    const int32_t *A;                   // the bidding side's lines (W for rows, W^T for columns)
+    long long pitch;
+    int len;
+    double *other_dual;                 // opposite duals as doubles, raised with atomicMax on the bits
+    unsigned long long *otherword;      // opposite packed (dual, holder): the authoritative copy
+    double eps, Kd;
+};
+
+// Loads that must observe values other wavefronts produced during this kernel:
+// they bypass the caches that atomics performed at the memory side do not update.
+__device__ inline double load_fresh(const double *p)
 {
-    __shared__ Top2 red[BID_THREADS / 64];
-    const int count = cnt[cur];
+    return __longlong_as_double((long long)__hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// Scans line A[0..len) against dual[0..len): best and second-best value of
+// K*w - dual, the smallest index attaining the best and its weight.  Every
+// thread of the NT-thread block must call it; the result is valid in the
+// first wavefront (threads 0..63).  A is 16-byte aligned and padded to a
+// multiple of four entries, dual likewise.  `fresh` re-reads the duals past
+// the caches (block-uniform).
+template <int NT>
+__device__ inline Top2 block_scan(const int32_t *__restrict__ A, const double *__restrict__ dual,
+                                  int len, double Kd, bool fresh, Top2 *red)
+{
+    constexpr int UN = 4;               // independent load batches in flight per thread
+    Top2 t{NEG_HUGE, NEG_HUGE, 0x7fffffff, 0};
+    for (int j0 = threadIdx.x * 4; j0 < len; j0 += NT * 4 * UN) {
+        int4 w[UN];
+        double p[UN][4];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int j = j0 + u * NT * 4;
+            if (j < len) {
+                w[u] = *(const int4 *)(A + j);
+                if (fresh) {
+                    p[u][0] = load_fresh(dual + j); p[u][1] = load_fresh(dual + j + 1);
+                    p[u][2] = load_fresh(dual + j + 2); p[u][3] = load_fresh(dual + j + 3);
+                } else {
+                    const double2 p01 = *(const double2 *)(dual + j);
+                    const double2 p23 = *(const double2 *)(dual + j + 2);
+                    p[u][0] = p01.x; p[u][1] = p01.y; p[u][2] = p23.x; p[u][3] = p23.y;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int j = j0 + u * NT * 4;
+            if (j < len) {
+                double v0 = fma(Kd, (double)w[u].x, -p[u][0]);
+                double v1 = fma(Kd, (double)w[u].y, -p[u][1]);
+                double v2 = fma(Kd, (double)w[u].z, -p[u][2]);
+                double v3 = fma(Kd, (double)w[u].w, -p[u][3]);
+                if (j + 3 >= len) {
+                    if (j + 1 >= len) v1 = NEG_HUGE;
+                    if (j + 2 >= len) v2 = NEG_HUGE;
+                    v3 = NEG_HUGE;
+                }
+                top2_push(t, v0, j, w[u].x);
+                top2_push(t, v1, j + 1, w[u].y);
+                top2_push(t, v2, j + 2, w[u].z);
+                top2_push(t, v3, j + 3, w[u].w);
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) top2_merge(t, top2_shuffle_xor(t, off));
+    if (NT == 64) return t;
+    __syncthreads();                       // protect `red` from the previous line
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        t = red[threadIdx.x < NT / 64 ? threadIdx.x : 0];
+#pragma unroll
+        for (int off = NT / 128; off >= 1; off >>= 1) top2_merge(t, top2_shuffle_xor(t, off));
+    }
+    return t;
+}
+
+// One thread: bidder b has seen best value t.b1 at column/row t.idx and
+// second-best t.b2.  A bidder whose best value is at most eps rests with dual
+// 0.  (A bidder's own dual is implied by what it holds - K*w minus the dual it
+// offered, or 0 when it holds nothing - and is written out once the run is
+// over; nothing reads it while bids are flying.)  Otherwise it offers the opposite workload the highest dual at which that
+// workload is still within eps of the bidder's best alternative; the offer is
+// an atomicMax on the packed (dual, holder) word, so the highest offer wins
+// whatever the order.  The offer is formed from the weight itself, not from the
+// dual the scan happened to read, which may have moved since.
+// Returns the workload that has to bid next because of this bid (the bidder
+// itself if it was outbid in the meantime, the previous holder if it won), or -1.
+__device__ inline int decide_and_bid(const SideArgs &s, int b, const Top2 &t)
+{
+    if (t.b1 <= s.eps) return -1;
+    const double keep = fmax(t.b2 - s.eps, 0.0);
+    const double offer = s.Kd * (double)t.w - keep;
+    const unsigned long long mine = pack_word(offer, b + 1);
+    const unsigned long long old = atomicMax(&s.otherword[t.idx], mine);
+    unsigned long long *dual_bits = (unsigned long long *)&s.other_dual[t.idx];
+    if (old < mine) {
+        atomicMax(dual_bits, (unsigned long long)__double_as_longlong(offer));
+        return word_id(old);
+    }
+    atomicMax(dual_bits, (unsigned long long)__double_as_longlong(word_dual(old)));
+    return b;
+}
+
+// One round for many bidders: a workgroup per bidder, bids taking effect at
+// once.  Later bidders of the same round may already see them (or a slightly
+// older dual): the auction tolerates both because duals only move one way and a
+// bid computed from an outdated dual simply fails to win.  The counters form a
+// ring: round r reads cnt[r], fills cnt[r+1] and clears cnt[r+2].
+template <int NT>
+__global__ __launch_bounds__(NT) void round_kernel(SideArgs s, const int *__restrict__ list,
+                                                   int *__restrict__ next, mf_device_stats *stats,
+                                                   int ring)
+{
+    __shared__ Top2 red[NT / 64];
+    const int count = stats->cnt[ring & 3];
+    int *ncnt = &stats->cnt[(ring + 1) & 3];
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        cnt[cur ^ 1] = 0;                  // the list the settle step of this round will fill
+        stats->cnt[(ring + 2) & 3] = 0;
+        stats->head = 0;
         if (count > 0) {
             stats->rounds += 1ull;
             stats->bids += (unsigned long long)count;
-            stats->bytes += (unsigned long long)count * (unsigned long long)len * 4ull;
+            stats->bytes += (unsigned long long)count * (unsigned long long)s.len * 4ull;
         }
     }
     for (int item = blockIdx.x; item < count; item += gridDim.x) {
         const int b = list[item];
-        const Top2 t = scan_line(A + (size_t)b * pitch, other_dual, len, Kd, red);
+        const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch, s.other_dual, s.len, s.Kd, false, red);
         if (threadIdx.x == 0) {
-            if (t.b1 <= eps) {
-                own_dual[b] = 0.0;
-                ownword[b] = 0ull;
-                own2other[b] = -1;
-                tent_tgt[b] = -1;
-            } else {
-                const double keep = fmax(t.b2 - eps, 0.0);
-                const double offer = t.b1 + other_dual[t.idx] - keep;    // K*w - keep
-                atomicMax(&otherword[t.idx], pack_word(offer, b + 1));
-                tent_tgt[b] = t.idx;
-                tent_keep[b] = keep;
-            }
+            const int again = decide_and_bid(s, b, t);
+            if (again >= 0) next[atomicAdd(ncnt, 1)] = again;
         }
     }
 }
 
-// Resolves a bidding round: the holder recorded in the target's word won.
-__global__ void settle_kernel(const unsigned long long *__restrict__ otherword,
-                              double *__restrict__ other_dual, int *__restrict__ other2own,
-                              double *__restrict__ own_dual, unsigned long long *__restrict__ ownword,
-                              int *__restrict__ own2other, const int *__restrict__ tent_tgt,
-                              const double *__restrict__ tent_keep, const int *__restrict__ list,
-                              int *__restrict__ next, int *__restrict__ cnt, int cur)
+// The tail of a run.  When few bidders are left, rounds are bound by launch
+// latency and the work is a handful of chains: a bid evicts a holder, who bids
+// next, and so on.  Each workgroup takes a pending bidder and then follows its
+// chain - after every bid it goes on with whoever has to bid because of it -
+// so no workgroup creates work for another, none waits for another, and each
+// stops as soon as the list is used up.
+constexpr int CHAIN_THREADS = 1024;
+
+__global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const int *__restrict__ list,
+                                                              int *__restrict__ out_list,
+                                                              mf_device_stats *stats, int ring,
+                                                              long long step_cap)
 {
-    const int count = cnt[cur];
-    for (int item = blockIdx.x * blockDim.x + threadIdx.x; item < count; item += gridDim.x * blockDim.x) {
-        const int b = list[item];
-        const int tgt = tent_tgt[b];
-        if (tgt < 0) continue;                                   // resting
-        const unsigned long long word = otherword[tgt];
-        if (word_id(word) == b) {
-            const int old = other2own[tgt];
-            if (old >= 0) {
-                own2other[old] = -1;
-                const double d = own_dual[old];
-                ownword[old] = pack_word(d, 0);
-                if (d > 0.0) next[atomicAdd(&cnt[cur ^ 1], 1)] = old;
+    __shared__ Top2 red[CHAIN_THREADS / 64];
+    __shared__ int s_next;
+    const int count = stats->cnt[ring & 3];
+    unsigned long long steps = 0, retries = 0;
+    for (;;) {
+        __syncthreads();
+        if (threadIdx.x == 0) s_next = atomicAdd(&stats->head, 1);
+        __syncthreads();
+        const int item = s_next;
+        if (item >= count) break;
+        int b = list[item];
+        bool fresh = false;                 // re-read the duals past the caches after a bid that lost
+        while (b >= 0) {
+            if ((long long)steps >= step_cap) {                     // hand the bidder back to the host loop
+                if (threadIdx.x == 0) out_list[atomicAdd(&stats->cnt[(ring + 1) & 3], 1)] = b;
+                break;
             }
-            other2own[tgt] = b;
-            own2other[b] = tgt;
-            other_dual[tgt] = word_dual(word);
-            own_dual[b] = tent_keep[b];
-            ownword[b] = pack_word(tent_keep[b], tgt + 1);
-        } else {
-            next[atomicAdd(&cnt[cur ^ 1], 1)] = b;
+            ++steps;
+            const Top2 t = block_scan<CHAIN_THREADS>(s.A + (size_t)b * s.pitch, s.other_dual, s.len, s.Kd,
+                                                      fresh, red);
+            if (threadIdx.x == 0) s_next = decide_and_bid(s, b, t);
+            __syncthreads();
+            fresh = (s_next == b);
+            if (fresh && threadIdx.x == 0) ++retries;
+            b = s_next;
         }
     }
+    if (threadIdx.x == 0 && steps) {
+        atomicAdd(&stats->bids, steps);
+        atomicAdd(&stats->chain_bids, steps);
+        atomicAdd(&stats->bytes, steps * (unsigned long long)s.len * 4ull);
+        atomicMax(&stats->launch_max, steps);
+        if (retries) atomicAdd(&stats->chain_retries, retries);
+    }
+}
+
+__global__ void chain_begin_kernel(mf_device_stats *stats, int ring)
+{
+    stats->head = 0;
+    stats->cnt[(ring + 1) & 3] = 0;
+    stats->cnt[(ring + 2) & 3] = 0;
+    stats->rounds += 1ull;
+    stats->chain_depth += stats->launch_max;     // of the previous chain kernel
+    stats->launch_max = 0;
 }
 
 // Start of an epsilon phase: drop the assignment, keep the duals, all rows bid.
 __global__ void reset_kernel(int n, int m, const double *__restrict__ price,
-                             const double *__restrict__ profit, unsigned long long *colword,
-                             unsigned long long *roword, int *row2col, int *col2row, int *list,
-                             int *cnt)
+                             unsigned long long *colword, int *row2col, int *col2row, int *list,
+                             mf_device_stats *stats)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) { row2col[i] = -1; roword[i] = pack_word(profit[i], 0); list[i] = i; }
+    if (i < n) { row2col[i] = -1; list[i] = i; }
     if (i < m) { col2row[i] = -1; colword[i] = pack_word(price[i], 0); }
-    if (i == 0) { cnt[0] = n; cnt[1] = 0; }
+    if (i == 0) { stats->cnt[0] = n; stats->cnt[1] = 0; stats->cnt[2] = 0; stats->cnt[3] = 0; }
 }
 
-// After the forward rounds: unassigned columns that still carry a price must bid.
-__global__ void reverse_list_kernel(int m, const double *__restrict__ price,
-                                    const int *__restrict__ col2row, int *list, int *cnt)
+// After the forward rounds the price words name every column's holder, and a
+// row's profit is whatever its column leaves it (0 for a row that rests).
+__global__ void forward_done_rows_kernel(int n, double *__restrict__ profit,
+                                         unsigned long long *roword, int *row2col)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { row2col[i] = -1; profit[i] = 0.0; roword[i] = 0ull; }
+}
+
+__global__ void forward_done_cols_kernel(int m, const int32_t *__restrict__ W, int64_t ldw, double Kd,
+                                         const unsigned long long *__restrict__ colword,
+                                         const double *__restrict__ price, double *__restrict__ profit,
+                                         unsigned long long *roword, int *row2col, int *col2row,
+                                         int *list, mf_device_stats *stats)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j < m && col2row[j] < 0 && price[j] > 0.0) list[atomicAdd(&cnt[0], 1)] = j;
+    if (j >= m) return;
+    const unsigned long long word = colword[j];
+    const int r = word_id(word);
+    col2row[j] = r;
+    if (r >= 0) {
+        const double pi = Kd * (double)W[(size_t)r * ldw + j] - word_dual(word);
+        row2col[r] = j;
+        profit[r] = pi;
+        roword[r] = pack_word(pi, j + 1);
+    } else if (price[j] > 0.0) {
+        list[atomicAdd(&stats->cnt[0], 1)] = j;    // an unassigned column that still carries a price must bid
+    }
 }
 
-__global__ void clear_counts_kernel(int *cnt) { cnt[0] = 0; cnt[1] = 0; }
+// After the reverse rounds the profit words name every row's holder; a column's
+// price is whatever its row leaves it (0 for a column that rests).
+__global__ void reverse_done_cols_kernel(int m, double *__restrict__ price, int *col2row)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < m) { col2row[j] = -1; price[j] = 0.0; }
+}
+
+__global__ void reverse_done_rows_kernel(int n, const int32_t *__restrict__ W, int64_t ldw, double Kd,
+                                         const unsigned long long *__restrict__ roword,
+                                         double *__restrict__ price, int *row2col, int *col2row)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const unsigned long long word = roword[i];
+    const int c = word_id(word);
+    row2col[i] = c;
+    if (c >= 0) {
+        col2row[c] = i;
+        price[c] = Kd * (double)W[(size_t)i * ldw + c] - word_dual(word);
+    }
+}
+
+__global__ void clear_counts_kernel(mf_device_stats *stats)
+{
+    stats->cnt[0] = 0; stats->cnt[1] = 0; stats->cnt[2] = 0; stats->cnt[3] = 0;
+}
 
 // W^T (for the reverse rounds' coalesced column scans) and the largest weight.
 __global__ void transpose_kernel(const int32_t *__restrict__ W, int n, int m, int64_t ldw,
@@ -238,7 +377,7 @@ __global__ __launch_bounds__(BID_THREADS) void duals_kernel(
 {
     __shared__ Top2 red[BID_THREADS / 64];
     for (int i = blockIdx.x; i < n; i += gridDim.x) {
-        const Top2 t = scan_line(W + (size_t)i * ldw, price, m, Kd, red);
+        const Top2 t = block_scan<BID_THREADS>(W + (size_t)i * ldw, price, m, Kd, false, red);
         if (threadIdx.x == 0) {
             u[i] = (int64_t)fmax(t.b1, 0.0);
             out_row2col[i] = row2col[i];
@@ -332,55 +471,52 @@ __global__ void init_solver_kernel(int n, int m, double *price, double *profit, 
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n + 4) profit[i] = 0.0;
     if (i < m + 4) price[i] = 0.0;
-    if (i == 0) { stats->rounds = 0; stats->bids = 0; stats->bytes = 0; stats->max_weight = 0; }
+    if (i == 0) {
+        stats->rounds = 0; stats->bids = 0; stats->bytes = 0; stats->head = 0;
+        stats->chain_bids = 0; stats->chain_depth = 0; stats->launch_max = 0; stats->chain_retries = 0; stats->max_weight = 0;
+        stats->cnt[0] = 0; stats->cnt[1] = 0; stats->cnt[2] = 0; stats->cnt[3] = 0;
+    }
 }
 
-struct Side {
-    const int32_t *A;
-    int64_t pitch;
-    int len;
-    double *own_dual, *other_dual;
-    unsigned long long *ownword, *otherword;
-    int *own2other, *other2own;
-};
-
-// Runs bidding rounds for one side until nobody is left to bid.  `count` is
-// the number of bidders in list[0].  Returns MF_OK or an error.
-int run_side(mf_ctx *ctx, const Side &s, int count, double eps, double Kd, int64_t *rounds_left,
-             bool time_first)
+// Runs one side until nobody is left to bid.  list[0] / cnt[0] hold the first
+// bidders (`count` of them).  Returns MF_OK or an error.
+int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
 {
-    int cur = 0;
+    int ring = 0;
     while (count > 0) {
-        const int batch = count > 2048 ? 1 : (count > 128 ? 4 : 16);
-        if (*rounds_left < batch) return MF_ERR_NOT_CONVERGED;
-        *rounds_left -= batch;
-        const int grid = count < MAX_GRID ? count : MAX_GRID;
-        const int sgrid = (count + 255) / 256 < 64 ? (count + 255) / 256 : 64;
-        for (int r = 0; r < batch; ++r) {
-            if (time_first && r == 0) MF_HIP(hipEventRecord(ctx->ev[6], ctx->stream));
-            hipLaunchKernelGGL(bid_kernel, dim3(grid), dim3(BID_THREADS), 0, ctx->stream, s.A, s.pitch,
-                               s.len, s.other_dual, s.otherword, s.own_dual, s.ownword, s.own2other,
-                               ctx->tent_tgt, ctx->tent_keep, ctx->list[cur], ctx->cnt, cur, eps, Kd,
-                               ctx->stats);
-            if (time_first && r == 0) MF_HIP(hipEventRecord(ctx->ev[7], ctx->stream));
-            hipLaunchKernelGGL(settle_kernel, dim3(sgrid), dim3(256), 0, ctx->stream, s.otherword,
-                               s.other_dual, s.other2own, s.own_dual, s.ownword, s.own2other,
-                               ctx->tent_tgt, ctx->tent_keep, ctx->list[cur], ctx->list[cur ^ 1],
-                               ctx->cnt, cur);
-            cur ^= 1;
+        bool timed = false;
+        const long long left = ctx->max_rounds - (long long)ctx->h_stats->bids;
+        if (left <= 0) return MF_ERR_NOT_CONVERGED;
+        if (count > ctx->tail_max) {
+            const int batch = count > 4096 ? 1 : 3;
+            const int grid = count < MAX_GRID ? count : MAX_GRID;
+            for (int r = 0; r < batch; ++r) {
+                if (time_first && r == 0) { MF_HIP(hipEventRecord(ctx->ev[6], ctx->stream)); timed = true; }
+                hipLaunchKernelGGL(round_kernel<BID_THREADS>, dim3(grid), dim3(BID_THREADS), 0, ctx->stream,
+                                   s, ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, ring);
+                if (time_first && r == 0) MF_HIP(hipEventRecord(ctx->ev[7], ctx->stream));
+                ++ring;
+            }
+        } else {
+            const int grid = count < ctx->chain_grid ? count : ctx->chain_grid;
+            hipLaunchKernelGGL(chain_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats, ring);
+            hipLaunchKernelGGL(chain_kernel, dim3(grid), dim3(CHAIN_THREADS), 0, ctx->stream, s,
+                               ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, ring,
+                               left / grid + 1);
+            ++ring;
         }
         MF_HIP(hipGetLastError());
-        MF_HIP(hipMemcpyAsync(ctx->h_cnt, ctx->cnt, 2 * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+        MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
         MF_HIP(hipStreamSynchronize(ctx->stream));
-        if (time_first) {
+        if (timed) {
             float ms = 0.0f;
             MF_HIP(hipEventElapsedTime(&ms, ctx->ev[6], ctx->ev[7]));
             ctx->timings[T_BID_BULK] += ms;
             ctx->timings[T_BID_BULK_LAUNCHES] += 1.0f;
             ctx->timings[T_BID_BULK_BYTES] += (float)((double)count * s.len * 4.0);
-            time_first = false;
         }
-        count = ctx->h_cnt[cur];
+        time_first = false;
+        count = ctx->h_stats->cnt[ring & 3];
     }
     return MF_OK;
 }
@@ -435,27 +571,39 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     const long long cmax = K * (long long)ctx->h_stats->max_weight;
     if (cmax >= MF_MAX_DUAL) return MF_ERR_RANGE;
 
-    const Side fwd{d_W, ldw, m, ctx->profit, ctx->price, ctx->roword, ctx->colword, ctx->row2col, ctx->col2row};
-    const Side rev{ctx->wt, ldt, n, ctx->price, ctx->profit, ctx->colword, ctx->roword, ctx->col2row, ctx->row2col};
+    SideArgs fwd{d_W, (long long)ldw, m, ctx->price, ctx->colword, 0.0, Kd};
+    SideArgs rev{ctx->wt, (long long)ldt, n, ctx->profit, ctx->roword, 0.0, Kd};
 
     long long eps = cmax / ctx->theta;
     if (eps < 1) eps = 1;
-    int64_t rounds_left = ctx->max_rounds;
     int phases = 0;
     for (;;) {
         ++phases;
+        fwd.eps = rev.eps = (double)eps;
         hipLaunchKernelGGL(reset_kernel, dim3((nm + 255) / 256), dim3(256), 0, ctx->stream, n, m, ctx->price,
-                           ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row,
-                           ctx->list[0], ctx->cnt);
-        int rc = run_side(ctx, fwd, n, (double)eps, Kd, &rounds_left, true);
+                           ctx->colword, ctx->row2col, ctx->col2row, ctx->list[0], ctx->stats);
+        int rc = run_side(ctx, fwd, n, true);
         if (rc != MF_OK) return rc;
-        hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->cnt);
-        hipLaunchKernelGGL(reverse_list_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, m,
-                           ctx->price, ctx->col2row, ctx->list[0], ctx->cnt);
-        MF_HIP(hipMemcpyAsync(ctx->h_cnt, ctx->cnt, 2 * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+        // who holds what after the forward rounds; unassigned priced columns go to list[0]
+        hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats);
+        hipLaunchKernelGGL(forward_done_rows_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, n,
+                           ctx->profit, ctx->roword, ctx->row2col);
+        hipLaunchKernelGGL(forward_done_cols_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, m,
+                           d_W, ldw, Kd, ctx->colword, ctx->price, ctx->profit, ctx->roword, ctx->row2col,
+                           ctx->col2row, ctx->list[0], ctx->stats);
+        MF_HIP(hipGetLastError());
+        MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
         MF_HIP(hipStreamSynchronize(ctx->stream));
-        rc = run_side(ctx, rev, ctx->h_cnt[0], (double)eps, Kd, &rounds_left, false);
-        if (rc != MF_OK) return rc;
+        const int rev_count = ctx->h_stats->cnt[0];
+        if (rev_count > 0) {
+            rc = run_side(ctx, rev, rev_count, false);
+            if (rc != MF_OK) return rc;
+            hipLaunchKernelGGL(reverse_done_cols_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, m,
+                               ctx->price, ctx->col2row);
+            hipLaunchKernelGGL(reverse_done_rows_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, n,
+                               d_W, ldw, Kd, ctx->roword, ctx->price, ctx->row2col, ctx->col2row);
+            MF_HIP(hipGetLastError());
+        }
         if (eps == 1) break;
         eps /= ctx->theta;
         if (eps < 1) eps = 1;
@@ -483,6 +631,9 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     h_res->rounds = (int64_t)ctx->h_stats->rounds;
     h_res->bids = (int64_t)ctx->h_stats->bids;
     h_res->bytes_scanned = (int64_t)ctx->h_stats->bytes;
+    h_res->chain_bids = (int64_t)ctx->h_stats->chain_bids;
+    h_res->chain_retries = (int64_t)ctx->h_stats->chain_retries;
+    h_res->chain_depth = (int64_t)(ctx->h_stats->chain_depth + ctx->h_stats->launch_max);
     h_res->phases = phases;
     h_res->ms_solve = ms_solve;
     h_res->ms_certify = ms_duals + ms_cert;

@@ -25,11 +25,16 @@ enum { T_PROJ = 0, T_PAIR, T_BID_BULK, T_BID_BULK_LAUNCHES, T_TRANSPOSE, T_DUALS
        T_BID_BULK_BYTES, T_COUNT = 16 };
 
 struct mf_device_stats {            // lives in device memory, cleared per solve
-    unsigned long long rounds;
-    unsigned long long bids;
-    unsigned long long bytes;
+    unsigned long long rounds;      // bidding rounds
+    unsigned long long bids;        // bids evaluated (one line scan each)
+    unsigned long long bytes;       // weight bytes those scans read
+    unsigned long long chain_bids;  // bids evaluated by chain kernels
+    unsigned long long chain_depth; // sum over chain kernels of the most bids any one workgroup evaluated
+    unsigned long long chain_retries; // chain bids that lost and were redone with uncached dual reads
+    unsigned long long launch_max;  // scratch: that maximum for the chain kernel in flight
     int max_weight;
-    int pad;
+    int cnt[4];                     // ring of bidder-list lengths: round r reads cnt[r & 3]
+    int head;                       // next unclaimed entry of the list a chain kernel works through
 };
 
 struct mf_cert_out {                // lives in device memory, cleared per check
@@ -53,15 +58,13 @@ struct mf_ctx {
     double *price, *profit;         // [max_m+4], [max_n+4]: exact integers held in doubles
     unsigned long long *colword, *roword;
     int *row2col, *col2row;
-    int *tent_tgt;                  // [max(max_n,max_m)]
-    double *tent_keep;
+    int tail_max;                   // bidder count at or below which chains are followed in one kernel
+    int chain_grid;                 // workgroups of that kernel
     int *list[2];
-    int *cnt;                       // [2]
     int *colmark;                   // [max_m]
     mf_device_stats *stats;
     mf_cert_out *cert;
     // pinned host mirrors
-    int *h_cnt;
     mf_device_stats *h_stats;
     mf_cert_out *h_cert;
     // options
