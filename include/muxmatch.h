@@ -161,7 +161,8 @@ int mf_schedule_round(mf_ctx *ctx, const mf_predictor *pred,
 /* Solver knobs: "theta" (epsilon divisor per phase, default 8), "max_rounds" (limit on
  * evaluated bids, default 4,000,000,000), "tail_max" (bidder count at or below which one
  * kernel follows the remaining eviction chains to their end, default 512), "chain_grid"
- * (workgroups of that kernel, default 256). */
+ * (workgroups of that kernel, default 256), "bulk_shape" (0..4: threads x lines per workgroup
+ * in rounds with many bidders: 256x1, 64x4 (default), 64x2, 128x4, 256x4). */
 int mf_set_option(mf_ctx *ctx, const char *name, int64_t value);
 
 /*

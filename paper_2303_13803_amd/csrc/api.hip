@@ -70,6 +70,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->max_rounds = 4000000000ll;
     ctx->tail_max = 512;
     ctx->chain_grid = 256;
+    ctx->bulk_shape = 1;
     const size_t nm = (size_t)max_m;                      // max_m >= max_n
     const size_t ldt = ((size_t)max_n + 3) & ~(size_t)3;
     hipError_t e = hipSuccess;
@@ -194,6 +195,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!ctx || !name) return MF_ERR_ARG;
     if (!strcmp(name, "theta")) { if (value < 2 || value > 1024) return MF_ERR_ARG; ctx->theta = value; return MF_OK; }
     if (!strcmp(name, "tail_max")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->tail_max = (int)value; return MF_OK; }
+    if (!strcmp(name, "bulk_shape")) { if (value < 0 || value > 4) return MF_ERR_ARG; ctx->bulk_shape = (int)value; return MF_OK; }
     if (!strcmp(name, "chain_grid")) { if (value < 1 || value > 4096) return MF_ERR_ARG; ctx->chain_grid = (int)value; return MF_OK; }
     if (!strcmp(name, "max_rounds")) { if (value < 1) return MF_ERR_ARG; ctx->max_rounds = value; return MF_OK; }
     return MF_ERR_ARG;

@@ -157,6 +157,84 @@ __device__ inline Top2 block_scan(const int32_t *__restrict__ A, const double *_
     return t;
 }
 
+// The same scan for RB lines at once: the opposite duals are loaded once per
+// four entries and applied to all RB lines, which cuts the on-chip traffic per
+// entry (duals are 8 bytes, weights 4) and keeps RB + 2 loads in flight per
+// thread.  Results are valid in the first wavefront.
+// Folds four consecutive entries (values v0..v3 at index j) into a running
+// top-2: a min/max network finds the group's best two, and only a group that
+// beats the running best pays for locating the entry.
+__device__ __forceinline__ void top2_push4(double &b1, double &b2, int &idx, int &wbest, double v0,
+                                           double v1, double v2, double v3, int j, const int4 &w)
+{
+    const double hi0 = fmax(v0, v1), lo0 = fmin(v0, v1);
+    const double hi1 = fmax(v2, v3), lo1 = fmin(v2, v3);
+    const double g1 = fmax(hi0, hi1);
+    const double g2 = fmax(fmin(hi0, hi1), fmax(lo0, lo1));
+    if (g1 > b1) {                                      // smallest index attaining the group's best
+        const bool a0 = v0 == g1, a1 = v1 == g1, a2 = v2 == g1;
+        idx = j + (a0 ? 0 : a1 ? 1 : a2 ? 2 : 3);
+        wbest = a0 ? w.x : a1 ? w.y : a2 ? w.z : w.w;
+    }
+    b2 = fmax(fmax(b2, g2), fmin(b1, g1));
+    b1 = fmax(b1, g1);
+}
+
+// Whole-line scan of RB lines at once: the opposite duals are loaded once per
+// four entries and applied to all RB lines, which cuts the on-chip traffic per
+// entry (duals are 8 bytes, weights 4) and keeps RB + 2 loads in flight per
+// thread.  On return red[r] holds line r's result (a barrier has been passed).
+template <int NT, int RB>
+__device__ __forceinline__ void block_scan_rows(const int32_t *const (&rows)[RB],
+                                                const double *__restrict__ dual, int len, double Kd,
+                                                Top2 *red)
+{
+    double b1[RB], b2[RB];
+    int idx[RB], wb[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) { b1[r] = NEG_HUGE; b2[r] = NEG_HUGE; idx[r] = 0x7fffffff; wb[r] = 0; }
+    const int full = len & ~3;                          // whole groups of four
+#pragma unroll 2
+    for (int j = threadIdx.x * 4; j < full; j += NT * 4) {
+        int4 w[RB];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) w[r] = *(const int4 *)(rows[r] + j);
+        const double2 p01 = *(const double2 *)(dual + j);
+        const double2 p23 = *(const double2 *)(dual + j + 2);
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+            top2_push4(b1[r], b2[r], idx[r], wb[r], fma(Kd, (double)w[r].x, -p01.x),
+                       fma(Kd, (double)w[r].y, -p01.y), fma(Kd, (double)w[r].z, -p23.x),
+                       fma(Kd, (double)w[r].w, -p23.y), j, w[r]);
+    }
+    if (full < len && (int)threadIdx.x == (full / 4) % NT) {   // the last, partial group
+        const double2 p01 = *(const double2 *)(dual + full);
+        const double2 p23 = *(const double2 *)(dual + full + 2);
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            const int4 w = *(const int4 *)(rows[r] + full);
+            top2_push4(b1[r], b2[r], idx[r], wb[r], fma(Kd, (double)w.x, -p01.x),
+                       full + 1 < len ? fma(Kd, (double)w.y, -p01.y) : NEG_HUGE,
+                       full + 2 < len ? fma(Kd, (double)w.z, -p23.x) : NEG_HUGE, NEG_HUGE, full, w);
+        }
+    }
+    __syncthreads();                       // protect `red` from its previous use
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        Top2 t{b1[r], b2[r], idx[r], wb[r]};
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) top2_merge(t, top2_shuffle_xor(t, off));
+        if ((threadIdx.x & 63) == 0) red[RB + r * (NT / 64) + (threadIdx.x >> 6)] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x < RB) {                // thread r folds the per-wave results of line r
+        Top2 t = red[RB + threadIdx.x * (NT / 64)];
+        for (int wv = 1; wv < NT / 64; ++wv) top2_merge(t, red[RB + threadIdx.x * (NT / 64) + wv]);
+        red[threadIdx.x] = t;
+    }
+    __syncthreads();
+}
+
 // One thread: bidder b has seen best value t.b1 at column/row t.idx and
 // second-best t.b2.  A bidder whose best value is at most eps rests with dual
 // 0.  (A bidder's own dual is implied by what it holds - K*w minus the dual it
@@ -189,12 +267,12 @@ __device__ inline int decide_and_bid(const SideArgs &s, int b, const Top2 &t)
 // older dual): the auction tolerates both because duals only move one way and a
 // bid computed from an outdated dual simply fails to win.  The counters form a
 // ring: round r reads cnt[r], fills cnt[r+1] and clears cnt[r+2].
-template <int NT>
+template <int NT, int RB>
 __global__ __launch_bounds__(NT) void round_kernel(SideArgs s, const int *__restrict__ list,
                                                    int *__restrict__ next, mf_device_stats *stats,
                                                    int ring)
 {
-    __shared__ Top2 red[NT / 64];
+    __shared__ Top2 red[RB + RB * (NT / 64)];
     const int count = stats->cnt[ring & 3];
     int *ncnt = &stats->cnt[(ring + 1) & 3];
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -206,12 +284,27 @@ __global__ __launch_bounds__(NT) void round_kernel(SideArgs s, const int *__rest
             stats->bytes += (unsigned long long)count * (unsigned long long)s.len * 4ull;
         }
     }
-    for (int item = blockIdx.x; item < count; item += gridDim.x) {
-        const int b = list[item];
-        const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch, s.other_dual, s.len, s.Kd, false, red);
-        if (threadIdx.x == 0) {
-            const int again = decide_and_bid(s, b, t);
-            if (again >= 0) next[atomicAdd(ncnt, 1)] = again;
+    for (int item = blockIdx.x * RB; item < count; item += gridDim.x * RB) {
+        int b[RB];
+        const int32_t *rows[RB];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            b[r] = list[min(item + r, count - 1)];          // a short last group repeats its last line
+            rows[r] = s.A + (size_t)b[r] * s.pitch;
+        }
+        block_scan_rows<NT, RB>(rows, s.other_dual, s.len, s.Kd, red);
+        if (threadIdx.x < 64) {                                      // first wavefront: one lane bids per line
+            int again = -1;
+            if (threadIdx.x < RB && item + (int)threadIdx.x < count)
+                again = decide_and_bid(s, list[item + threadIdx.x], red[threadIdx.x]);
+            // one counter update per workgroup: the list counter is a single hot address
+            const unsigned long long pushing = __ballot(again >= 0);
+            if (pushing) {
+                int base = 0;
+                if (threadIdx.x == 0) base = atomicAdd(ncnt, __popcll(pushing));
+                base = __shfl(base, 0);
+                if (again >= 0) next[base + __popcll(pushing & ((1ull << threadIdx.x) - 1ull))] = again;
+            }
         }
     }
 }
@@ -478,6 +571,26 @@ __global__ void init_solver_kernel(int n, int m, double *price, double *profit, 
     }
 }
 
+template <int NT, int RB>
+void launch_round_shape(mf_ctx *ctx, const SideArgs &s, int count, int ring)
+{
+    int grid = (count + RB - 1) / RB;
+    if (grid > MAX_GRID) grid = MAX_GRID;
+    hipLaunchKernelGGL((round_kernel<NT, RB>), dim3(grid), dim3(NT), 0, ctx->stream, s, ctx->list[ring & 1],
+                       ctx->list[(ring + 1) & 1], ctx->stats, ring);
+}
+
+void launch_round(mf_ctx *ctx, const SideArgs &s, int count, int ring)
+{
+    switch (count >= 2048 ? ctx->bulk_shape : 0) {      // small rounds: one line per workgroup
+    case 1: launch_round_shape<64, 4>(ctx, s, count, ring); break;
+    case 2: launch_round_shape<64, 2>(ctx, s, count, ring); break;
+    case 3: launch_round_shape<128, 4>(ctx, s, count, ring); break;
+    case 4: launch_round_shape<256, 4>(ctx, s, count, ring); break;
+    default: launch_round_shape<256, 1>(ctx, s, count, ring); break;
+    }
+}
+
 // Runs one side until nobody is left to bid.  list[0] / cnt[0] hold the first
 // bidders (`count` of them).  Returns MF_OK or an error.
 int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
@@ -489,11 +602,9 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
         if (left <= 0) return MF_ERR_NOT_CONVERGED;
         if (count > ctx->tail_max) {
             const int batch = count > 4096 ? 1 : 3;
-            const int grid = count < MAX_GRID ? count : MAX_GRID;
             for (int r = 0; r < batch; ++r) {
                 if (time_first && r == 0) { MF_HIP(hipEventRecord(ctx->ev[6], ctx->stream)); timed = true; }
-                hipLaunchKernelGGL(round_kernel<BID_THREADS>, dim3(grid), dim3(BID_THREADS), 0, ctx->stream,
-                                   s, ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, ring);
+                launch_round(ctx, s, count, ring);
                 if (time_first && r == 0) MF_HIP(hipEventRecord(ctx->ev[7], ctx->stream));
                 ++ring;
             }

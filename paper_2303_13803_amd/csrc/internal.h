@@ -59,6 +59,7 @@ struct mf_ctx {
     unsigned long long *colword, *roword;
     int *row2col, *col2row;
     int tail_max;                   // bidder count at or below which chains are followed in one kernel
+    int bulk_shape;                 // workgroup shape of rounds with many bidders (see launch_round)
     int chain_grid;                 // workgroups of that kernel
     int *list[2];
     int *colmark;                   // [max_m]
