@@ -94,6 +94,7 @@ typedef struct {
     int64_t chain_bids;         /* bids evaluated by the chain-following kernels        */
     int64_t chain_depth;        /* longest per-workgroup bid sequence, summed over them */
     int64_t chain_retries;      /* chain bids that lost and were redone                 */
+    int64_t team_bids;          /* chain bids evaluated by several workgroups together  */
     int32_t matched;            /* rows with a partner                                  */
     int32_t phases;             /* epsilon-scaling phases                               */
     int32_t cert_ok;            /* 1: matching valid, duals feasible, 0 <= D - K*P < K  */

@@ -47,15 +47,6 @@ struct Top2 {
     int idx, w;         // position and weight of the best
 };
 
-__device__ inline void top2_push(Top2 &t, double val, int j, int w)
-{
-    const bool gt = val > t.b1;
-    t.b2 = fmax(t.b2, fmin(val, t.b1));
-    t.idx = gt ? j : t.idx;
-    t.w = gt ? w : t.w;
-    t.b1 = fmax(t.b1, val);
-}
-
 __device__ inline void top2_merge(Top2 &t, const Top2 &o)
 {
     const double nb2 = fmax(fmax(t.b2, o.b2), fmin(t.b1, o.b1));
@@ -64,16 +55,6 @@ __device__ inline void top2_merge(Top2 &t, const Top2 &o)
     t.w = take ? o.w : t.w;
     t.b1 = fmax(t.b1, o.b1);
     t.b2 = nb2;
-}
-
-__device__ inline Top2 top2_shuffle_xor(const Top2 &t, int off)
-{
-    Top2 o;
-    o.b1 = __shfl_xor(t.b1, off);
-    o.b2 = __shfl_xor(t.b2, off);
-    o.idx = __shfl_xor(t.idx, off);
-    o.w = __shfl_xor(t.w, off);
-    return o;
 }
 
 struct SideArgs {
@@ -87,80 +68,24 @@ struct SideArgs {
 
 // Loads that must observe values other wavefronts produced during this kernel:
 // they bypass the caches that atomics performed at the memory side do not update.
+__device__ inline unsigned long long load_fresh_u64(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline unsigned load_fresh_u32(const unsigned *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void store_through(unsigned long long *p, unsigned long long v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ inline double load_fresh(const double *p)
 {
     return __longlong_as_double((long long)__hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED,
                                                              __HIP_MEMORY_SCOPE_AGENT));
 }
 
-// Scans line A[0..len) against dual[0..len): best and second-best value of
-// K*w - dual, the smallest index attaining the best and its weight.  Every
-// thread of the NT-thread block must call it; the result is valid in the
-// first wavefront (threads 0..63).  A is 16-byte aligned and padded to a
-// multiple of four entries, dual likewise.  `fresh` re-reads the duals past
-// the caches (block-uniform).
-template <int NT>
-__device__ inline Top2 block_scan(const int32_t *__restrict__ A, const double *__restrict__ dual,
-                                  int len, double Kd, bool fresh, Top2 *red)
-{
-    constexpr int UN = 4;               // independent load batches in flight per thread
-    Top2 t{NEG_HUGE, NEG_HUGE, 0x7fffffff, 0};
-    for (int j0 = threadIdx.x * 4; j0 < len; j0 += NT * 4 * UN) {
-        int4 w[UN];
-        double p[UN][4];
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int j = j0 + u * NT * 4;
-            if (j < len) {
-                w[u] = *(const int4 *)(A + j);
-                if (fresh) {
-                    p[u][0] = load_fresh(dual + j); p[u][1] = load_fresh(dual + j + 1);
-                    p[u][2] = load_fresh(dual + j + 2); p[u][3] = load_fresh(dual + j + 3);
-                } else {
-                    const double2 p01 = *(const double2 *)(dual + j);
-                    const double2 p23 = *(const double2 *)(dual + j + 2);
-                    p[u][0] = p01.x; p[u][1] = p01.y; p[u][2] = p23.x; p[u][3] = p23.y;
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int j = j0 + u * NT * 4;
-            if (j < len) {
-                double v0 = fma(Kd, (double)w[u].x, -p[u][0]);
-                double v1 = fma(Kd, (double)w[u].y, -p[u][1]);
-                double v2 = fma(Kd, (double)w[u].z, -p[u][2]);
-                double v3 = fma(Kd, (double)w[u].w, -p[u][3]);
-                if (j + 3 >= len) {
-                    if (j + 1 >= len) v1 = NEG_HUGE;
-                    if (j + 2 >= len) v2 = NEG_HUGE;
-                    v3 = NEG_HUGE;
-                }
-                top2_push(t, v0, j, w[u].x);
-                top2_push(t, v1, j + 1, w[u].y);
-                top2_push(t, v2, j + 2, w[u].z);
-                top2_push(t, v3, j + 3, w[u].w);
-            }
-        }
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) top2_merge(t, top2_shuffle_xor(t, off));
-    if (NT == 64) return t;
-    __syncthreads();                       // protect `red` from the previous line
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
-    __syncthreads();
-    if (threadIdx.x < 64) {
-        t = red[threadIdx.x < NT / 64 ? threadIdx.x : 0];
-#pragma unroll
-        for (int off = NT / 128; off >= 1; off >>= 1) top2_merge(t, top2_shuffle_xor(t, off));
-    }
-    return t;
-}
-
-// The same scan for RB lines at once: the opposite duals are loaded once per
-// four entries and applied to all RB lines, which cuts the on-chip traffic per
-// entry (duals are 8 bytes, weights 4) and keeps RB + 2 loads in flight per
-// thread.  Results are valid in the first wavefront.
 // Folds four consecutive entries (values v0..v3 at index j) into a running
 // top-2: a min/max network finds the group's best two, and only a group that
 // beats the running best pays for locating the entry.
@@ -178,6 +103,127 @@ __device__ __forceinline__ void top2_push4(double &b1, double &b2, int &idx, int
     }
     b2 = fmax(fmax(b2, g2), fmin(b1, g1));
     b1 = fmax(b1, g1);
+}
+
+// Wavefront-wide reductions by data-parallel-primitive moves (row shifts
+// within each row of 16 lanes, then row broadcasts), which cost a few cycles
+// per step where a cross-lane permute through LDS costs a hundred.  Lanes a
+// step has no source for keep their own value; maximum and minimum do not mind
+// seeing a value twice.  The total lands in lane 63 and is read from there.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v)
+{
+    return __hiloint2double(dpp_move<CTRL>(__double2hiint(v)), dpp_move<CTRL>(__double2loint(v)));
+}
+constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118,
+              DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+
+__device__ __forceinline__ double wave_max(double v)
+{
+    v = fmax(v, dpp_move<DPP_ROW_SHR1>(v));
+    v = fmax(v, dpp_move<DPP_ROW_SHR2>(v));
+    v = fmax(v, dpp_move<DPP_ROW_SHR4>(v));
+    v = fmax(v, dpp_move<DPP_ROW_SHR8>(v));
+    v = fmax(v, dpp_move<DPP_ROW_BCAST15>(v));
+    v = fmax(v, dpp_move<DPP_ROW_BCAST31>(v));
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63),
+                            __builtin_amdgcn_readlane(__double2loint(v), 63));
+}
+
+__device__ __forceinline__ int wave_min(int v)
+{
+    v = min(v, dpp_move<DPP_ROW_SHR1>(v));
+    v = min(v, dpp_move<DPP_ROW_SHR2>(v));
+    v = min(v, dpp_move<DPP_ROW_SHR4>(v));
+    v = min(v, dpp_move<DPP_ROW_SHR8>(v));
+    v = min(v, dpp_move<DPP_ROW_BCAST15>(v));
+    v = min(v, dpp_move<DPP_ROW_BCAST31>(v));
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
+// Wavefront-wide top-2 of per-lane top-2s, as two plain maximum reductions: the
+// best value, the first lane holding it (its index and weight are then read
+// from that lane), and the best of everything else.
+__device__ __forceinline__ Top2 wave_top2(const Top2 &t)
+{
+    Top2 r;
+    r.b1 = wave_max(t.b1);
+    // among lanes attaining the best, the smallest index wins (ties between lanes are rare)
+    const bool hit = t.b1 == r.b1;
+    const int idx = wave_min(hit ? t.idx : 0x7fffffff);
+    r.idx = idx;
+    const bool owner = hit && t.idx == idx;
+    const unsigned long long own = __ballot(owner);
+    const int src = own ? (int)__ffsll((long long)own) - 1 : 0;
+    r.w = __builtin_amdgcn_readlane(t.w, src);
+    r.b2 = wave_max(owner ? t.b2 : t.b1);
+    return r;
+}
+
+// Scans line A[0..len) against dual[0..len): best and second-best value of
+// K*w - dual, the smallest index attaining the best and its weight.  Every
+// thread of the NT-thread block must call it; the result is valid in thread 0.
+// A is 16-byte aligned and padded to a multiple of four entries, dual
+// likewise.  `fresh` re-reads the duals past the caches (block-uniform).
+template <int NT>
+__device__ inline Top2 block_scan(const int32_t *__restrict__ A, const double *__restrict__ dual,
+                                  int len, double Kd, bool fresh, Top2 *red)
+{
+    constexpr int UN = 4;               // independent load batches in flight per thread
+    Top2 t{NEG_HUGE, NEG_HUGE, 0x7fffffff, 0};
+    const int full = len & ~3;          // whole groups of four
+    for (int j0 = threadIdx.x * 4; j0 < full; j0 += NT * 4 * UN) {
+        int4 w[UN];
+        double p[UN][4];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int j = j0 + u * NT * 4;
+            if (j < full) {
+                w[u] = *(const int4 *)(A + j);
+                if (fresh) {
+                    p[u][0] = load_fresh(dual + j); p[u][1] = load_fresh(dual + j + 1);
+                    p[u][2] = load_fresh(dual + j + 2); p[u][3] = load_fresh(dual + j + 3);
+                } else {
+                    const double2 p01 = *(const double2 *)(dual + j);
+                    const double2 p23 = *(const double2 *)(dual + j + 2);
+                    p[u][0] = p01.x; p[u][1] = p01.y; p[u][2] = p23.x; p[u][3] = p23.y;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int j = j0 + u * NT * 4;
+            if (j < full)
+                top2_push4(t.b1, t.b2, t.idx, t.w, fma(Kd, (double)w[u].x, -p[u][0]),
+                           fma(Kd, (double)w[u].y, -p[u][1]), fma(Kd, (double)w[u].z, -p[u][2]),
+                           fma(Kd, (double)w[u].w, -p[u][3]), j, w[u]);
+        }
+    }
+    if (full < len && (int)threadIdx.x == (full / 4) % NT) {   // the last, partial group
+        const int4 w = *(const int4 *)(A + full);
+        double p[3];
+        for (int e = 0; e < 3; ++e) p[e] = fresh ? load_fresh(dual + full + e) : dual[full + e];
+        top2_push4(t.b1, t.b2, t.idx, t.w, fma(Kd, (double)w.x, -p[0]),
+                   full + 1 < len ? fma(Kd, (double)w.y, -p[1]) : NEG_HUGE,
+                   full + 2 < len ? fma(Kd, (double)w.z, -p[2]) : NEG_HUGE, NEG_HUGE, full, w);
+    }
+    // waves that saw no entry skip the reduction (they share SIMDs with the busy ones)
+    const bool busy = (int)(threadIdx.x & ~63u) * 4 < len;
+    if (busy) t = wave_top2(t);
+    if (NT == 64) return t;
+    __syncthreads();                       // protect `red` from its previous use
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        t = threadIdx.x < NT / 64 ? red[threadIdx.x] : Top2{NEG_HUGE, NEG_HUGE, 0x7fffffff, 0};
+        t = wave_top2(t);
+    }
+    return t;
 }
 
 // Whole-line scan of RB lines at once: the opposite duals are loaded once per
@@ -221,9 +267,7 @@ __device__ __forceinline__ void block_scan_rows(const int32_t *const (&rows)[RB]
     __syncthreads();                       // protect `red` from its previous use
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
-        Top2 t{b1[r], b2[r], idx[r], wb[r]};
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) top2_merge(t, top2_shuffle_xor(t, off));
+        const Top2 t = wave_top2(Top2{b1[r], b2[r], idx[r], wb[r]});
         if ((threadIdx.x & 63) == 0) red[RB + r * (NT / 64) + (threadIdx.x >> 6)] = t;
     }
     __syncthreads();
@@ -314,16 +358,19 @@ __global__ __launch_bounds__(NT) void round_kernel(SideArgs s, const int *__rest
 // next, and so on.  Each workgroup takes a pending bidder and then follows its
 // chain - after every bid it goes on with whoever has to bid because of it -
 // so no workgroup creates work for another, none waits for another, and each
-// stops as soon as the list is used up.
+// stops as soon as the list is used up.  `stats->active` counts the workgroups
+// still following a chain; once it is at most `hand_back_at` the rest hand their
+// bidders back, so that the host can put several workgroups on each chain.
 constexpr int CHAIN_THREADS = 1024;
 
 __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const int *__restrict__ list,
                                                               int *__restrict__ out_list,
                                                               mf_device_stats *stats, int ring,
-                                                              long long step_cap)
+                                                              long long step_cap, int hand_back_at)
 {
     __shared__ Top2 red[CHAIN_THREADS / 64];
-    __shared__ int s_next;
+    __shared__ int s_next, s_active;
+    if (threadIdx.x == 0) s_active = 0x7fffffff;
     const int count = stats->cnt[ring & 3];
     unsigned long long steps = 0, retries = 0;
     for (;;) {
@@ -335,7 +382,13 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const 
         int b = list[item];
         bool fresh = false;                 // re-read the duals past the caches after a bid that lost
         while (b >= 0) {
-            if ((long long)steps >= step_cap) {                     // hand the bidder back to the host loop
+            if ((steps & 3) == 0) {         // now and then: how many workgroups still follow a chain?
+                __syncthreads();
+                if (threadIdx.x == 0)
+                    s_active = __hip_atomic_load(&stats->active, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __syncthreads();
+            }
+            if ((long long)steps >= step_cap || s_active <= hand_back_at) {
                 if (threadIdx.x == 0) out_list[atomicAdd(&stats->cnt[(ring + 1) & 3], 1)] = b;
                 break;
             }
@@ -348,24 +401,192 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const 
             if (fresh && threadIdx.x == 0) ++retries;
             b = s_next;
         }
+        if (b >= 0) break;                  // handed back: take no further bidder
     }
-    if (threadIdx.x == 0 && steps) {
-        atomicAdd(&stats->bids, steps);
-        atomicAdd(&stats->chain_bids, steps);
-        atomicAdd(&stats->bytes, steps * (unsigned long long)s.len * 4ull);
-        atomicMax(&stats->launch_max, steps);
-        if (retries) atomicAdd(&stats->chain_retries, retries);
+    if (threadIdx.x == 0) {
+        atomicAdd(&stats->active, -1);      // this workgroup follows no chain any more
+        if (steps) {
+            atomicAdd(&stats->bids, steps);
+            atomicAdd(&stats->chain_bids, steps);
+            atomicAdd(&stats->bytes, steps * (unsigned long long)s.len * 4ull);
+            atomicMax(&stats->launch_max, steps);
+            if (retries) atomicAdd(&stats->chain_retries, retries);
+        }
     }
 }
 
-__global__ void chain_begin_kernel(mf_device_stats *stats, int ring)
+__global__ void chain_begin_kernel(mf_device_stats *stats, int ring, int workgroups)
 {
     stats->head = 0;
+    stats->active = workgroups;
     stats->cnt[(ring + 1) & 3] = 0;
     stats->cnt[(ring + 2) & 3] = 0;
     stats->rounds += 1ull;
     stats->chain_depth += stats->launch_max;     // of the previous chain kernel
     stats->launch_max = 0;
+}
+
+// The last few chains.  One compute unit cannot keep enough memory requests in
+// flight to read a 100 KB line in much under ten microseconds, and with one
+// or two chains left that latency is all there is.  Here TEAM_SIZE workgroups
+// (on as many compute units) share each step of one chain: the leader
+// publishes the bidder, every member scans its slice of the line and posts
+// its top-2, the leader merges them, bids and publishes the next bidder.
+// Members only ever wait for their leader and the leader for its members;
+// every wait is bounded, and a wait that runs out raises `abort` so that all
+// workgroups leave and the host falls back to chain_kernel.
+constexpr int TEAM_SIZE = 16;
+constexpr int TEAM_MAX = 8;
+constexpr unsigned TEAM_SPIN_LIMIT = 1u << 21;
+
+struct alignas(128) TeamCtl {
+    unsigned long long cmd;             // sequence << 32 | fresh << 31 | (bidder + 1); bidder + 1 == 0: stop
+    unsigned int arrived;               // member results posted so far
+    unsigned int abort;
+    unsigned long long pad[14];
+    unsigned long long partial[TEAM_SIZE][4];   // b1 bits, b2 bits, w << 32 | idx
+};
+
+__global__ void team_begin_kernel(mf_device_stats *stats, TeamCtl *ctl, int ring)
+{
+    const int t = threadIdx.x;
+    if (t < TEAM_MAX) { ctl[t].cmd = 0ull; ctl[t].arrived = 0u; ctl[t].abort = 0u; }
+    if (t == 0) {
+        stats->head = 0;
+        stats->cnt[(ring + 1) & 3] = 0;
+        stats->cnt[(ring + 2) & 3] = 0;
+        stats->rounds += 1ull;
+        stats->chain_depth += stats->launch_max;
+        stats->launch_max = 0;
+    }
+}
+
+__global__ __launch_bounds__(CHAIN_THREADS) void team_kernel(SideArgs s, const int *__restrict__ list,
+                                                             int *__restrict__ out_list,
+                                                             mf_device_stats *stats, TeamCtl *ctl_all,
+                                                             int ring, long long step_cap)
+{
+    __shared__ Top2 red[CHAIN_THREADS / 64];
+    __shared__ long long s_word;
+    TeamCtl *ctl = ctl_all + blockIdx.x / TEAM_SIZE;
+    const int member = blockIdx.x % TEAM_SIZE;
+    const int slice = (((s.len + TEAM_SIZE - 1) / TEAM_SIZE) + 3) & ~3;
+    const int off = member * slice;
+    const int my_len = max(0, min(slice, s.len - off));
+    const int count = stats->cnt[ring & 3];
+
+    if (member != 0) {
+        // ---- member: wait for the leader's next command, scan, post ----
+        unsigned expect = 1;
+        for (;;) {
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                unsigned long long c = 0ull;
+                unsigned spins = 0;
+                for (;;) {
+                    c = load_fresh_u64(&ctl->cmd);
+                    if ((unsigned)(c >> 32) == expect) break;
+                    if (++spins > TEAM_SPIN_LIMIT || load_fresh_u32(&ctl->abort)) { c = 0ull; break; }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+                if (c == 0ull) atomicExch(&ctl->abort, 1u);
+                s_word = (long long)c;
+            }
+            __syncthreads();
+            const unsigned long long c = (unsigned long long)s_word;
+            const int b = (int)(c & 0x7fffffffull) - 1;
+            if (b < 0) break;                                   // stop (or abort)
+            const bool fresh = (c >> 31) & 1ull;
+            const Top2 t = block_scan<CHAIN_THREADS>(s.A + (size_t)b * s.pitch + off, s.other_dual + off,
+                                                      my_len, s.Kd, fresh, red);
+            if (threadIdx.x == 0) {
+                store_through(&ctl->partial[member][0], (unsigned long long)__double_as_longlong(t.b1));
+                store_through(&ctl->partial[member][1], (unsigned long long)__double_as_longlong(t.b2));
+                store_through(&ctl->partial[member][2],
+                              ((unsigned long long)(unsigned)t.w << 32) | (unsigned)(t.idx + off));
+                __threadfence();
+                atomicAdd(&ctl->arrived, 1u);
+            }
+            ++expect;
+        }
+        return;
+    }
+
+    // ---- leader: follow chains, one command per step ----
+    unsigned seq = 0;
+    unsigned long long steps = 0, retries = 0;
+    bool dead = false;
+    while (!dead) {
+        __syncthreads();
+        if (threadIdx.x == 0) s_word = atomicAdd(&stats->head, 1);
+        __syncthreads();
+        const int item = (int)s_word;
+        if (item >= count) break;
+        int b = list[item];
+        bool fresh = false;
+        while (b >= 0) {
+            if ((long long)steps >= step_cap) {
+                if (threadIdx.x == 0) out_list[atomicAdd(&stats->cnt[(ring + 1) & 3], 1)] = b;
+                dead = true;
+                break;
+            }
+            ++steps;
+            ++seq;
+            if (threadIdx.x == 0)
+                store_through(&ctl->cmd, ((unsigned long long)seq << 32) | (fresh ? 0x80000000ull : 0ull) |
+                                             (unsigned long long)(b + 1));
+            const Top2 t = block_scan<CHAIN_THREADS>(s.A + (size_t)b * s.pitch, s.other_dual, my_len, s.Kd,
+                                                      fresh, red);
+            if (threadIdx.x < 64) {                         // first wavefront: collect the members' results
+                int ok = 1;
+                if (threadIdx.x == 0) {
+                    unsigned spins = 0;
+                    while (load_fresh_u32(&ctl->arrived) != seq * (unsigned)(TEAM_SIZE - 1)) {
+                        if (++spins > TEAM_SPIN_LIMIT || load_fresh_u32(&ctl->abort)) { ok = 0; break; }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                }
+                ok = __shfl(ok, 0);
+                if (ok) {
+                    Top2 mine = t;                          // the leader's own slice
+                    const int k = threadIdx.x;
+                    if (k >= TEAM_SIZE) {
+                        mine = Top2{NEG_HUGE, NEG_HUGE, 0x7fffffff, 0};
+                    } else if (k >= 1) {                    // one member's result per lane
+                        mine.b1 = __longlong_as_double((long long)load_fresh_u64(&ctl->partial[k][0]));
+                        mine.b2 = __longlong_as_double((long long)load_fresh_u64(&ctl->partial[k][1]));
+                        const unsigned long long iw = load_fresh_u64(&ctl->partial[k][2]);
+                        mine.idx = (int)(unsigned)(iw & 0xffffffffull);
+                        mine.w = (int)(unsigned)(iw >> 32);
+                    }
+                    mine = wave_top2(mine);
+                    if (threadIdx.x == 0) s_word = decide_and_bid(s, b, mine);
+                } else if (threadIdx.x == 0) {
+                    atomicExch(&ctl->abort, 1u);
+                    out_list[atomicAdd(&stats->cnt[(ring + 1) & 3], 1)] = b;
+                    s_word = -2;
+                }
+            }
+            __syncthreads();
+            const int next = (int)s_word;
+            if (next == -2) { dead = true; break; }
+            fresh = (next == b);
+            retries += fresh;
+            b = next;
+        }
+    }
+    if (threadIdx.x == 0) {
+        store_through(&ctl->cmd, (unsigned long long)(seq + 1) << 32);      // stop
+        if (load_fresh_u32(&ctl->abort)) atomicExch(&stats->team_abort, 1);
+        if (steps) {
+            atomicAdd(&stats->bids, steps);
+            atomicAdd(&stats->chain_bids, steps);
+            atomicAdd(&stats->team_bids, steps);
+            atomicAdd(&stats->bytes, steps * (unsigned long long)s.len * 4ull);
+            atomicMax(&stats->launch_max, steps);
+            if (retries) atomicAdd(&stats->chain_retries, retries);
+        }
+    }
 }
 
 // Start of an epsilon phase: drop the assignment, keep the duals, all rows bid.
@@ -566,7 +787,7 @@ __global__ void init_solver_kernel(int n, int m, double *price, double *profit, 
     if (i < m + 4) price[i] = 0.0;
     if (i == 0) {
         stats->rounds = 0; stats->bids = 0; stats->bytes = 0; stats->head = 0;
-        stats->chain_bids = 0; stats->chain_depth = 0; stats->launch_max = 0; stats->chain_retries = 0; stats->max_weight = 0;
+        stats->chain_bids = 0; stats->chain_depth = 0; stats->launch_max = 0; stats->chain_retries = 0; stats->team_bids = 0; stats->team_abort = 0; stats->active = 0; stats->max_weight = 0;
         stats->cnt[0] = 0; stats->cnt[1] = 0; stats->cnt[2] = 0; stats->cnt[3] = 0;
     }
 }
@@ -608,12 +829,21 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
                 if (time_first && r == 0) MF_HIP(hipEventRecord(ctx->ev[7], ctx->stream));
                 ++ring;
             }
-        } else {
+        } else if (count > ctx->team_max || ctx->team_max == 0 || ctx->team_off) {
             const int grid = count < ctx->chain_grid ? count : ctx->chain_grid;
-            hipLaunchKernelGGL(chain_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats, ring);
+            const int hand_back = ctx->team_off ? -1 : ctx->team_max;
+            hipLaunchKernelGGL(chain_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats, ring, grid);
             hipLaunchKernelGGL(chain_kernel, dim3(grid), dim3(CHAIN_THREADS), 0, ctx->stream, s,
                                ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, ring,
-                               left / grid + 1);
+                               left / grid + 1, hand_back);
+            ++ring;
+        } else {
+            const int teams = count < ctx->team_max ? count : ctx->team_max;
+            hipLaunchKernelGGL(team_begin_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->stats,
+                               (TeamCtl *)ctx->team_ctl, ring);
+            hipLaunchKernelGGL(team_kernel, dim3(teams * TEAM_SIZE), dim3(CHAIN_THREADS), 0, ctx->stream, s,
+                               ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats,
+                               (TeamCtl *)ctx->team_ctl, ring, left / teams + 1);
             ++ring;
         }
         MF_HIP(hipGetLastError());
@@ -628,6 +858,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
         }
         time_first = false;
         count = ctx->h_stats->cnt[ring & 3];
+        if (ctx->h_stats->team_abort) ctx->team_off = true;   // a bounded wait ran out: one workgroup per chain from now on
     }
     return MF_OK;
 }
@@ -744,6 +975,7 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     h_res->bytes_scanned = (int64_t)ctx->h_stats->bytes;
     h_res->chain_bids = (int64_t)ctx->h_stats->chain_bids;
     h_res->chain_retries = (int64_t)ctx->h_stats->chain_retries;
+    h_res->team_bids = (int64_t)ctx->h_stats->team_bids;
     h_res->chain_depth = (int64_t)(ctx->h_stats->chain_depth + ctx->h_stats->launch_max);
     h_res->phases = phases;
     h_res->ms_solve = ms_solve;

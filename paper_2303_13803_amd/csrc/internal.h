@@ -31,10 +31,13 @@ struct mf_device_stats {            // lives in device memory, cleared per solve
     unsigned long long chain_bids;  // bids evaluated by chain kernels
     unsigned long long chain_depth; // sum over chain kernels of the most bids any one workgroup evaluated
     unsigned long long chain_retries; // chain bids that lost and were redone with uncached dual reads
+    unsigned long long team_bids;   // chain bids evaluated by several workgroups together
     unsigned long long launch_max;  // scratch: that maximum for the chain kernel in flight
     int max_weight;
     int cnt[4];                     // ring of bidder-list lengths: round r reads cnt[r & 3]
     int head;                       // next unclaimed entry of the list a chain kernel works through
+    int active;                     // workgroups of the running chain kernel still following a chain
+    int team_abort;                 // a bounded wait between cooperating workgroups ran out
 };
 
 struct mf_cert_out {                // lives in device memory, cleared per check
@@ -60,6 +63,9 @@ struct mf_ctx {
     int *row2col, *col2row;
     int tail_max;                   // bidder count at or below which chains are followed in one kernel
     int bulk_shape;                 // workgroup shape of rounds with many bidders (see launch_round)
+    int team_max;                   // chains at or below which several workgroups share each chain (0: never)
+    bool team_off;                  // set after a team wait ran out
+    void *team_ctl;                 // control blocks of the cooperating workgroups
     int chain_grid;                 // workgroups of that kernel
     int *list[2];
     int *colmark;                   // [max_m]
