@@ -103,7 +103,7 @@ def main():
     achieved = flops / (pair_ms * 1e-3)
     bulk_launches = max(avg["bulk_bid_launches"], 1.0)
     bulk_bytes = avg["bulk_bid_bytes"] / bulk_launches
-    bulk_ms = avg["bulk_bid_ms"] / bulk_launches
+    bulk_ms = max(avg["bulk_bid_ms"] / bulk_launches, 1e-9)      # no bulk round at tiny sizes
     out = {
         "metric": "pairs scored/s + schedule_round latency (ms) at 20k x 20k on 1 MI355X",
         "value": n * m / (ms_per_step * 1e-3), "unit": "pairs/s",

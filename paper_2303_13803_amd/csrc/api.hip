@@ -72,6 +72,8 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->chain_grid = 256;
     ctx->bulk_shape = 1;
     ctx->team_max = 8;
+    ctx->team_size = 16;
+    ctx->team_threads = 1024;
     const size_t nm = (size_t)max_m;                      // max_m >= max_n
     const size_t ldt = ((size_t)max_n + 3) & ~(size_t)3;
     hipError_t e = hipSuccess;
@@ -87,7 +89,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->roword, (size_t)max_n));
     TRY(dev_alloc(&ctx->row2col, (size_t)max_n));
     TRY(dev_alloc(&ctx->col2row, (size_t)max_m));
-    TRY(hipMalloc(&ctx->team_ctl, 8 * 1024));
+    TRY(hipMalloc(&ctx->team_ctl, 32 * 1024));
     TRY(dev_alloc(&ctx->list[0], nm));
     TRY(dev_alloc(&ctx->list[1], nm));
     TRY(dev_alloc(&ctx->colmark, (size_t)max_m));
@@ -198,7 +200,9 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "theta")) { if (value < 2 || value > 1024) return MF_ERR_ARG; ctx->theta = value; return MF_OK; }
     if (!strcmp(name, "tail_max")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->tail_max = (int)value; return MF_OK; }
     if (!strcmp(name, "bulk_shape")) { if (value < 0 || value > 4) return MF_ERR_ARG; ctx->bulk_shape = (int)value; return MF_OK; }
-    if (!strcmp(name, "team_max")) { if (value < 0 || value > 8) return MF_ERR_ARG; ctx->team_max = (int)value; return MF_OK; }
+    if (!strcmp(name, "team_max")) { if (value < 0 || value > 16) return MF_ERR_ARG; ctx->team_max = (int)value; return MF_OK; }
+    if (!strcmp(name, "team_size")) { if (value < 2 || value > 32) return MF_ERR_ARG; ctx->team_size = (int)value; return MF_OK; }
+    if (!strcmp(name, "team_threads")) { if (value != 256 && value != 512 && value != 1024) return MF_ERR_ARG; ctx->team_threads = (int)value; return MF_OK; }
     if (!strcmp(name, "chain_grid")) { if (value < 1 || value > 4096) return MF_ERR_ARG; ctx->chain_grid = (int)value; return MF_OK; }
     if (!strcmp(name, "max_rounds")) { if (value < 1) return MF_ERR_ARG; ctx->max_rounds = value; return MF_OK; }
     return MF_ERR_ARG;

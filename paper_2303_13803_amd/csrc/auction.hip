@@ -435,8 +435,8 @@ __global__ void chain_begin_kernel(mf_device_stats *stats, int ring, int workgro
 // Members only ever wait for their leader and the leader for its members;
 // every wait is bounded, and a wait that runs out raises `abort` so that all
 // workgroups leave and the host falls back to chain_kernel.
-constexpr int TEAM_SIZE = 16;
-constexpr int TEAM_MAX = 8;
+constexpr int TEAM_SIZE_MAX = 32;        // workgroups per chain (run-time choice up to this)
+constexpr int TEAM_MAX = 16;             // chains served at once
 constexpr unsigned TEAM_SPIN_LIMIT = 1u << 21;
 
 struct alignas(128) TeamCtl {
@@ -444,7 +444,7 @@ struct alignas(128) TeamCtl {
     unsigned int arrived;               // member results posted so far
     unsigned int abort;
     unsigned long long pad[14];
-    unsigned long long partial[TEAM_SIZE][4];   // b1 bits, b2 bits, w << 32 | idx
+    unsigned long long partial[TEAM_SIZE_MAX][4];   // b1 bits, b2 bits, w << 32 | idx
 };
 
 __global__ void team_begin_kernel(mf_device_stats *stats, TeamCtl *ctl, int ring)
@@ -461,12 +461,13 @@ __global__ void team_begin_kernel(mf_device_stats *stats, TeamCtl *ctl, int ring
     }
 }
 
-__global__ __launch_bounds__(CHAIN_THREADS) void team_kernel(SideArgs s, const int *__restrict__ list,
-                                                             int *__restrict__ out_list,
-                                                             mf_device_stats *stats, TeamCtl *ctl_all,
-                                                             int ring, long long step_cap)
+template <int NT>
+__global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restrict__ list,
+                                                  int *__restrict__ out_list, mf_device_stats *stats,
+                                                  TeamCtl *ctl_all, int ring, long long step_cap,
+                                                  int TEAM_SIZE)
 {
-    __shared__ Top2 red[CHAIN_THREADS / 64];
+    __shared__ Top2 red[NT / 64];
     __shared__ long long s_word;
     TeamCtl *ctl = ctl_all + blockIdx.x / TEAM_SIZE;
     const int member = blockIdx.x % TEAM_SIZE;
@@ -497,7 +498,7 @@ __global__ __launch_bounds__(CHAIN_THREADS) void team_kernel(SideArgs s, const i
             const int b = (int)(c & 0x7fffffffull) - 1;
             if (b < 0) break;                                   // stop (or abort)
             const bool fresh = (c >> 31) & 1ull;
-            const Top2 t = block_scan<CHAIN_THREADS>(s.A + (size_t)b * s.pitch + off, s.other_dual + off,
+            const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch + off, s.other_dual + off,
                                                       my_len, s.Kd, fresh, red);
             if (threadIdx.x == 0) {
                 store_through(&ctl->partial[member][0], (unsigned long long)__double_as_longlong(t.b1));
@@ -535,8 +536,7 @@ __global__ __launch_bounds__(CHAIN_THREADS) void team_kernel(SideArgs s, const i
             if (threadIdx.x == 0)
                 store_through(&ctl->cmd, ((unsigned long long)seq << 32) | (fresh ? 0x80000000ull : 0ull) |
                                              (unsigned long long)(b + 1));
-            const Top2 t = block_scan<CHAIN_THREADS>(s.A + (size_t)b * s.pitch, s.other_dual, my_len, s.Kd,
-                                                      fresh, red);
+            const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch, s.other_dual, my_len, s.Kd, fresh, red);
             if (threadIdx.x < 64) {                         // first wavefront: collect the members' results
                 int ok = 1;
                 if (threadIdx.x == 0) {
@@ -841,9 +841,19 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
             const int teams = count < ctx->team_max ? count : ctx->team_max;
             hipLaunchKernelGGL(team_begin_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->stats,
                                (TeamCtl *)ctx->team_ctl, ring);
-            hipLaunchKernelGGL(team_kernel, dim3(teams * TEAM_SIZE), dim3(CHAIN_THREADS), 0, ctx->stream, s,
-                               ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats,
-                               (TeamCtl *)ctx->team_ctl, ring, left / teams + 1);
+            const dim3 grid(teams * ctx->team_size);
+            if (ctx->team_threads == 256)
+                hipLaunchKernelGGL(team_kernel<256>, grid, dim3(256), 0, ctx->stream, s, ctx->list[ring & 1],
+                                   ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
+                                   left / teams + 1, ctx->team_size);
+            else if (ctx->team_threads == 512)
+                hipLaunchKernelGGL(team_kernel<512>, grid, dim3(512), 0, ctx->stream, s, ctx->list[ring & 1],
+                                   ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
+                                   left / teams + 1, ctx->team_size);
+            else
+                hipLaunchKernelGGL(team_kernel<1024>, grid, dim3(1024), 0, ctx->stream, s, ctx->list[ring & 1],
+                                   ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
+                                   left / teams + 1, ctx->team_size);
             ++ring;
         }
         MF_HIP(hipGetLastError());

@@ -64,6 +64,7 @@ struct mf_ctx {
     int tail_max;                   // bidder count at or below which chains are followed in one kernel
     int bulk_shape;                 // workgroup shape of rounds with many bidders (see launch_round)
     int team_max;                   // chains at or below which several workgroups share each chain (0: never)
+    int team_size, team_threads;    // workgroups per chain, threads per such workgroup
     bool team_off;                  // set after a team wait ran out
     void *team_ctl;                 // control blocks of the cooperating workgroups
     int chain_grid;                 // workgroups of that kernel
