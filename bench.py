@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=192)
     ap.add_argument("--cpu-block", type=int, default=1536)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calib-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB (reference for hardware byte counters)")
     ap.add_argument("--opt", action="append", default=[], help="solver option name=value (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -84,6 +86,13 @@ def main():
         res = ctx.schedule_round(pred, x_on, x_off, W, r2c, u, v)
         return res, ctx.last_timings()
 
+    if args.calib_mib:
+        src = torch.ones(args.calib_mib * 262144, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

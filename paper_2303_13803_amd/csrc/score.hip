@@ -69,9 +69,13 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hh = lane >> 5, nn = lane & 31;
-    const int row0 = blockIdx.y * ROWS;
+    // consecutive workgroups (which the hardware deals out to the eight XCDs in turn) share one
+    // tile of offline columns and walk down the online rows, so that tile stays in every L2
+    // and each XCD keeps re-reading the same eighth of the online projections
+    const int row0 = blockIdx.x * ROWS;
+    if (row0 >= n) return;                  // the grid's x extent is padded to a multiple of eight
     const int nrows = min(ROWS, n - row0);
-    const int j0 = (blockIdx.x * PAIR_WAVES + wave) * 32;
+    const int j0 = (blockIdx.y * PAIR_WAVES + wave) * 32;
 
     for (int idx = tid; idx < MB * Q * 64; idx += PAIR_THREADS) {
         int ln = idx & 63, s4 = (idx >> 6) % Q, mb = idx / (64 * Q);
@@ -164,7 +168,8 @@ int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, 
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS_BYTES));
         configured = true;
     }
-    dim3 grid((m + PAIR_COLS - 1) / PAIR_COLS, (n + S::ROWS - 1) / S::ROWS);
+    // x padded to a multiple of 8: every XCD then meets the same row tiles for each column tile
+    dim3 grid((((n + S::ROWS - 1) / S::ROWS) + 7) & ~7, (m + PAIR_COLS - 1) / PAIR_COLS);
     hipLaunchKernelGGL(pair_mlp_kernel<H>, grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
                        ctx->proj_on, ctx->proj_off, p->d_W2, p->d_b2, p->d_W3, p->d_b3,
                        ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma);
