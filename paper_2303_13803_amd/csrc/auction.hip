@@ -441,16 +441,32 @@ constexpr unsigned TEAM_SPIN_LIMIT = 1u << 21;
 
 struct alignas(128) TeamCtl {
     unsigned long long cmd;             // sequence << 32 | fresh << 31 | (bidder + 1); bidder + 1 == 0: stop
-    unsigned int arrived;               // member results posted so far
     unsigned int abort;
+    unsigned int pad0;
     unsigned long long pad[14];
-    unsigned long long partial[TEAM_SIZE_MAX][4];   // b1 bits, b2 bits, w << 32 | idx
+    // a member's result: three words, each carrying the low 8 bits of the step's sequence number,
+    // so that the leader can tell a word of this step from the previous one without any fence:
+    // best << 8 | tag, second << 8 | tag, index << 40 | (weight & 0xffffffff) << 8 | tag
+    unsigned long long partial[TEAM_SIZE_MAX][4];
 };
+
+__device__ inline unsigned long long tag_value(double v, unsigned tag)
+{
+    const double c = fmin(fmax(v, -4.0e15), 4.0e15);        // integers up to 2^52 in magnitude
+    return ((unsigned long long)(long long)c << 8) | (unsigned long long)(tag & 0xffu);
+}
+__device__ inline double untag_value(unsigned long long w)
+{
+    return (double)((long long)w >> 8);
+}
 
 __global__ void team_begin_kernel(mf_device_stats *stats, TeamCtl *ctl, int ring)
 {
     const int t = threadIdx.x;
-    if (t < TEAM_MAX) { ctl[t].cmd = 0ull; ctl[t].arrived = 0u; ctl[t].abort = 0u; }
+    if (t < TEAM_MAX) {
+        ctl[t].cmd = 0ull; ctl[t].abort = 0u;
+        for (int k = 0; k < TEAM_SIZE_MAX; ++k) { ctl[t].partial[k][0] = 0ull; ctl[t].partial[k][1] = 0ull; ctl[t].partial[k][2] = 0ull; }
+    }
     if (t == 0) {
         stats->head = 0;
         stats->cnt[(ring + 1) & 3] = 0;
@@ -487,8 +503,8 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
                 for (;;) {
                     c = load_fresh_u64(&ctl->cmd);
                     if ((unsigned)(c >> 32) == expect) break;
-                    if (++spins > TEAM_SPIN_LIMIT || load_fresh_u32(&ctl->abort)) { c = 0ull; break; }
-                    __builtin_amdgcn_s_sleep(2);
+                    ++spins;
+                    if (spins > TEAM_SPIN_LIMIT || ((spins & 255u) == 0u && load_fresh_u32(&ctl->abort))) { c = 0ull; break; }
                 }
                 if (c == 0ull) atomicExch(&ctl->abort, 1u);
                 s_word = (long long)c;
@@ -497,16 +513,16 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
             const unsigned long long c = (unsigned long long)s_word;
             const int b = (int)(c & 0x7fffffffull) - 1;
             if (b < 0) break;                                   // stop (or abort)
-            const bool fresh = (c >> 31) & 1ull;
+            // a slice is small enough to stay in this compute unit's cache from step to step, so the
+            // duals are always read past the caches here
             const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch + off, s.other_dual + off,
-                                                      my_len, s.Kd, fresh, red);
+                                                      my_len, s.Kd, true, red);
             if (threadIdx.x == 0) {
-                store_through(&ctl->partial[member][0], (unsigned long long)__double_as_longlong(t.b1));
-                store_through(&ctl->partial[member][1], (unsigned long long)__double_as_longlong(t.b2));
-                store_through(&ctl->partial[member][2],
-                              ((unsigned long long)(unsigned)t.w << 32) | (unsigned)(t.idx + off));
-                __threadfence();
-                atomicAdd(&ctl->arrived, 1u);
+                const int idx = t.idx == 0x7fffffff ? 0 : t.idx + off;
+                store_through(&ctl->partial[member][0], tag_value(t.b1, expect));
+                store_through(&ctl->partial[member][1], tag_value(t.b2, expect));
+                store_through(&ctl->partial[member][2], ((unsigned long long)(unsigned)idx << 40) |
+                                                            ((unsigned long long)(unsigned)t.w << 8) | (expect & 0xffu));
             }
             ++expect;
         }
@@ -536,29 +552,32 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
             if (threadIdx.x == 0)
                 store_through(&ctl->cmd, ((unsigned long long)seq << 32) | (fresh ? 0x80000000ull : 0ull) |
                                              (unsigned long long)(b + 1));
-            const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch, s.other_dual, my_len, s.Kd, fresh, red);
-            if (threadIdx.x < 64) {                         // first wavefront: collect the members' results
+            const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch, s.other_dual, my_len, s.Kd, true, red);
+            if (threadIdx.x < 64) {                         // first wavefront: one lane per member
+                const int k = threadIdx.x;
+                Top2 mine = t;                              // lane 0: the leader's own slice
                 int ok = 1;
-                if (threadIdx.x == 0) {
+                if (k >= TEAM_SIZE) {
+                    mine = Top2{NEG_HUGE, NEG_HUGE, 0x7fffffff, 0};
+                } else if (k >= 1) {                        // wait for member k's three words of this step
+                    const unsigned tag = seq & 0xffu;
+                    unsigned long long w0, w1, w2;
                     unsigned spins = 0;
-                    while (load_fresh_u32(&ctl->arrived) != seq * (unsigned)(TEAM_SIZE - 1)) {
-                        if (++spins > TEAM_SPIN_LIMIT || load_fresh_u32(&ctl->abort)) { ok = 0; break; }
-                        __builtin_amdgcn_s_sleep(1);
+                    for (;;) {
+                        w0 = load_fresh_u64(&ctl->partial[k][0]);
+                        w1 = load_fresh_u64(&ctl->partial[k][1]);
+                        w2 = load_fresh_u64(&ctl->partial[k][2]);
+                        if ((w0 & 0xffu) == tag && (w1 & 0xffu) == tag && (w2 & 0xffu) == tag) break;
+                        ++spins;
+                        if (spins > TEAM_SPIN_LIMIT || ((spins & 255u) == 0u && load_fresh_u32(&ctl->abort))) { ok = 0; break; }
                     }
+                    mine.b1 = untag_value(w0);
+                    mine.b2 = untag_value(w1);
+                    mine.idx = (int)(w2 >> 40);
+                    mine.w = (int)(unsigned)((w2 >> 8) & 0xffffffffull);
                 }
-                ok = __shfl(ok, 0);
+                ok = __all(ok);
                 if (ok) {
-                    Top2 mine = t;                          // the leader's own slice
-                    const int k = threadIdx.x;
-                    if (k >= TEAM_SIZE) {
-                        mine = Top2{NEG_HUGE, NEG_HUGE, 0x7fffffff, 0};
-                    } else if (k >= 1) {                    // one member's result per lane
-                        mine.b1 = __longlong_as_double((long long)load_fresh_u64(&ctl->partial[k][0]));
-                        mine.b2 = __longlong_as_double((long long)load_fresh_u64(&ctl->partial[k][1]));
-                        const unsigned long long iw = load_fresh_u64(&ctl->partial[k][2]);
-                        mine.idx = (int)(unsigned)(iw & 0xffffffffull);
-                        mine.w = (int)(unsigned)(iw >> 32);
-                    }
                     mine = wave_top2(mine);
                     if (threadIdx.x == 0) s_word = decide_and_bid(s, b, mine);
                 } else if (threadIdx.x == 0) {
