@@ -17,6 +17,14 @@ sys.path.insert(0, ROOT)
 MFMA_FP32_PEAK = 157.3e12      # MI355X dense fp32 matrix peak, flop/s
 HBM_PEAK = 8.0e12              # byte/s
 
+# HBM bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
+# what the same counters read for a 1 GiB copy), valid for the named kernel at the named workload
+# only.  Set an entry to None when its kernel changes after the counters were taken.
+MEASURED_TRAFFIC = {
+    ("C4", "pair_mlp_kernel"): 2.000e9,
+    ("C4", "round_kernel"): 1.609e9,
+}
+
 
 def cpu_baseline(r, Wg_block, sample_rows):
     """Times the CPU checker, as it stands, on a bounded sample of the same round."""
@@ -132,10 +140,16 @@ def main():
                     "primal": res.primal, "cert_ok": res.cert_ok},
         "roofline": {"bound": "mfma", "kernel": "pair_mlp_kernel", "achieved": achieved / 1e12,
                      "peak": MFMA_FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_FP32_PEAK,
-                     "traffic": None},
-        "roofline_bid_scan": {"bound": "hbm", "kernel": "bid_kernel (first round of each phase: every row bids)",
+                     "traffic": MEASURED_TRAFFIC.get((cfg.name, "pair_mlp_kernel"))},
+        "roofline_bid_scan": {"bound": "hbm", "kernel": "round_kernel (first round of each phase: every row bids)",
                               "achieved": bulk_bytes / (bulk_ms * 1e-3) / 1e9, "peak": HBM_PEAK / 1e9,
-                              "unit": "GB/s", "frac": bulk_bytes / (bulk_ms * 1e-3) / HBM_PEAK, "traffic": None},
+                              "unit": "GB/s", "frac": bulk_bytes / (bulk_ms * 1e-3) / HBM_PEAK,
+                              "traffic": MEASURED_TRAFFIC.get((cfg.name, "round_kernel"))},
+        # the chain-following kernels take most of the auction's time but are bound by the latency of
+        # dependent steps, not by bandwidth: reported as steps and microseconds per step
+        "auction_tail": {"kernels": "chain_kernel + team_kernel", "bound": "latency",
+                         "sequential_steps": res.chain_depth, "bids": res.chain_bids,
+                         "us_per_sequential_step": (avg["auction_ms"] * 1e3 / res.chain_depth) if res.chain_depth else None},
     }
     if not args.no_cpu:
         blk = min(args.cpu_block, n)
