@@ -861,7 +861,15 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
             hipLaunchKernelGGL(team_begin_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->stats,
                                (TeamCtl *)ctx->team_ctl, ring);
             const dim3 grid(teams * ctx->team_size);
-            if (ctx->team_threads == 256)
+            if (ctx->team_threads == 64)
+                hipLaunchKernelGGL(team_kernel<64>, grid, dim3(64), 0, ctx->stream, s, ctx->list[ring & 1],
+                                   ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
+                                   left / teams + 1, ctx->team_size);
+            else if (ctx->team_threads == 128)
+                hipLaunchKernelGGL(team_kernel<128>, grid, dim3(128), 0, ctx->stream, s, ctx->list[ring & 1],
+                                   ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
+                                   left / teams + 1, ctx->team_size);
+            else if (ctx->team_threads == 256)
                 hipLaunchKernelGGL(team_kernel<256>, grid, dim3(256), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
                                    left / teams + 1, ctx->team_size);
