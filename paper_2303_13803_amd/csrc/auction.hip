@@ -89,8 +89,20 @@ __device__ inline double load_fresh(const double *p)
 // Folds four consecutive entries (values v0..v3 at index j) into a running
 // top-2: a min/max network finds the group's best two, and only a group that
 // beats the running best pays for locating the entry.
+//
+// Ties.  Any entry attaining the best value is a correct choice, and "the
+// smallest index" sends every one of a set of identical bidders to the same
+// entry, where all but one lose.  Indices are therefore compared through a
+// per-bidder key, index ^ salt (salt below 2^20, so keys stay below 2^20 too):
+// identical bidders spread over tied entries.  Scans return the key; callers
+// undo it with the same xor.
+__device__ __forceinline__ int tie_salt(int bidder)
+{
+    return (int)(((unsigned)bidder * 2654435761u) >> 12) & 0xfffff;
+}
+
 __device__ __forceinline__ void top2_push4(double &b1, double &b2, int &idx, int &wbest, double v0,
-                                           double v1, double v2, double v3, int j, const int4 &w)
+                                           double v1, double v2, double v3, int j, const int4 &w, int salt)
 {
     const double hi0 = fmax(v0, v1), lo0 = fmin(v0, v1);
     const double hi1 = fmax(v2, v3), lo1 = fmin(v2, v3);
@@ -98,7 +110,7 @@ __device__ __forceinline__ void top2_push4(double &b1, double &b2, int &idx, int
     const double g2 = fmax(fmin(hi0, hi1), fmax(lo0, lo1));
     if (g1 > b1) {                                      // smallest index attaining the group's best
         const bool a0 = v0 == g1, a1 = v1 == g1, a2 = v2 == g1;
-        idx = j + (a0 ? 0 : a1 ? 1 : a2 ? 2 : 3);
+        idx = (j + (a0 ? 0 : a1 ? 1 : a2 ? 2 : 3)) ^ salt;
         wbest = a0 ? w.x : a1 ? w.y : a2 ? w.z : w.w;
     }
     b2 = fmax(fmax(b2, g2), fmin(b1, g1));
@@ -166,13 +178,14 @@ __device__ __forceinline__ Top2 wave_top2(const Top2 &t)
 }
 
 // Scans line A[0..len) against dual[0..len): best and second-best value of
-// K*w - dual, the smallest index attaining the best and its weight.  Every
-// thread of the NT-thread block must call it; the result is valid in thread 0.
+// K*w - dual, the entry attaining the best (as the key (index_base + position)
+// ^ salt, smallest key among ties) and its weight.  Every thread of the
+// NT-thread block must call it; the result is valid in thread 0.
 // A is 16-byte aligned and padded to a multiple of four entries, dual
 // likewise.  `fresh` re-reads the duals past the caches (block-uniform).
 template <int NT>
 __device__ inline Top2 block_scan(const int32_t *__restrict__ A, const double *__restrict__ dual,
-                                  int len, double Kd, bool fresh, Top2 *red)
+                                  int len, double Kd, bool fresh, Top2 *red, int index_base, int salt)
 {
     constexpr int UN = 4;               // independent load batches in flight per thread
     Top2 t{NEG_HUGE, NEG_HUGE, 0x7fffffff, 0};
@@ -201,7 +214,7 @@ __device__ inline Top2 block_scan(const int32_t *__restrict__ A, const double *_
             if (j < full)
                 top2_push4(t.b1, t.b2, t.idx, t.w, fma(Kd, (double)w[u].x, -p[u][0]),
                            fma(Kd, (double)w[u].y, -p[u][1]), fma(Kd, (double)w[u].z, -p[u][2]),
-                           fma(Kd, (double)w[u].w, -p[u][3]), j, w[u]);
+                           fma(Kd, (double)w[u].w, -p[u][3]), j + index_base, w[u], salt);
         }
     }
     if (full < len && (int)threadIdx.x == (full / 4) % NT) {   // the last, partial group
@@ -210,7 +223,7 @@ __device__ inline Top2 block_scan(const int32_t *__restrict__ A, const double *_
         for (int e = 0; e < 3; ++e) p[e] = fresh ? load_fresh(dual + full + e) : dual[full + e];
         top2_push4(t.b1, t.b2, t.idx, t.w, fma(Kd, (double)w.x, -p[0]),
                    full + 1 < len ? fma(Kd, (double)w.y, -p[1]) : NEG_HUGE,
-                   full + 2 < len ? fma(Kd, (double)w.z, -p[2]) : NEG_HUGE, NEG_HUGE, full, w);
+                   full + 2 < len ? fma(Kd, (double)w.z, -p[2]) : NEG_HUGE, NEG_HUGE, full + index_base, w, salt);
     }
     // waves that saw no entry skip the reduction (they share SIMDs with the busy ones)
     const bool busy = (int)(threadIdx.x & ~63u) * 4 < len;
@@ -231,7 +244,7 @@ __device__ inline Top2 block_scan(const int32_t *__restrict__ A, const double *_
 // entry (duals are 8 bytes, weights 4) and keeps RB + 2 loads in flight per
 // thread.  On return red[r] holds line r's result (a barrier has been passed).
 template <int NT, int RB>
-__device__ __forceinline__ void block_scan_rows(const int32_t *const (&rows)[RB],
+__device__ __forceinline__ void block_scan_rows(const int32_t *const (&rows)[RB], const int (&salt)[RB],
                                                 const double *__restrict__ dual, int len, double Kd,
                                                 Top2 *red)
 {
@@ -251,7 +264,7 @@ __device__ __forceinline__ void block_scan_rows(const int32_t *const (&rows)[RB]
         for (int r = 0; r < RB; ++r)
             top2_push4(b1[r], b2[r], idx[r], wb[r], fma(Kd, (double)w[r].x, -p01.x),
                        fma(Kd, (double)w[r].y, -p01.y), fma(Kd, (double)w[r].z, -p23.x),
-                       fma(Kd, (double)w[r].w, -p23.y), j, w[r]);
+                       fma(Kd, (double)w[r].w, -p23.y), j, w[r], salt[r]);
     }
     if (full < len && (int)threadIdx.x == (full / 4) % NT) {   // the last, partial group
         const double2 p01 = *(const double2 *)(dual + full);
@@ -261,7 +274,7 @@ __device__ __forceinline__ void block_scan_rows(const int32_t *const (&rows)[RB]
             const int4 w = *(const int4 *)(rows[r] + full);
             top2_push4(b1[r], b2[r], idx[r], wb[r], fma(Kd, (double)w.x, -p01.x),
                        full + 1 < len ? fma(Kd, (double)w.y, -p01.y) : NEG_HUGE,
-                       full + 2 < len ? fma(Kd, (double)w.z, -p23.x) : NEG_HUGE, NEG_HUGE, full, w);
+                       full + 2 < len ? fma(Kd, (double)w.z, -p23.x) : NEG_HUGE, NEG_HUGE, full, w, salt[r]);
         }
     }
     __syncthreads();                       // protect `red` from its previous use
@@ -329,18 +342,23 @@ __global__ __launch_bounds__(NT) void round_kernel(SideArgs s, const int *__rest
         }
     }
     for (int item = blockIdx.x * RB; item < count; item += gridDim.x * RB) {
-        int b[RB];
+        int salt[RB];
         const int32_t *rows[RB];
 #pragma unroll
         for (int r = 0; r < RB; ++r) {
-            b[r] = list[min(item + r, count - 1)];          // a short last group repeats its last line
-            rows[r] = s.A + (size_t)b[r] * s.pitch;
+            const int b = list[min(item + r, count - 1)];   // a short last group repeats its last line
+            rows[r] = s.A + (size_t)b * s.pitch;
+            salt[r] = tie_salt(b);
         }
-        block_scan_rows<NT, RB>(rows, s.other_dual, s.len, s.Kd, red);
+        block_scan_rows<NT, RB>(rows, salt, s.other_dual, s.len, s.Kd, red);
         if (threadIdx.x < 64) {                                      // first wavefront: one lane bids per line
             int again = -1;
-            if (threadIdx.x < RB && item + (int)threadIdx.x < count)
-                again = decide_and_bid(s, list[item + threadIdx.x], red[threadIdx.x]);
+            if (threadIdx.x < RB && item + (int)threadIdx.x < count) {
+                const int b = list[item + threadIdx.x];
+                Top2 t = red[threadIdx.x];
+                t.idx ^= tie_salt(b);
+                again = decide_and_bid(s, b, t);
+            }
             // one counter update per workgroup: the list counter is a single hot address
             const unsigned long long pushing = __ballot(again >= 0);
             if (pushing) {
@@ -393,8 +411,9 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const 
                 break;
             }
             ++steps;
-            const Top2 t = block_scan<CHAIN_THREADS>(s.A + (size_t)b * s.pitch, s.other_dual, s.len, s.Kd,
-                                                      fresh, red);
+            Top2 t = block_scan<CHAIN_THREADS>(s.A + (size_t)b * s.pitch, s.other_dual, s.len, s.Kd, fresh, red,
+                                               0, tie_salt(b));
+            t.idx ^= tie_salt(b);
             if (threadIdx.x == 0) s_next = decide_and_bid(s, b, t);
             __syncthreads();
             fresh = (s_next == b);
@@ -515,10 +534,10 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
             if (b < 0) break;                                   // stop (or abort)
             // a slice is small enough to stay in this compute unit's cache from step to step, so the
             // duals are always read past the caches here
-            const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch + off, s.other_dual + off,
-                                                      my_len, s.Kd, true, red);
+            const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch + off, s.other_dual + off, my_len, s.Kd,
+                                          true, red, off, tie_salt(b));
             if (threadIdx.x == 0) {
-                const int idx = t.idx == 0x7fffffff ? 0 : t.idx + off;
+                const int idx = t.idx == 0x7fffffff ? 0 : t.idx;      // already a key on the global index
                 store_through(&ctl->partial[member][0], tag_value(t.b1, expect));
                 store_through(&ctl->partial[member][1], tag_value(t.b2, expect));
                 store_through(&ctl->partial[member][2], ((unsigned long long)(unsigned)idx << 40) |
@@ -552,7 +571,8 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
             if (threadIdx.x == 0)
                 store_through(&ctl->cmd, ((unsigned long long)seq << 32) | (fresh ? 0x80000000ull : 0ull) |
                                              (unsigned long long)(b + 1));
-            const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch, s.other_dual, my_len, s.Kd, true, red);
+            const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch, s.other_dual, my_len, s.Kd, true, red, 0,
+                                          tie_salt(b));
             if (threadIdx.x < 64) {                         // first wavefront: one lane per member
                 const int k = threadIdx.x;
                 Top2 mine = t;                              // lane 0: the leader's own slice
@@ -579,6 +599,7 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
                 ok = __all(ok);
                 if (ok) {
                     mine = wave_top2(mine);
+                    mine.idx ^= tie_salt(b);
                     if (threadIdx.x == 0) s_word = decide_and_bid(s, b, mine);
                 } else if (threadIdx.x == 0) {
                     atomicExch(&ctl->abort, 1u);
@@ -710,7 +731,7 @@ __global__ __launch_bounds__(BID_THREADS) void duals_kernel(
 {
     __shared__ Top2 red[BID_THREADS / 64];
     for (int i = blockIdx.x; i < n; i += gridDim.x) {
-        const Top2 t = block_scan<BID_THREADS>(W + (size_t)i * ldw, price, m, Kd, false, red);
+        const Top2 t = block_scan<BID_THREADS>(W + (size_t)i * ldw, price, m, Kd, false, red, 0, 0);
         if (threadIdx.x == 0) {
             u[i] = (int64_t)fmax(t.b1, 0.0);
             out_row2col[i] = row2col[i];
