@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=192)
     ap.add_argument("--cpu-block", type=int, default=1536)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--update-rounds", type=int, default=3,
+                    help="also time this many follow-up rounds with --churn of the workloads replaced")
+    ap.add_argument("--churn", type=float, default=0.02)
     ap.add_argument("--calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (reference for hardware byte counters)")
     ap.add_argument("--opt", action="append", default=[], help="solver option name=value (repeatable)")
@@ -151,6 +154,29 @@ def main():
                          "sequential_steps": res.chain_depth, "bids": res.chain_bids,
                          "us_per_sequential_step": (avg["auction_ms"] * 1e3 / res.chain_depth) if res.chain_depth else None},
     }
+    if args.update_rounds > 0:
+        # follow-up rounds: a share of the online and offline workloads is replaced by fresh draws,
+        # only their rows/columns are re-scored and the matching starts from the previous prices
+        xo, xf = r["x_on"].copy(), r["x_off"].copy()
+        times, last = [], None
+        for k in range(args.update_rounds):
+            fresh = synth.scheduling_round(cfg, args.seed + 100 + k)
+            rows = np.sort(synth.permutation(args.seed + k, n, 3)[:max(1, int(args.churn * n))]).astype(np.int32)
+            cols = np.sort(synth.permutation(args.seed + k, m, 4)[:max(1, int(args.churn * m))]).astype(np.int32)
+            xo[rows] = fresh["x_on"][rows]; xf[cols] = fresh["x_off"][cols]
+            d_on, d_off, d_rows, d_cols = dev(xo), dev(xf), dev(rows), dev(cols)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            last = ctx.schedule_round_update(pred, d_on, d_off, d_rows, d_cols, W, r2c, u, v)
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - t0) * 1e3)
+            assert last.cert_ok == 1
+        tm = ctx.last_timings()
+        out["next_round_update"] = {"churn": args.churn, "rounds": args.update_rounds, "ms_per_round": float(np.mean(times)),
+                                    "ms_each": times, "auction_ms_last": tm["auction_ms"],
+                                    "rescore_ms_last": tm["pair_scoring_ms"] + tm["projections_ms"],
+                                    "phases_last": last.phases, "bids_last": last.bids,
+                                    "sequential_steps_last": last.chain_depth}
     if not args.no_cpu:
         blk = min(args.cpu_block, n)
         Wg_block = W[:blk, :min(m, blk * (m // n))].cpu().numpy()

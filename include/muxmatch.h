@@ -159,10 +159,40 @@ int mf_schedule_round(mf_ctx *ctx, const mf_predictor *pred,
                       int32_t *d_W, int64_t ldw,
                       int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
 
+/*
+ * The next scheduling round.  The scheduler is invoked periodically on a
+ * workload set that changes slowly (paper: Section "Implementation", "invokes
+ * the scheduler periodically to schedule all offline workloads"; Section
+ * "Evaluation", the 15-minute interval).  d_W must hold the matrix the previous
+ * round on this context scored for the same n and m; d_on / d_off hold the
+ * current features of all workloads; d_changed_on[n_changed_on] and
+ * d_changed_off[n_changed_off] (device arrays of distinct indices, may be
+ * empty) name the online / offline workloads whose features differ from that
+ * round (changed or replaced).  Only their rows and columns of d_W are
+ * re-scored; the matching is then solved again.  Outputs, certificate and
+ * error codes are those of mf_schedule_round: the result is the exact optimum
+ * of the updated matrix.  By default the matching starts from scratch; with
+ * the option "warm_eps_units" > 0 it starts from the previous round's column
+ * prices (those of the listed offline workloads reset to 0, unless
+ * "warm_reset_cols" is 0) at epsilon = warm_eps_units weight units - still
+ * exact, since every phase re-establishes its invariants from any non-negative
+ * prices, but measured no faster on the benchmark workloads.
+ * Index lists are checked on the device before use (MF_ERR_ARG if out of range).
+ */
+int mf_schedule_round_update(mf_ctx *ctx, const mf_predictor *pred,
+                             const float *d_on, int n, const float *d_off, int m,
+                             const int32_t *d_changed_on, int n_changed_on,
+                             const int32_t *d_changed_off, int n_changed_off,
+                             int32_t *d_W, int64_t ldw,
+                             int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
+
 /* Solver knobs: "theta" (epsilon divisor per phase, default 8), "max_rounds" (limit on
  * evaluated bids, default 4,000,000,000), "tail_max" (bidder count at or below which one
  * kernel follows the remaining eviction chains to their end, default 512), "chain_grid"
- * (workgroups of that kernel, default 256), "bulk_shape" (0..4: threads x lines per workgroup
+ * (workgroups of that kernel, default 256), "warm_eps_units" (0, the default: mf_schedule_round_update
+ * matches from scratch; > 0: from the previous prices at that epsilon, in weight units), "warm_reset_cols", "team_size" / "team_threads"
+ * (workgroups per chain and threads per workgroup of the kernel that shares chains, default
+ * 16 / 1024), "team_max" (chains at or below which it takes over, default 8), "bulk_shape" (0..4: threads x lines per workgroup
  * in rounds with many bidders: 256x1, 64x4 (default), 64x2, 128x4, 256x4). */
 int mf_set_option(mf_ctx *ctx, const char *name, int64_t value);
 

@@ -17,7 +17,7 @@ INFEASIBLE = -2147483648
 OK, ERR_ARG, ERR_SHAPE, ERR_HIP, ERR_NOT_CONVERGED, ERR_CERT, ERR_RANGE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["mf_create", "mf_destroy", "mf_score_pairs", "mf_solve_assignment",
-           "mf_check_certificate", "mf_schedule_round", "mf_set_option", "mf_last_timings",
+           "mf_check_certificate", "mf_schedule_round", "mf_schedule_round_update", "mf_set_option", "mf_last_timings",
            "mf_strerror", "mf_last_hip_error"]
 
 TIMING_NAMES = ["projections_ms", "pair_scoring_ms", "bulk_bid_ms", "bulk_bid_launches",
@@ -55,6 +55,8 @@ def load_library():
     lib.mf_check_certificate.argtypes = [vp, vp, i32, i32, i64, vp, vp, vp, i64, C.POINTER(Result)]
     lib.mf_schedule_round.argtypes = [vp, C.POINTER(Predictor), vp, i32, vp, i32, vp, i64, vp, vp, vp,
                                       C.POINTER(Result)]
+    lib.mf_schedule_round_update.argtypes = [vp, C.POINTER(Predictor), vp, i32, vp, i32, vp, i32, vp, i32, vp, i64,
+                                             vp, vp, vp, C.POINTER(Result)]
     lib.mf_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.mf_last_timings.argtypes = [vp, C.POINTER(C.c_float * 16)]
     lib.mf_strerror.argtypes = [i32]
@@ -151,6 +153,19 @@ class Context:
                                            _ptr(x_off, torch.float32), m, _ptr(W, torch.int32),
                                            W.stride(0), _ptr(row2col, torch.int32),
                                            _ptr(u, torch.int64), _ptr(v, torch.int64), C.byref(res)))
+        return res
+
+    def schedule_round_update(self, pred, x_on, x_off, changed_on, changed_off, W, row2col, u, v):
+        n, m = x_on.shape[0], x_off.shape[0]
+        res = Result()
+        self._check(_lib.mf_schedule_round_update(
+            self._h, C.byref(pred), _ptr(x_on, torch.float32), n, _ptr(x_off, torch.float32), m,
+            _ptr(changed_on, torch.int32) if changed_on is not None and changed_on.numel() else None,
+            0 if changed_on is None else changed_on.numel(),
+            _ptr(changed_off, torch.int32) if changed_off is not None and changed_off.numel() else None,
+            0 if changed_off is None else changed_off.numel(),
+            _ptr(W, torch.int32), W.stride(0), _ptr(row2col, torch.int32), _ptr(u, torch.int64),
+            _ptr(v, torch.int64), C.byref(res)))
         return res
 
     def last_timings(self):

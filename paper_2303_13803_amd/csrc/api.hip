@@ -69,6 +69,8 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->theta = 8;
     ctx->max_rounds = 4000000000ll;
     ctx->tail_max = 512;
+    ctx->warm_eps_units = 0;
+    ctx->warm_reset_cols = true;
     ctx->chain_grid = 256;
     ctx->bulk_shape = 1;
     ctx->team_max = 8;
@@ -145,7 +147,7 @@ int mf_solve_assignment(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t l
     MF_HIP(hipSetDevice(ctx->device));
     clear_timings(ctx);
     memset(h_res, 0, sizeof(*h_res));
-    rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res);
+    rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, false, nullptr, 0);
     h_res->status = rc;
     return rc;
 }
@@ -185,7 +187,37 @@ int mf_schedule_round(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, 
     clear_timings(ctx);
     memset(h_res, 0, sizeof(*h_res));
     rc = mf_launch_score(ctx, pred, d_on, n, d_off, m, d_W, ldw, nullptr);
-    if (rc == MF_OK) rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res);
+    if (rc == MF_OK) rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, false, nullptr, 0);
+    if (rc == MF_OK || rc == MF_ERR_CERT) {
+        int rt = finish_score_timing(ctx);
+        if (rt != MF_OK) rc = rt;
+    }
+    h_res->status = rc;
+    return rc;
+}
+
+int mf_schedule_round_update(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, int n,
+                             const float *d_off, int m, const int32_t *d_changed_on, int n_changed_on,
+                             const int32_t *d_changed_off, int n_changed_off, int32_t *d_W, int64_t ldw,
+                             int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res)
+{
+    if (!d_on || !d_off || !d_row2col || !d_u || !d_v || !h_res) return MF_ERR_ARG;
+    if (n_changed_on < 0 || n_changed_off < 0 || (n_changed_on > 0 && !d_changed_on) ||
+        (n_changed_off > 0 && !d_changed_off))
+        return MF_ERR_ARG;
+    int rc = check_matrix(ctx, d_W, n, m, ldw);
+    if (rc != MF_OK) return rc;
+    rc = check_predictor(pred);
+    if (rc != MF_OK) return rc;
+    if (n_changed_on > n || n_changed_off > m) return MF_ERR_SHAPE;
+    MF_HIP(hipSetDevice(ctx->device));
+    clear_timings(ctx);
+    memset(h_res, 0, sizeof(*h_res));
+    rc = mf_launch_rescore(ctx, pred, d_on, n, d_off, m, d_W, ldw, d_changed_on, n_changed_on,
+                           d_changed_off, n_changed_off);
+    if (rc == MF_OK)
+        rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, ctx->warm_eps_units > 0, d_changed_off,
+                           ctx->warm_reset_cols ? n_changed_off : 0);
     if (rc == MF_OK || rc == MF_ERR_CERT) {
         int rt = finish_score_timing(ctx);
         if (rt != MF_OK) rc = rt;
@@ -200,6 +232,8 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "theta")) { if (value < 2 || value > 1024) return MF_ERR_ARG; ctx->theta = value; return MF_OK; }
     if (!strcmp(name, "tail_max")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->tail_max = (int)value; return MF_OK; }
     if (!strcmp(name, "bulk_shape")) { if (value < 0 || value > 4) return MF_ERR_ARG; ctx->bulk_shape = (int)value; return MF_OK; }
+    if (!strcmp(name, "warm_reset_cols")) { ctx->warm_reset_cols = value != 0; return MF_OK; }
+    if (!strcmp(name, "warm_eps_units")) { if (value < 0 || value > (1 << 30)) return MF_ERR_ARG; ctx->warm_eps_units = value; return MF_OK; }
     if (!strcmp(name, "team_max")) { if (value < 0 || value > 16) return MF_ERR_ARG; ctx->team_max = (int)value; return MF_OK; }
     if (!strcmp(name, "team_size")) { if (value < 2 || value > 32) return MF_ERR_ARG; ctx->team_size = (int)value; return MF_OK; }
     if (!strcmp(name, "team_threads")) { if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return MF_ERR_ARG; ctx->team_threads = (int)value; return MF_OK; }

@@ -820,11 +820,18 @@ __global__ void init_cert_kernel(mf_cert_out *out)
     out->primal = 0; out->dual = 0; out->min_rc = INT64_MAX; out->matched = 0; out->flags = 0;
 }
 
-__global__ void init_solver_kernel(int n, int m, double *price, double *profit, mf_device_stats *stats)
+__global__ void zero_listed_kernel(double *price, const int32_t *__restrict__ which, int count, int m)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count && which[i] >= 0 && which[i] < m) price[which[i]] = 0.0;
+}
+
+__global__ void init_solver_kernel(int n, int m, double *price, double *profit, mf_device_stats *stats,
+                                   int keep_prices)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n + 4) profit[i] = 0.0;
-    if (i < m + 4) price[i] = 0.0;
+    if (i < m + 4 && (!keep_prices || i >= m)) price[i] = 0.0;
     if (i == 0) {
         stats->rounds = 0; stats->bids = 0; stats->bytes = 0; stats->head = 0;
         stats->chain_bids = 0; stats->chain_depth = 0; stats->launch_max = 0; stats->chain_retries = 0; stats->team_bids = 0; stats->team_abort = 0; stats->active = 0; stats->max_weight = 0;
@@ -946,9 +953,17 @@ int mf_run_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ld
     return MF_OK;
 }
 
+// `warm`: start from the prices the previous solve of the same shape left in
+// the context (those of the columns listed in d_reset_cols set to 0) and from a
+// small epsilon.  Any non-negative starting prices are valid - every phase
+// drops the assignment and re-establishes its invariants - so this changes
+// only how much work the phases have to do.
 int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
-                  int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res)
+                  int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res,
+                  bool warm, const int32_t *d_reset_cols, int n_reset_cols)
 {
+    warm = warm && ctx->warm_n == n && ctx->warm_m == m;
+    ctx->warm_n = ctx->warm_m = 0;
     const int64_t ldt = ((int64_t)n + 3) & ~3ll;
     const long long K = (long long)n + 1;
     const double Kd = (double)K;
@@ -956,7 +971,10 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
 
     MF_HIP(hipEventRecord(ctx->ev[3], ctx->stream));
     hipLaunchKernelGGL(init_solver_kernel, dim3((nm + 4 + 255) / 256), dim3(256), 0, ctx->stream, n, m,
-                       ctx->price, ctx->profit, ctx->stats);
+                       ctx->price, ctx->profit, ctx->stats, warm ? 1 : 0);
+    if (warm && n_reset_cols > 0)
+        hipLaunchKernelGGL(zero_listed_kernel, dim3((n_reset_cols + 255) / 256), dim3(256), 0, ctx->stream,
+                           ctx->price, d_reset_cols, n_reset_cols, m);
     hipLaunchKernelGGL(transpose_kernel, dim3((m + 63) / 64, (n + 63) / 64), dim3(256), 0, ctx->stream,
                        d_W, n, m, ldw, ctx->wt, ldt, ctx->stats);
     MF_HIP(hipGetLastError());
@@ -975,6 +993,7 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     SideArgs rev{ctx->wt, (long long)ldt, n, ctx->profit, ctx->roword, 0.0, Kd};
 
     long long eps = cmax / ctx->theta;
+    if (warm && ctx->warm_eps_units * K < eps) eps = ctx->warm_eps_units * K;
     if (eps < 1) eps = 1;
     int phases = 0;
     for (;;) {
@@ -1038,5 +1057,6 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     h_res->phases = phases;
     h_res->ms_solve = ms_solve;
     h_res->ms_certify = ms_duals + ms_cert;
+    if (h_res->cert_ok) { ctx->warm_n = n; ctx->warm_m = m; }      // these prices may seed the next solve
     return h_res->cert_ok ? MF_OK : MF_ERR_CERT;
 }

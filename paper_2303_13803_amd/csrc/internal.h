@@ -61,6 +61,9 @@ struct mf_ctx {
     double *price, *profit;         // [max_m+4], [max_n+4]: exact integers held in doubles
     unsigned long long *colword, *roword;
     int *row2col, *col2row;
+    int warm_n, warm_m;             // shape of the solve whose prices the context still holds (0: none)
+    bool warm_reset_cols;           // start replaced columns at price 0 instead of their predecessor's price
+    int64_t warm_eps_units;         // first epsilon of a warm-started solve, in weight units
     int tail_max;                   // bidder count at or below which chains are followed in one kernel
     int bulk_shape;                 // workgroup shape of rounds with many bidders (see launch_round)
     int team_max;                   // chains at or below which several workgroups share each chain (0: never)
@@ -86,9 +89,13 @@ struct mf_ctx {
 // score.hip
 int mf_launch_score(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, int n,
                     const float *d_off, int m, int32_t *d_W, int64_t ldw, float *d_sigma);
+int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, int n, const float *d_off,
+                      int m, int32_t *d_W, int64_t ldw, const int32_t *d_rows, int n_rows,
+                      const int32_t *d_cols, int n_cols);
 // auction.hip
 int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
-                  int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
+                  int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res,
+                  bool warm, const int32_t *d_reset_cols, int n_reset_cols);
 int mf_run_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
                        const int32_t *d_row2col, const int64_t *d_u, const int64_t *d_v,
                        int64_t K, mf_result *h_res);

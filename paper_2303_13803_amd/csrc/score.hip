@@ -46,7 +46,10 @@ template <int H> struct PairShape {
 };
 
 // One wavefront owns 32 offline columns (lane & 31) and walks down the online
-// rows of the tile.  v_mfma_f32_32x32x2_f32 computes D[32x32] += A[32x2] B[2x32]
+// rows of the tile.  n and m count the rows and columns to score; with
+// row_map / col_map (either may be null) entry t of the map names the online
+// row / offline column that tile position t stands for, so a scattered subset
+// of rows or columns can be re-scored in place.  v_mfma_f32_32x32x2_f32 computes D[32x32] += A[32x2] B[2x32]
 // with lane l supplying A[l%32][l/32] and B[l/32][l%32]; we let the two k
 // slots of step s be hidden features s and H/2 + s, so each half-wave streams
 // a contiguous half of the projections.  Accumulator register r of lane l is
@@ -57,7 +60,8 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     const float *__restrict__ W2, const float *__restrict__ b2, const float *__restrict__ W3,
     const float *__restrict__ b3, const float *__restrict__ mem_on,
     const float *__restrict__ mem_off, int n, int m, float scale, float mem_limit,
-    int32_t *__restrict__ W, int64_t ldw, float *__restrict__ sigma)
+    int32_t *__restrict__ W, int64_t ldw, float *__restrict__ sigma,
+    const int32_t *__restrict__ row_map, const int32_t *__restrict__ col_map)
 {
     using S = PairShape<H>;
     constexpr int KS = S::KS, MB = S::MB, ROWS = S::ROWS, Q = KS / 4;
@@ -81,14 +85,17 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
         int ln = idx & 63, s4 = (idx >> 6) % Q, mb = idx / (64 * Q);
         a_lds[idx] = *(const float4 *)(W2 + (size_t)(mb * 32 + (ln & 31)) * H + (ln >> 5) * KS + s4 * 4);
     }
-    for (int idx = tid; idx < nrows * (H / 4); idx += PAIR_THREADS)
-        ((float4 *)pon_lds)[idx] = ((const float4 *)(P_on + (size_t)row0 * H))[idx];
+    for (int idx = tid; idx < nrows * (H / 4); idx += PAIR_THREADS) {
+        const int r = idx / (H / 4), q = idx % (H / 4);
+        const int gi = row_map ? row_map[row0 + r] : row0 + r;
+        ((float4 *)pon_lds)[idx] = ((const float4 *)(P_on + (size_t)gi * H))[q];
+    }
     if (tid < H) { b2_lds[tid] = b2[tid]; w3_lds[tid] = W3[tid]; }
     __syncthreads();
     if (j0 >= m) return;
 
     const int j = j0 + nn;
-    const int jc = min(j, m - 1);
+    const int jc = col_map ? col_map[min(j, m - 1)] : min(j, m - 1);     // the column this lane scores
     float poff[KS];
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
@@ -145,21 +152,21 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
         const float z = zp + __shfl_xor(zp, 32) + bias3;
         const float sg = 1.0f / (1.0f + expf(-z));
         if (hh == 0 && j < m) {
-            const int i = row0 + r;
+            const int i = row_map ? row_map[row0 + r] : row0 + r;
             float q = rintf(sg * scale);
             q = fminf(fmaxf(q, 0.0f), scale);
             int32_t w = (int32_t)q;
             const float memsum = mem_on[i] + moff;
             if (memsum > mem_limit) w = MF_INFEASIBLE;
-            W[(size_t)i * ldw + j] = w;
-            if (sigma) sigma[(size_t)i * m + j] = sg;
+            W[(size_t)i * ldw + jc] = w;
+            if (sigma) sigma[(size_t)i * m + jc] = sg;
         }
     }
 }
 
 template <int H>
 int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
-                float *d_sigma)
+                float *d_sigma, const int32_t *row_map, const int32_t *col_map)
 {
     using S = PairShape<H>;
     static bool configured = false;
@@ -172,7 +179,7 @@ int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, 
     dim3 grid((((n + S::ROWS - 1) / S::ROWS) + 7) & ~7, (m + PAIR_COLS - 1) / PAIR_COLS);
     hipLaunchKernelGGL(pair_mlp_kernel<H>, grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
                        ctx->proj_on, ctx->proj_off, p->d_W2, p->d_b2, p->d_W3, p->d_b3,
-                       ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma);
+                       ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma, row_map, col_map);
     MF_HIP(hipGetLastError());
     return MF_OK;
 }
@@ -195,8 +202,65 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int n
         MF_HIP(hipGetLastError());
     }
     MF_HIP(hipEventRecord(ctx->ev[1], ctx->stream));
-    int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, d_W, ldw, d_sigma)
-                       : launch_pair<128>(ctx, p, n, m, d_W, ldw, d_sigma);
+    int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, d_W, ldw, d_sigma, nullptr, nullptr)
+                       : launch_pair<128>(ctx, p, n, m, d_W, ldw, d_sigma, nullptr, nullptr);
+    if (rc != MF_OK) return rc;
+    MF_HIP(hipEventRecord(ctx->ev[2], ctx->stream));
+    ctx->score_pending = true;
+    return MF_OK;
+}
+
+namespace {
+
+__global__ void fill_flag_kernel(int *flag) { *flag = 0; }
+
+__global__ void check_indices_kernel(const int32_t *__restrict__ list, int count, int limit, int *bad)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count && (list[i] < 0 || list[i] >= limit)) atomicExch(bad, 1);
+}
+
+}  // namespace
+
+// Re-scores, in place, the rows of the listed online workloads and the columns
+// of the listed offline workloads (device index lists).  Projections are
+// recomputed for everybody (they cost 2(n+m)FH flop); the pair kernel then runs
+// on `n_rows x m` and `n x n_cols` through its index maps.
+int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int n, const float *d_off,
+                      int m, int32_t *d_W, int64_t ldw, const int32_t *d_rows, int n_rows,
+                      const int32_t *d_cols, int n_cols)
+{
+    const int H = p->H, F = p->F;
+    // the lists index device arrays: refuse anything out of range before a kernel trusts it
+    hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->colmark);
+    if (n_rows > 0)
+        hipLaunchKernelGGL(check_indices_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, ctx->stream, d_rows,
+                           n_rows, n, ctx->colmark);
+    if (n_cols > 0)
+        hipLaunchKernelGGL(check_indices_kernel, dim3((n_cols + 255) / 256), dim3(256), 0, ctx->stream, d_cols,
+                           n_cols, m, ctx->colmark);
+    MF_HIP(hipGetLastError());
+    int bad = 0;
+    MF_HIP(hipMemcpyAsync(&bad, ctx->colmark, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    MF_HIP(hipStreamSynchronize(ctx->stream));
+    if (bad) return MF_ERR_ARG;
+    MF_HIP(hipEventRecord(ctx->ev[0], ctx->stream));
+    long tot = (long)n * H;
+    hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
+                       d_on, n, F, p->d_W1, 0, p->d_b1, H, ctx->proj_on, p->mem_feature, ctx->mem_on);
+    tot = (long)m * H;
+    hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
+                       d_off, m, F, p->d_W1, F, (const float *)nullptr, H, ctx->proj_off,
+                       p->mem_feature, ctx->mem_off);
+    MF_HIP(hipGetLastError());
+    MF_HIP(hipEventRecord(ctx->ev[1], ctx->stream));
+    int rc = MF_OK;
+    if (n_rows > 0)
+        rc = (H == 64) ? launch_pair<64>(ctx, p, n_rows, m, d_W, ldw, nullptr, d_rows, nullptr)
+                       : launch_pair<128>(ctx, p, n_rows, m, d_W, ldw, nullptr, d_rows, nullptr);
+    if (rc == MF_OK && n_cols > 0)
+        rc = (H == 64) ? launch_pair<64>(ctx, p, n, n_cols, d_W, ldw, nullptr, nullptr, d_cols)
+                       : launch_pair<128>(ctx, p, n, n_cols, d_W, ldw, nullptr, nullptr, d_cols);
     if (rc != MF_OK) return rc;
     MF_HIP(hipEventRecord(ctx->ev[2], ctx->stream));
     ctx->score_pending = true;
