@@ -47,7 +47,7 @@ extern "C" {
 enum {
     MF_OK = 0,
     MF_ERR_ARG = -1,            /* null pointer, non-positive size, bad pitch or alignment   */
-    MF_ERR_SHAPE = -2,          /* n > m, or a size beyond what the context was created for  */
+    MF_ERR_SHAPE = -2,          /* a size beyond what the context was created for            */
     MF_ERR_HIP = -3,            /* a HIP runtime call failed (see mf_last_hip_error)         */
     MF_ERR_NOT_CONVERGED = -4,  /* the solver hit its round limit                            */
     MF_ERR_CERT = -5,           /* the optimality certificate did not verify                 */
@@ -86,7 +86,7 @@ typedef struct {
 typedef struct {
     int64_t primal;             /* P: sum of matched weights (weight units)             */
     int64_t dual;               /* D: sum u + sum v (1/K weight units)                  */
-    int64_t K;                  /* dual scale, K = n + 1                                */
+    int64_t K;                  /* dual scale, K = min(n, m) + 1                        */
     int64_t min_reduced_cost;   /* min over feasible (i,j) of u_i + v_j - K*W_ij        */
     int64_t rounds;             /* bidding kernels run (forward + reverse)              */
     int64_t bids;               /* bids evaluated: each scans one row or column         */
@@ -106,7 +106,7 @@ typedef struct {
 /*
  * Creates a context bound to HIP device `device` and to `hip_stream` (a
  * hipStream_t passed as void*, NULL = the default stream).  Allocates all
- * scratch for problems up to max_n x max_m (max_n <= max_m <= 2^20 - 2):
+ * scratch for problems up to max_n x max_m (each at most 2^20 - 2):
  * layer-1 projections, a transposed copy of the weight matrix
  * (4*max_n*max_m bytes) and O(max_n + max_m) solver state.
  * Fails with MF_ERR_HIP when no such device exists or memory runs out.
@@ -127,7 +127,9 @@ int mf_score_pairs(mf_ctx *ctx, const mf_predictor *pred,
 
 /*
  * GetMatching of the scheduling algorithm: a maximum-weight matching of the
- * bipartite graph given by d_W (n <= m).  A matching is a set of feasible
+ * bipartite graph given by d_W (any n, m: when there are more online than
+ * offline workloads the solver works on the transposed problem and maps the
+ * result back).  A matching is a set of feasible
  * pairs using each row and each column at most once; it need not be perfect.
  * Outputs (device): d_row2col[n] (partner column, -1 = none) and integral
  * duals d_u[n], d_v[m] in units of 1/K of a weight unit that satisfy

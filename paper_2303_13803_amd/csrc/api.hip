@@ -16,7 +16,7 @@ bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 int check_matrix(const mf_ctx *ctx, const void *d_W, int n, int m, int64_t ldw)
 {
     if (!ctx || !d_W || n <= 0 || m <= 0 || ldw < m || (ldw & 3) || !aligned16(d_W)) return MF_ERR_ARG;
-    if (n > m || n > ctx->max_n || m > ctx->max_m) return MF_ERR_SHAPE;
+    if (n > ctx->max_n || m > ctx->max_m) return MF_ERR_SHAPE;
     return MF_OK;
 }
 
@@ -54,7 +54,7 @@ extern "C" {
 
 int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
 {
-    if (!out || max_n <= 0 || max_m <= 0 || max_n > max_m || max_m > MF_MAX_DIM) return MF_ERR_ARG;
+    if (!out || max_n <= 0 || max_m <= 0 || max_n > MF_MAX_DIM || max_m > MF_MAX_DIM) return MF_ERR_ARG;
     *out = nullptr;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return MF_ERR_HIP;
@@ -76,7 +76,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->team_max = 8;
     ctx->team_size = 16;
     ctx->team_threads = 1024;
-    const size_t nm = (size_t)max_m;                      // max_m >= max_n
+    const size_t nm = (size_t)(max_n > max_m ? max_n : max_m);   // either side may be the one that bids first
     const size_t ldt = ((size_t)max_n + 3) & ~(size_t)3;
     hipError_t e = hipSuccess;
 #define TRY(x) do { if (e == hipSuccess) e = (x); } while (0)
@@ -85,12 +85,12 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->mem_on, (size_t)max_n));
     TRY(dev_alloc(&ctx->mem_off, (size_t)max_m));
     TRY(dev_alloc(&ctx->wt, (size_t)max_m * ldt));
-    TRY(dev_alloc(&ctx->price, (size_t)max_m + 8));
-    TRY(dev_alloc(&ctx->profit, (size_t)max_n + 8));
-    TRY(dev_alloc(&ctx->colword, (size_t)max_m));
-    TRY(dev_alloc(&ctx->roword, (size_t)max_n));
-    TRY(dev_alloc(&ctx->row2col, (size_t)max_n));
-    TRY(dev_alloc(&ctx->col2row, (size_t)max_m));
+    TRY(dev_alloc(&ctx->price, nm + 8));
+    TRY(dev_alloc(&ctx->profit, nm + 8));
+    TRY(dev_alloc(&ctx->colword, nm));
+    TRY(dev_alloc(&ctx->roword, nm));
+    TRY(dev_alloc(&ctx->row2col, nm));
+    TRY(dev_alloc(&ctx->col2row, nm));
     TRY(hipMalloc(&ctx->team_ctl, 32 * 1024));
     TRY(dev_alloc(&ctx->list[0], nm));
     TRY(dev_alloc(&ctx->list[1], nm));
@@ -258,7 +258,7 @@ const char *mf_strerror(int code)
     switch (code) {
     case MF_OK: return "ok";
     case MF_ERR_ARG: return "bad argument (null pointer, non-positive size, pitch or alignment)";
-    case MF_ERR_SHAPE: return "shape not supported (n > m, or larger than the context)";
+    case MF_ERR_SHAPE: return "shape larger than the context was created for";
     case MF_ERR_HIP: return "HIP runtime error";
     case MF_ERR_NOT_CONVERGED: return "round limit reached before the auction finished";
     case MF_ERR_CERT: return "optimality certificate did not verify";

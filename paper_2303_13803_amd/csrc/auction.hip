@@ -6,8 +6,8 @@
 // same optimum is reached by an epsilon-scaling forward/reverse auction, whose
 // unit of work - "scan one line of the weight matrix against the current duals
 // and keep the best two" - is a coalesced streaming read, and whose updates are
-// 64-bit atomic maxima.  Weights are multiplied by K = n + 1 so that the final
-// epsilon = 1 is below 1/n of a weight unit: the matching is then exactly
+// 64-bit atomic maxima.  Weights are multiplied by K = min(n, m) + 1 so that the final
+// epsilon = 1 is below 1/min(n, m) of a weight unit: the matching is then exactly
 // optimal, and the duals it leaves behind prove it (see certificate_kernel).
 //
 // Formulation.  maximise sum W_ij x_ij, every row and column used at most
@@ -16,7 +16,7 @@
 //   (I1) pi_i + p_j >= K W_ij - eps on every feasible pair,
 //   (I2) pi_i + p_j  = K W_ij      on every assigned pair,
 // and stops a phase when every unassigned row has pi_i = 0 and every
-// unassigned column has p_j = 0; then the assignment is within n*eps of the
+// unassigned column has p_j = 0; then the assignment is within min(n, m)*eps of the
 // optimum.  A forward round lets unassigned rows raise prices p; a reverse
 // round lets unassigned columns that still carry a positive price raise
 // profits pi (and lower their own price).  Both are the same computation with
@@ -815,6 +815,13 @@ __global__ void fill_int_kernel(int *p, int count, int value)
     if (i < count) p[i] = value;
 }
 
+// to[from[i]] = i for every i with a partner; `to` was filled with -1 before.
+__global__ void invert_map_kernel(const int32_t *__restrict__ from, int count, int32_t *to)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count && from[i] >= 0) to[from[i]] = i;
+}
+
 __global__ void init_cert_kernel(mf_cert_out *out)
 {
     out->primal = 0; out->dual = 0; out->min_rc = INT64_MAX; out->matched = 0; out->flags = 0;
@@ -962,15 +969,24 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
                   int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res,
                   bool warm, const int32_t *d_reset_cols, int n_reset_cols)
 {
-    warm = warm && ctx->warm_n == n && ctx->warm_m == m;
+    // The side with fewer lines bids first ("rows" below); with more online than
+    // offline workloads the roles of the matrix and its transposed copy swap and
+    // the results are mapped back at the end.
+    const bool flip = n > m;
+    warm = warm && !flip && ctx->warm_n == n && ctx->warm_m == m;
     ctx->warm_n = ctx->warm_m = 0;
     const int64_t ldt = ((int64_t)n + 3) & ~3ll;
-    const long long K = (long long)n + 1;
+    const int rn = flip ? m : n, rm = flip ? n : m;
+    const int32_t *A = flip ? ctx->wt : d_W;
+    const int64_t lda = flip ? ldt : ldw;
+    const int32_t *At = flip ? d_W : ctx->wt;
+    const int64_t ldat = flip ? ldw : ldt;
+    const long long K = (long long)rn + 1;
     const double Kd = (double)K;
-    const int nm = n > m ? n : m;
+    const int nm = rm;
 
     MF_HIP(hipEventRecord(ctx->ev[3], ctx->stream));
-    hipLaunchKernelGGL(init_solver_kernel, dim3((nm + 4 + 255) / 256), dim3(256), 0, ctx->stream, n, m,
+    hipLaunchKernelGGL(init_solver_kernel, dim3((nm + 4 + 255) / 256), dim3(256), 0, ctx->stream, rn, rm,
                        ctx->price, ctx->profit, ctx->stats, warm ? 1 : 0);
     if (warm && n_reset_cols > 0)
         hipLaunchKernelGGL(zero_listed_kernel, dim3((n_reset_cols + 255) / 256), dim3(256), 0, ctx->stream,
@@ -989,8 +1005,8 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     const long long cmax = K * (long long)ctx->h_stats->max_weight;
     if (cmax >= MF_MAX_DUAL) return MF_ERR_RANGE;
 
-    SideArgs fwd{d_W, (long long)ldw, m, ctx->price, ctx->colword, 0.0, Kd};
-    SideArgs rev{ctx->wt, (long long)ldt, n, ctx->profit, ctx->roword, 0.0, Kd};
+    SideArgs fwd{A, (long long)lda, rm, ctx->price, ctx->colword, 0.0, Kd};
+    SideArgs rev{At, (long long)ldat, rn, ctx->profit, ctx->roword, 0.0, Kd};
 
     long long eps = cmax / ctx->theta;
     if (warm && ctx->warm_eps_units * K < eps) eps = ctx->warm_eps_units * K;
@@ -999,16 +1015,16 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     for (;;) {
         ++phases;
         fwd.eps = rev.eps = (double)eps;
-        hipLaunchKernelGGL(reset_kernel, dim3((nm + 255) / 256), dim3(256), 0, ctx->stream, n, m, ctx->price,
+        hipLaunchKernelGGL(reset_kernel, dim3((nm + 255) / 256), dim3(256), 0, ctx->stream, rn, rm, ctx->price,
                            ctx->colword, ctx->row2col, ctx->col2row, ctx->list[0], ctx->stats);
-        int rc = run_side(ctx, fwd, n, true);
+        int rc = run_side(ctx, fwd, rn, true);
         if (rc != MF_OK) return rc;
         // who holds what after the forward rounds; unassigned priced columns go to list[0]
         hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats);
-        hipLaunchKernelGGL(forward_done_rows_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, n,
+        hipLaunchKernelGGL(forward_done_rows_kernel, dim3((rn + 255) / 256), dim3(256), 0, ctx->stream, rn,
                            ctx->profit, ctx->roword, ctx->row2col);
-        hipLaunchKernelGGL(forward_done_cols_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, m,
-                           d_W, ldw, Kd, ctx->colword, ctx->price, ctx->profit, ctx->roword, ctx->row2col,
+        hipLaunchKernelGGL(forward_done_cols_kernel, dim3((rm + 255) / 256), dim3(256), 0, ctx->stream, rm,
+                           A, lda, Kd, ctx->colword, ctx->price, ctx->profit, ctx->roword, ctx->row2col,
                            ctx->col2row, ctx->list[0], ctx->stats);
         MF_HIP(hipGetLastError());
         MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
@@ -1017,10 +1033,10 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         if (rev_count > 0) {
             rc = run_side(ctx, rev, rev_count, false);
             if (rc != MF_OK) return rc;
-            hipLaunchKernelGGL(reverse_done_cols_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, m,
+            hipLaunchKernelGGL(reverse_done_cols_kernel, dim3((rm + 255) / 256), dim3(256), 0, ctx->stream, rm,
                                ctx->price, ctx->col2row);
-            hipLaunchKernelGGL(reverse_done_rows_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, n,
-                               d_W, ldw, Kd, ctx->roword, ctx->price, ctx->row2col, ctx->col2row);
+            hipLaunchKernelGGL(reverse_done_rows_kernel, dim3((rn + 255) / 256), dim3(256), 0, ctx->stream, rn,
+                               A, lda, Kd, ctx->roword, ctx->price, ctx->row2col, ctx->col2row);
             MF_HIP(hipGetLastError());
         }
         if (eps == 1) break;
@@ -1029,9 +1045,19 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     }
     MF_HIP(hipEventRecord(ctx->ev[4], ctx->stream));
     {
-        const int grid = n < MAX_GRID ? n : MAX_GRID;
-        hipLaunchKernelGGL(duals_kernel, dim3(grid), dim3(BID_THREADS), 0, ctx->stream, d_W, ldw, n, m,
-                           ctx->price, ctx->row2col, Kd, d_row2col, d_u, d_v);
+        const int grid = rn < MAX_GRID ? rn : MAX_GRID;
+        if (!flip) {
+            hipLaunchKernelGGL(duals_kernel, dim3(grid), dim3(BID_THREADS), 0, ctx->stream, A, lda, rn, rm,
+                               ctx->price, ctx->row2col, Kd, d_row2col, d_u, d_v);
+        } else {
+            // bidders were the offline workloads: their duals are v, and list[0] takes
+            // their partners until the map is inverted into the caller's row2col
+            hipLaunchKernelGGL(duals_kernel, dim3(grid), dim3(BID_THREADS), 0, ctx->stream, A, lda, rn, rm,
+                               ctx->price, ctx->row2col, Kd, ctx->list[0], d_v, d_u);
+            hipLaunchKernelGGL(fill_int_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, d_row2col, n, -1);
+            hipLaunchKernelGGL(invert_map_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream,
+                               ctx->list[0], m, d_row2col);
+        }
         MF_HIP(hipGetLastError());
     }
     MF_HIP(hipEventRecord(ctx->ev[5], ctx->stream));

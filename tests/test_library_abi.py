@@ -40,7 +40,7 @@ def test_error_strings_and_argument_checks_without_a_device():
     assert binding.strerror(-99) == "unknown error"
     handle = C.c_void_p()
     assert lib.mf_create(None, 0, None, 4, 4) == binding.ERR_ARG              # no place for the handle
-    assert lib.mf_create(C.byref(handle), 0, None, 8, 4) == binding.ERR_ARG   # more rows than columns
+    assert lib.mf_create(C.byref(handle), 0, None, 4, 1 << 20) == binding.ERR_ARG   # beyond the id field of a packed word
     assert lib.mf_create(C.byref(handle), 0, None, 0, 4) == binding.ERR_ARG
     assert lib.mf_destroy(None) == binding.ERR_ARG
     assert lib.mf_set_option(None, b"theta", 8) == binding.ERR_ARG
