@@ -119,7 +119,9 @@ def main():
     avg = {k: float(np.mean([s[1][k] for s in stages])) for k in stages[0][1]}
 
     pair_ms = avg["pair_scoring_ms"]
-    flops = 2.0 * cfg.H * cfg.H * n * m                      # hidden-layer MFMA flops of one launch
+    # hidden-layer MFMA flops one launch issues: pairs that cannot fit in memory get no MLP pass
+    evaluated = avg["pairs_evaluated_fraction"]
+    flops = 2.0 * cfg.H * cfg.H * n * m * evaluated
     achieved = flops / (pair_ms * 1e-3)
     bulk_launches = max(avg["bulk_bid_launches"], 1.0)
     bulk_bytes = avg["bulk_bid_bytes"] / bulk_launches
@@ -143,6 +145,7 @@ def main():
                     "primal": res.primal, "cert_ok": res.cert_ok},
         "roofline": {"bound": "mfma", "kernel": "pair_mlp_kernel", "achieved": achieved / 1e12,
                      "peak": MFMA_FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_FP32_PEAK,
+                     "pairs_evaluated_fraction": evaluated,
                      "traffic": MEASURED_TRAFFIC.get((cfg.name, "pair_mlp_kernel"))},
         "roofline_bid_scan": {"bound": "hbm", "kernel": "round_kernel (first round of each phase: every row bids)",
                               "achieved": bulk_bytes / (bulk_ms * 1e-3) / 1e9, "peak": HBM_PEAK / 1e9,

@@ -120,6 +120,9 @@ int mf_destroy(mf_ctx *ctx);
  * d_on is [n][F], d_off is [m][F] float32 (device).  If d_sigma is not NULL
  * it must hold n*m floats and receives the unquantised score of every pair
  * (pitch m).  Padding columns [m, ldw) are left untouched.
+ * Without d_sigma the kernel walks rows and columns in order of their memory
+ * fraction and leaves out the MLP for pairs that cannot fit (option
+ * "fit_order", default 1); d_W is the same either way.
  */
 int mf_score_pairs(mf_ctx *ctx, const mf_predictor *pred,
                    const float *d_on, int n, const float *d_off, int m,
@@ -195,16 +198,20 @@ int mf_schedule_round_update(mf_ctx *ctx, const mf_predictor *pred,
  * matches from scratch; > 0: from the previous prices at that epsilon, in weight units), "warm_reset_cols", "team_size" / "team_threads"
  * (workgroups per chain and threads per workgroup of the kernel that shares chains, default
  * 16 / 1024), "team_max" (chains at or below which it takes over, default 8), "bulk_shape" (0..4: threads x lines per workgroup
- * in rounds with many bidders: 256x1, 64x4 (default), 64x2, 128x4, 256x4). */
+ * in rounds with many bidders: 256x1, 64x4 (default), 64x2, 128x4, 256x4), "fit_order" (1, the default:
+ * scoring skips pairs that cannot fit in memory; 0: every pair goes through the MLP). */
 int mf_set_option(mf_ctx *ctx, const char *name, int64_t value);
 
 /*
  * Device time, in milliseconds, of the kernels the last call on this context
- * launched, by stage: what[0] layer-1 projections, [1] pair scoring,
- * [2] bidding kernels, [3] settle/bookkeeping kernels, [4] transposition,
- * [5] dual extraction, [6] certificate, [7] launches of the pair-scoring
- * kernel, [8] launches of bidding kernels.  Measured with HIP events on the
- * context's stream; entries of stages that did not run are 0.
+ * launched, by stage, measured with HIP events on the context's stream:
+ * what[0] layer-1 projections (and the memory ordering), [1] pair scoring,
+ * [2] the bidding rounds in which every line of the bidding side scans (the
+ * first of each phase), [3] how many of those ran, [4] transposition,
+ * [5] dual extraction, [6] certificate, [7] the whole auction, [8] weight
+ * bytes the rounds of [2] scanned, [9] the fraction of the n*m pairs the pair
+ * kernel ran the MLP on (the rest could not fit in memory and were marked
+ * infeasible without being scored).  Entries of stages that did not run are 0.
  */
 int mf_last_timings(mf_ctx *ctx, float what[16]);
 

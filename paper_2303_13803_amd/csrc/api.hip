@@ -38,12 +38,15 @@ void clear_timings(mf_ctx *ctx)
 
 int finish_score_timing(mf_ctx *ctx)
 {
+    MF_HIP(hipMemcpyAsync(ctx->h_pairs_evaluated, ctx->pairs_evaluated, sizeof(unsigned long long),
+                          hipMemcpyDeviceToHost, ctx->stream));
     MF_HIP(hipStreamSynchronize(ctx->stream));
     float a = 0.0f, b = 0.0f;
     MF_HIP(hipEventElapsedTime(&a, ctx->ev[0], ctx->ev[1]));
     MF_HIP(hipEventElapsedTime(&b, ctx->ev[1], ctx->ev[2]));
     ctx->timings[T_PROJ] = a;
     ctx->timings[T_PAIR] = b;
+    ctx->timings[T_PAIR_EVALUATED] = ctx->pairs_total > 0 ? (float)((double)*ctx->h_pairs_evaluated / ctx->pairs_total) : 0.0f;
     ctx->score_pending = false;
     return MF_OK;
 }
@@ -76,6 +79,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->team_max = 8;
     ctx->team_size = 16;
     ctx->team_threads = 1024;
+    ctx->fit_order = true;
     const size_t nm = (size_t)(max_n > max_m ? max_n : max_m);   // either side may be the one that bids first
     const size_t ldt = ((size_t)max_n + 3) & ~(size_t)3;
     hipError_t e = hipSuccess;
@@ -84,6 +88,10 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->proj_off, (size_t)max_m * 128));
     TRY(dev_alloc(&ctx->mem_on, (size_t)max_n));
     TRY(dev_alloc(&ctx->mem_off, (size_t)max_m));
+    TRY(dev_alloc(&ctx->order_on, (size_t)max_n));
+    TRY(dev_alloc(&ctx->order_off, (size_t)max_m));
+    TRY(dev_alloc(&ctx->pairs_evaluated, 1));
+    TRY(hipHostMalloc((void **)&ctx->h_pairs_evaluated, sizeof(unsigned long long)));
     TRY(dev_alloc(&ctx->wt, (size_t)max_m * ldt));
     TRY(dev_alloc(&ctx->price, nm + 8));
     TRY(dev_alloc(&ctx->profit, nm + 8));
@@ -115,12 +123,13 @@ int mf_destroy(mf_ctx *ctx)
     if (!ctx) return MF_ERR_ARG;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->wt, ctx->price,
+    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->order_on, ctx->order_off, ctx->pairs_evaluated, ctx->wt, ctx->price,
                    ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (ctx->h_stats) (void)hipHostFree(ctx->h_stats);
     if (ctx->h_cert) (void)hipHostFree(ctx->h_cert);
+    if (ctx->h_pairs_evaluated) (void)hipHostFree(ctx->h_pairs_evaluated);
     for (int i = 0; i < 8; ++i) if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
     delete ctx;
     return MF_OK;
@@ -238,6 +247,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "team_size")) { if (value < 2 || value > 32) return MF_ERR_ARG; ctx->team_size = (int)value; return MF_OK; }
     if (!strcmp(name, "team_threads")) { if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return MF_ERR_ARG; ctx->team_threads = (int)value; return MF_OK; }
     if (!strcmp(name, "chain_grid")) { if (value < 1 || value > 4096) return MF_ERR_ARG; ctx->chain_grid = (int)value; return MF_OK; }
+    if (!strcmp(name, "fit_order")) { ctx->fit_order = value != 0; return MF_OK; }
     if (!strcmp(name, "max_rounds")) { if (value < 1) return MF_ERR_ARG; ctx->max_rounds = value; return MF_OK; }
     return MF_ERR_ARG;
 }

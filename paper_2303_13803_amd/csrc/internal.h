@@ -22,7 +22,7 @@
 #define MF_MAX_DUAL (1ll << 43)
 
 enum { T_PROJ = 0, T_PAIR, T_BID_BULK, T_BID_BULK_LAUNCHES, T_TRANSPOSE, T_DUALS, T_CERT, T_SOLVE,
-       T_BID_BULK_BYTES, T_COUNT = 16 };
+       T_BID_BULK_BYTES, T_PAIR_EVALUATED, T_COUNT = 16 };
 
 struct mf_device_stats {            // lives in device memory, cleared per solve
     unsigned long long rounds;      // bidding rounds
@@ -56,6 +56,10 @@ struct mf_ctx {
     // scoring scratch
     float *proj_on, *proj_off;      // [max_n][H], [max_m][H]
     float *mem_on, *mem_off;        // [max_n], [max_m]
+    int32_t *order_on, *order_off;  // workloads by ascending memory fraction
+    unsigned long long *pairs_evaluated, *h_pairs_evaluated;   // pairs the last scoring pass ran the MLP on (device, pinned)
+    double pairs_total;             // ... out of this many
+    bool fit_order;                 // score in memory order and skip pairs that cannot fit
     // solver scratch
     int32_t *wt;                    // transposed weights [max_m][ldt]
     double *price, *profit;         // [max_m+4], [max_n+4]: exact integers held in doubles

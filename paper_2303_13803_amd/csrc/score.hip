@@ -34,6 +34,83 @@ __global__ void project_kernel(const float *__restrict__ X, int rows, int F,
     if (k == 0) mem[r] = x[mem_feature];
 }
 
+// order[k] = the workload with the k-th smallest key (ties by index).  Keys are
+// compared through the usual order-preserving map of float bits to unsigned
+// integers, so the result is a permutation whatever the keys hold.  A plain
+// rank count: count^2 comparisons, staged through LDS, is microseconds at the
+// sizes a weight matrix fits in memory for.
+__device__ __forceinline__ unsigned ordered_bits(float x)
+{
+    const unsigned b = __float_as_uint(x);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+constexpr int RANK_THREADS = 256, RANK_TILE = 2048;
+
+// rank[i] += number of keys in [first, last) that sort before key i.  The y
+// extent of the grid splits the comparisons into slices so that a few thousand
+// keys still fill the device; rank[] starts at zero.
+__global__ __launch_bounds__(RANK_THREADS) void rank_count_kernel(const float *__restrict__ key, int count,
+                                                                  int slice, int32_t *__restrict__ rank)
+{
+    __shared__ __align__(16) unsigned tile[RANK_TILE];
+    const int i = blockIdx.x * RANK_THREADS + threadIdx.x;
+    const unsigned mine = i < count ? ordered_bits(key[i]) : 0u;
+    const int first = blockIdx.y * slice, last = min(count, first + slice);
+    const int ties_upto = min(i, last);                 // equal keys count when they sit earlier; padding never does
+    int before = 0;
+    for (int base = first; base < last; base += RANK_TILE) {
+        const int lim = min(RANK_TILE, last - base);
+        __syncthreads();
+        for (int t = threadIdx.x; t < RANK_TILE; t += RANK_THREADS)
+            tile[t] = t < lim ? ordered_bits(key[base + t]) : 0xffffffffu;      // padding sorts after everything
+        __syncthreads();
+        const int upto = (lim + 3) & ~3;
+        for (int t = 0; t < upto; t += 4) {
+            const uint4 v = *(const uint4 *)(tile + t);
+            const int at = base + t;
+            before += (v.x < mine) + ((v.x == mine) & (at < ties_upto));
+            before += (v.y < mine) + ((v.y == mine) & (at + 1 < ties_upto));
+            before += (v.z < mine) + ((v.z == mine) & (at + 2 < ties_upto));
+            before += (v.w < mine) + ((v.w == mine) & (at + 3 < ties_upto));
+        }
+    }
+    if (i < count && before) atomicAdd(&rank[i], before);
+}
+
+__global__ void order_from_rank_kernel(const int32_t *__restrict__ rank, int count, int32_t *__restrict__ order)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) order[rank[i]] = i;
+}
+
+// Marks every pair that cannot fit (paper: Section "Implementation", the memory quota) and
+// clears the rest, in whole coalesced lines, before the pair kernel fills in the scores.
+__global__ __launch_bounds__(256) void fit_mask_kernel(const float *__restrict__ mem_on,
+                                                       const float *__restrict__ mem_off, int n, int m,
+                                                       float mem_limit, int32_t *__restrict__ W, int64_t ldw,
+                                                       int wide_stores)
+{
+    const int i = blockIdx.x;
+    const float mon = mem_on[i];
+    int32_t *row = W + (size_t)i * ldw;
+    for (int j = (blockIdx.y * 256 + threadIdx.x) * 4; j < m; j += gridDim.y * 1024) {
+        int32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (j + e < m && mon + mem_off[j + e] > mem_limit) ? MF_INFEASIBLE : 0;
+        if (wide_stores && j + 3 < m) *(int4 *)(row + j) = make_int4(w[0], w[1], w[2], w[3]);
+        else for (int e = 0; j + e < m; ++e) row[j + e] = w[e];
+    }
+}
+
+__global__ void clear_counter_kernel(unsigned long long *c) { *c = 0ull; }
+
+__global__ void fill_zero_kernel(int32_t *p, int count)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0;
+}
+
 constexpr int PAIR_THREADS = 512;   // 8 wavefronts: two per SIMD share one LDS copy of W2
 constexpr int PAIR_WAVES = PAIR_THREADS / 64;
 constexpr int PAIR_COLS = PAIR_WAVES * 32;
@@ -42,7 +119,7 @@ template <int H> struct PairShape {
     static constexpr int ROWS = 64;                        // online rows per workgroup
     static constexpr int KS = H / 2;                       // k-steps of the 32x32x2 tile
     static constexpr int MB = H / 32;                      // 32-row blocks of the hidden layer
-    static constexpr size_t LDS_BYTES = sizeof(float) * ((size_t)H * H + (size_t)ROWS * H + 2 * H);
+    static constexpr size_t LDS_BYTES = sizeof(float) * ((size_t)H * H + (size_t)ROWS * H + 2 * H + ROWS);
 };
 
 // One wavefront owns 32 offline columns (lane & 31) and walks down the online
@@ -61,7 +138,8 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     const float *__restrict__ b3, const float *__restrict__ mem_on,
     const float *__restrict__ mem_off, int n, int m, float scale, float mem_limit,
     int32_t *__restrict__ W, int64_t ldw, float *__restrict__ sigma,
-    const int32_t *__restrict__ row_map, const int32_t *__restrict__ col_map)
+    const int32_t *__restrict__ row_map, const int32_t *__restrict__ col_map, int by_memory,
+    unsigned long long *__restrict__ evaluated)
 {
     using S = PairShape<H>;
     constexpr int KS = S::KS, MB = S::MB, ROWS = S::ROWS, Q = KS / 4;
@@ -70,16 +148,23 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     float *pon_lds = (float *)(lds4) + H * H;              // [ROWS][H]
     float *b2_lds = pon_lds + ROWS * H;
     float *w3_lds = b2_lds + H;
+    float *mon_lds = w3_lds + H;                           // [ROWS] memory fraction of the tile's rows
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hh = lane >> 5, nn = lane & 31;
     // consecutive workgroups (which the hardware deals out to the eight XCDs in turn) share one
     // tile of offline columns and walk down the online rows, so that tile stays in every L2
     // and each XCD keeps re-reading the same eighth of the online projections
-    const int row0 = blockIdx.x * ROWS;
+    // The row tile also shifts by one per column tile: in memory order the tiles with work
+    // are the first so-many of each column tile, and without the shift the low XCDs would
+    // collect the odd one out every time.
+    const int row0 = (int)((blockIdx.x + blockIdx.y) % gridDim.x) * ROWS;
     if (row0 >= n) return;                  // the grid's x extent is padded to a multiple of eight
     const int nrows = min(ROWS, n - row0);
     const int j0 = (blockIdx.y * PAIR_WAVES + wave) * 32;
+    // in memory order the tile's first row and first column are its smallest: if they do not
+    // fit together, nothing in the tile does, and it already holds its marks
+    if (by_memory && mem_on[row_map[row0]] + mem_off[col_map[blockIdx.y * PAIR_COLS]] > mem_limit) return;
 
     for (int idx = tid; idx < MB * Q * 64; idx += PAIR_THREADS) {
         int ln = idx & 63, s4 = (idx >> 6) % Q, mb = idx / (64 * Q);
@@ -91,6 +176,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
         ((float4 *)pon_lds)[idx] = ((const float4 *)(P_on + (size_t)gi * H))[q];
     }
     if (tid < H) { b2_lds[tid] = b2[tid]; w3_lds[tid] = W3[tid]; }
+    if (tid < nrows) mon_lds[tid] = mem_on[row_map ? row_map[row0 + tid] : row0 + tid];
     __syncthreads();
     if (j0 >= m) return;
 
@@ -104,10 +190,16 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     }
     const float moff = mem_off[jc];
     const float bias3 = b3[0];
+    // by_memory: the maps list rows and columns by ascending memory fraction, so this
+    // wavefront's first column has its smallest one, and once a row does not fit next to
+    // that column (float addition is monotone) no later row of the tile fits any of its columns
+    const float moff_least = by_memory ? __shfl(moff, 0) : 0.0f;
 
-    for (int r = 0; r < nrows; ++r) {
+    int r = 0;
+    for (; r < nrows; ++r) {
         // W2 does not fit in registers next to the accumulators: keep its loads inside the row loop
         asm volatile("" ::: "memory");
+        if (by_memory && mon_lds[r] + moff_least > mem_limit) break;
         floatx16 acc[MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
@@ -156,17 +248,19 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
             float q = rintf(sg * scale);
             q = fminf(fmaxf(q, 0.0f), scale);
             int32_t w = (int32_t)q;
-            const float memsum = mem_on[i] + moff;
+            const float memsum = mon_lds[r] + moff;
             if (memsum > mem_limit) w = MF_INFEASIBLE;
             W[(size_t)i * ldw + jc] = w;
             if (sigma) sigma[(size_t)i * m + jc] = sg;
         }
     }
+    // rows the loop left early hold the "cannot fit" marks fit_mask_kernel wrote
+    if (evaluated && lane == 0 && r > 0) atomicAdd(evaluated, (unsigned long long)r * (unsigned)min(32, m - j0));
 }
 
 template <int H>
 int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
-                float *d_sigma, const int32_t *row_map, const int32_t *col_map)
+                float *d_sigma, const int32_t *row_map, const int32_t *col_map, bool by_memory)
 {
     using S = PairShape<H>;
     static bool configured = false;
@@ -179,9 +273,24 @@ int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, 
     dim3 grid((((n + S::ROWS - 1) / S::ROWS) + 7) & ~7, (m + PAIR_COLS - 1) / PAIR_COLS);
     hipLaunchKernelGGL(pair_mlp_kernel<H>, grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
                        ctx->proj_on, ctx->proj_off, p->d_W2, p->d_b2, p->d_W3, p->d_b3,
-                       ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma, row_map, col_map);
+                       ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma, row_map, col_map,
+                       by_memory ? 1 : 0, ctx->pairs_evaluated);
     MF_HIP(hipGetLastError());
     return MF_OK;
+}
+
+// order[k] = the workload with the k-th smallest key; ranks are counted in list[0]
+void order_by_memory(mf_ctx *ctx, const float *key, int count, int32_t *order)
+{
+    const int blocks = (count + RANK_THREADS - 1) / RANK_THREADS;
+    int split = 2048 / blocks;
+    split = split < 1 ? 1 : (split > 64 ? 64 : split);
+    const int slice = ((count + split - 1) / split + 3) & ~3;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(RANK_THREADS), 0, ctx->stream, ctx->list[0], count);
+    hipLaunchKernelGGL(rank_count_kernel, dim3(blocks, (count + slice - 1) / slice), dim3(RANK_THREADS), 0,
+                       ctx->stream, key, count, slice, ctx->list[0]);
+    hipLaunchKernelGGL(order_from_rank_kernel, dim3(blocks), dim3(RANK_THREADS), 0, ctx->stream, ctx->list[0],
+                       count, order);
 }
 
 }  // namespace
@@ -201,9 +310,25 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int n
                            p->mem_feature, ctx->mem_off);
         MF_HIP(hipGetLastError());
     }
+    // Pairs whose memory fractions do not fit get no score, so unless the caller wants every
+    // score, walk rows and columns in memory order: the pairs that cannot fit then form one
+    // corner of the tile grid and the kernel leaves them out.  Results land at the same places.
+    const bool by_memory = ctx->fit_order && !d_sigma;
+    hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->pairs_evaluated);
+    if (by_memory) {
+        order_by_memory(ctx, ctx->mem_on, n, ctx->order_on);
+        order_by_memory(ctx, ctx->mem_off, m, ctx->order_off);
+        const int chunks = (m + 4095) / 4096 < 16 ? (m + 4095) / 4096 : 16;
+        const int wide = ((uintptr_t)d_W & 15u) == 0 && (ldw & 3) == 0;
+        hipLaunchKernelGGL(fit_mask_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->mem_on, ctx->mem_off,
+                           n, m, p->mem_limit, d_W, ldw, wide);
+        MF_HIP(hipGetLastError());
+    }
+    ctx->pairs_total = (double)n * (double)m;
     MF_HIP(hipEventRecord(ctx->ev[1], ctx->stream));
-    int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, d_W, ldw, d_sigma, nullptr, nullptr)
-                       : launch_pair<128>(ctx, p, n, m, d_W, ldw, d_sigma, nullptr, nullptr);
+    const int32_t *rmap = by_memory ? ctx->order_on : nullptr, *cmap = by_memory ? ctx->order_off : nullptr;
+    int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, d_W, ldw, d_sigma, rmap, cmap, by_memory)
+                       : launch_pair<128>(ctx, p, n, m, d_W, ldw, d_sigma, rmap, cmap, by_memory);
     if (rc != MF_OK) return rc;
     MF_HIP(hipEventRecord(ctx->ev[2], ctx->stream));
     ctx->score_pending = true;
@@ -253,14 +378,16 @@ int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int
                        d_off, m, F, p->d_W1, F, (const float *)nullptr, H, ctx->proj_off,
                        p->mem_feature, ctx->mem_off);
     MF_HIP(hipGetLastError());
+    hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->pairs_evaluated);
+    ctx->pairs_total = (double)n_rows * (double)m + (double)n * (double)n_cols;
     MF_HIP(hipEventRecord(ctx->ev[1], ctx->stream));
     int rc = MF_OK;
     if (n_rows > 0)
-        rc = (H == 64) ? launch_pair<64>(ctx, p, n_rows, m, d_W, ldw, nullptr, d_rows, nullptr)
-                       : launch_pair<128>(ctx, p, n_rows, m, d_W, ldw, nullptr, d_rows, nullptr);
+        rc = (H == 64) ? launch_pair<64>(ctx, p, n_rows, m, d_W, ldw, nullptr, d_rows, nullptr, false)
+                       : launch_pair<128>(ctx, p, n_rows, m, d_W, ldw, nullptr, d_rows, nullptr, false);
     if (rc == MF_OK && n_cols > 0)
-        rc = (H == 64) ? launch_pair<64>(ctx, p, n, n_cols, d_W, ldw, nullptr, nullptr, d_cols)
-                       : launch_pair<128>(ctx, p, n, n_cols, d_W, ldw, nullptr, nullptr, d_cols);
+        rc = (H == 64) ? launch_pair<64>(ctx, p, n, n_cols, d_W, ldw, nullptr, nullptr, d_cols, false)
+                       : launch_pair<128>(ctx, p, n, n_cols, d_W, ldw, nullptr, nullptr, d_cols, false);
     if (rc != MF_OK) return rc;
     MF_HIP(hipEventRecord(ctx->ev[2], ctx->stream));
     ctx->score_pending = true;

@@ -67,6 +67,57 @@ def test_scores_other_seeds_and_scales(mm, orc):
     ctx.close()
 
 
+@pytest.mark.parametrize("cfg,n,m", [("C1", None, None), ("C2", 130, 517), ("C4", 300, 1031), ("C5", 257, 700),
+                                     ("C3", 65, 257), ("C5", 1, 40), ("C3", 700, 90)])
+def test_memory_ordered_pass_gives_the_same_matrix(mm, orc, cfg, n, m):
+    """Without a score buffer the kernel walks rows and columns by memory fraction and leaves out
+    pairs that cannot fit: the matrix must equal the all-pairs pass bit for bit, and the checker's."""
+    r = synth.scheduling_round(cfg, 4, n=n, m=m)
+    n, m = r["n"], r["m"]
+    ctx = mm.Context(n, m)
+    Wg, _ = _score_on_gpu(mm, ctx, r, want_sigma=False)
+    part = ctx.last_timings()["pairs_evaluated_fraction"]
+    ctx.set_option("fit_order", 0)
+    Wall, _ = _score_on_gpu(mm, ctx, r, want_sigma=False)
+    assert ctx.last_timings()["pairs_evaluated_fraction"] == 1.0
+    assert (Wg == Wall).all()
+    _, W = orc.score_pairs(r["x_on"], r["x_off"], r["params"], r["cfg"].scale)
+    assert ((Wg == INF) == (W == INF)).all(), "mask bits differ"
+    ok = W != INF
+    if ok.any():
+        assert np.abs(Wg[ok].astype(np.int64) - W[ok].astype(np.int64)).max() <= weight_tolerance(r["cfg"].scale)
+    # every feasible pair went through the MLP; skipped ones are only whole 32-column runs
+    feasible = ok.mean()
+    assert feasible - 1e-6 <= part <= 1.0
+    if n >= 64 and m >= 256:
+        assert part <= feasible + 0.35
+    ctx.close()
+
+
+def test_memory_order_with_ties_and_odd_pitch(mm, orc):
+    """Many equal memory fractions (the ordering must still be a permutation), fractions of 0 and
+    above the limit, and a matrix pitch that rules out 16-byte stores."""
+    r = synth.scheduling_round("C3", 6, n=333, m=1001)
+    n, m = r["n"], r["m"]
+    r["x_on"][:, 0] = np.round(r["x_on"][:, 0] * 8) / np.float32(8)
+    r["x_off"][:, 0] = np.round(r["x_off"][:, 0] * 8) / np.float32(8)
+    r["x_on"][::7, 0] = 0.0; r["x_off"][::5, 0] = 1.5; r["x_off"][1::11, 0] = -0.0
+    ctx = mm.Context(n, m)
+    pred = ctx.predictor(dev_params(r["params"]), r["cfg"].scale)
+    _, W = orc.score_pairs(r["x_on"], r["x_off"], r["params"], r["cfg"].scale)
+    for pitch in (m, m + 3):
+        Wd = torch.full((n, pitch), -7, dtype=torch.int32, device="cuda")
+        ctx.score_pairs(pred, dev(r["x_on"]), dev(r["x_off"]), Wd)
+        torch.cuda.synchronize()
+        Wg = Wd.cpu().numpy()
+        assert (Wg[:, m:] == -7).all()
+        Wg = Wg[:, :m]
+        assert ((Wg == INF) == (W == INF)).all()
+        ok = W != INF
+        assert np.abs(Wg[ok].astype(np.int64) - W[ok].astype(np.int64)).max() <= weight_tolerance(r["cfg"].scale)
+    ctx.close()
+
+
 def test_closed_form_predictors(mm):
     # zero network: every feasible weight is exactly S/2
     F, H, S = 16, 64, float(2 ** 20)
