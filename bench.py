@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--update-rounds", type=int, default=3,
                     help="also time this many follow-up rounds with --churn of the workloads replaced")
     ap.add_argument("--churn", type=float, default=0.02)
+    ap.add_argument("--types", type=int, default=3,
+                    help="also time scoring with this many per-GPU-type predictors (0: skip)")
     ap.add_argument("--calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (reference for hardware byte counters)")
     ap.add_argument("--opt", action="append", default=[], help="solver option name=value (repeatable)")
@@ -180,6 +182,22 @@ def main():
                                     "rescore_ms_last": tm["pair_scoring_ms"] + tm["projections_ms"],
                                     "phases_last": last.phases, "bids_last": last.bids,
                                     "sequential_steps_last": last.chain_depth}
+    if args.types > 0:
+        # one predictor per GPU type: same shapes, other weights; rows are scored by their type's
+        plist = [{k: dev(v) for k, v in p.items()} for p in synth.typed_predictors(args.seed + 7, cfg.F, [cfg.H] * args.types)]
+        tpreds = [ctx.predictor(p, cfg.scale) for p in plist]
+        d_types = dev(synth.gpu_types(args.seed, n, args.types))
+        W2 = torch.empty_like(W)
+        ms = []
+        for _ in range(3):
+            ctx.score_pairs_typed(tpreds, d_types, x_on, x_off, W2)
+            torch.cuda.synchronize()
+            tm = ctx.last_timings()
+            ms.append(tm["pair_scoring_ms"] + tm["projections_ms"])
+        out["typed_scoring"] = {"gpu_types": args.types, "ms": float(np.median(ms)),
+                                "pairs_per_s": n * m / (float(np.median(ms)) * 1e-3),
+                                "pairs_evaluated_fraction": tm["pairs_evaluated_fraction"]}
+        del W2
     if not args.no_cpu:
         blk = min(args.cpu_block, n)
         Wg_block = W[:blk, :min(m, blk * (m // n))].cpu().numpy()

@@ -13,6 +13,8 @@
  *   mf_solve_assignment  the maximum-weight matching, with a proof of optimality
  *   mf_check_certificate re-verifies such a proof on the device
  *   mf_schedule_round    the two steps back to back (one call per round)
+ *   mf_*_typed           the same with one predictor per GPU type
+ *   mf_schedule_round_update  the next periodic round: re-scores what changed
  *
  * Conventions shared by every call
  *   - Pointers named d_* are DEVICE pointers (HIP global memory on the device
@@ -190,6 +192,24 @@ int mf_schedule_round_update(mf_ctx *ctx, const mf_predictor *pred,
                              const int32_t *d_changed_off, int n_changed_off,
                              int32_t *d_W, int64_t ldw,
                              int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
+
+/*
+ * One predictor per GPU type (paper: Section "Matching-based scheduling": GPU
+ * types perform differently, so an MLP is trained for each).  Online workload
+ * i runs on a GPU of type d_type_on[i] in [0, n_types) (device array of n
+ * int32) and every pair in its row is scored by preds[d_type_on[i]]
+ * (host array of n_types predictors, 1 <= n_types <= 64).  The predictors
+ * must agree on F, mem_feature, mem_limit and scale (else MF_ERR_ARG); their
+ * hidden widths may differ.  Everything else is as in mf_score_pairs /
+ * mf_schedule_round; a type out of range gives MF_ERR_ARG (checked on the
+ * device before use, which waits for the stream once).
+ */
+int mf_score_pairs_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types, const int32_t *d_type_on,
+                         const float *d_on, int n, const float *d_off, int m,
+                         int32_t *d_W, int64_t ldw, float *d_sigma);
+int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types, const int32_t *d_type_on,
+                            const float *d_on, int n, const float *d_off, int m, int32_t *d_W, int64_t ldw,
+                            int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
 
 /* Solver knobs: "theta" (epsilon divisor per phase, default 8), "max_rounds" (limit on
  * evaluated bids, default 4,000,000,000), "tail_max" (bidder count at or below which one

@@ -69,6 +69,23 @@ def score_pairs(x_on, x_off, params, scale, mem_feature=0, mem_limit=1.0, wide=T
     return sigma, w
 
 
+def score_pairs_typed(x_on, x_off, params_by_type, type_on, scale, mem_feature=0, mem_limit=1.0, wide=True):
+    """One predictor per GPU type (paper: Section "Matching-based scheduling", an MLP per GPU
+    type): row i of the result is row i of score_pairs under params_by_type[type_on[i]]."""
+    x_on = np.ascontiguousarray(x_on, np.float32)
+    type_on = np.asarray(type_on)
+    n, m = x_on.shape[0], np.asarray(x_off).shape[0]
+    sigma = np.empty((n, m), np.float32)
+    w = np.empty((n, m), np.int32)
+    for t, params in enumerate(params_by_type):
+        rows = np.nonzero(type_on == t)[0]
+        if len(rows):
+            sigma[rows], w[rows] = score_pairs(x_on[rows], x_off, params, scale, mem_feature, mem_limit, wide)
+    if ((type_on < 0) | (type_on >= len(params_by_type))).any():
+        raise ValueError("score_pairs_typed: type out of range")
+    return sigma, w
+
+
 def max_weight_matching(W):
     """Exact optimum: returns (total, row2col, u, v)."""
     W = np.ascontiguousarray(W, np.int32)

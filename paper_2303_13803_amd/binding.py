@@ -17,7 +17,8 @@ INFEASIBLE = -2147483648
 OK, ERR_ARG, ERR_SHAPE, ERR_HIP, ERR_NOT_CONVERGED, ERR_CERT, ERR_RANGE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["mf_create", "mf_destroy", "mf_score_pairs", "mf_solve_assignment",
-           "mf_check_certificate", "mf_schedule_round", "mf_schedule_round_update", "mf_set_option", "mf_last_timings",
+           "mf_check_certificate", "mf_schedule_round", "mf_schedule_round_update", "mf_score_pairs_typed",
+           "mf_schedule_round_typed", "mf_set_option", "mf_last_timings",
            "mf_strerror", "mf_last_hip_error"]
 
 TIMING_NAMES = ["projections_ms", "pair_scoring_ms", "bulk_bid_ms", "bulk_bid_launches",
@@ -45,7 +46,7 @@ class Result(C.Structure):
 
 def load_library():
     if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2303_13803_amd.build` "
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2303_13803_amd/build.py` "
                           "(there is no CPU fallback)")
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
@@ -58,6 +59,9 @@ def load_library():
                                       C.POINTER(Result)]
     lib.mf_schedule_round_update.argtypes = [vp, C.POINTER(Predictor), vp, i32, vp, i32, vp, i32, vp, i32, vp, i64,
                                              vp, vp, vp, C.POINTER(Result)]
+    lib.mf_score_pairs_typed.argtypes = [vp, C.POINTER(Predictor), i32, vp, vp, i32, vp, i32, vp, i64, vp]
+    lib.mf_schedule_round_typed.argtypes = [vp, C.POINTER(Predictor), i32, vp, vp, i32, vp, i32, vp, i64, vp, vp, vp,
+                                            C.POINTER(Result)]
     lib.mf_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.mf_last_timings.argtypes = [vp, C.POINTER(C.c_float * 16)]
     lib.mf_strerror.argtypes = [i32]
@@ -167,6 +171,24 @@ class Context:
             0 if changed_off is None else changed_off.numel(),
             _ptr(W, torch.int32), W.stride(0), _ptr(row2col, torch.int32), _ptr(u, torch.int64),
             _ptr(v, torch.int64), C.byref(res)))
+        return res
+
+    def score_pairs_typed(self, preds, type_on, x_on, x_off, W, sigma=None):
+        """preds: list of predictors, one per GPU type; type_on: int32 device tensor [n]."""
+        n, m = x_on.shape[0], x_off.shape[0]
+        arr = (Predictor * len(preds))(*preds)
+        self._check(_lib.mf_score_pairs_typed(self._h, arr, len(preds), _ptr(type_on, torch.int32),
+                                              _ptr(x_on, torch.float32), n, _ptr(x_off, torch.float32), m,
+                                              _ptr(W, torch.int32), W.stride(0), _ptr(sigma, torch.float32)))
+
+    def schedule_round_typed(self, preds, type_on, x_on, x_off, W, row2col, u, v):
+        n, m = x_on.shape[0], x_off.shape[0]
+        arr = (Predictor * len(preds))(*preds)
+        res = Result()
+        self._check(_lib.mf_schedule_round_typed(
+            self._h, arr, len(preds), _ptr(type_on, torch.int32), _ptr(x_on, torch.float32), n,
+            _ptr(x_off, torch.float32), m, _ptr(W, torch.int32), W.stride(0), _ptr(row2col, torch.int32),
+            _ptr(u, torch.int64), _ptr(v, torch.int64), C.byref(res)))
         return res
 
     def last_timings(self):

@@ -30,6 +30,20 @@ int check_predictor(const mf_predictor *p)
     return MF_OK;
 }
 
+// one predictor per GPU type: same inputs, same quantisation, same memory rule
+int check_predictors(const mf_predictor *preds, int n_types)
+{
+    if (!preds || n_types < 1 || n_types > MF_MAX_TYPES) return MF_ERR_ARG;
+    for (int t = 0; t < n_types; ++t) {
+        const int rc = check_predictor(&preds[t]);
+        if (rc != MF_OK) return rc;
+        if (preds[t].F != preds[0].F || preds[t].mem_feature != preds[0].mem_feature ||
+            preds[t].mem_limit != preds[0].mem_limit || preds[t].scale != preds[0].scale)
+            return MF_ERR_ARG;
+    }
+    return MF_OK;
+}
+
 void clear_timings(mf_ctx *ctx)
 {
     memset(ctx->timings, 0, sizeof(ctx->timings));
@@ -90,6 +104,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->mem_off, (size_t)max_m));
     TRY(dev_alloc(&ctx->order_on, (size_t)max_n));
     TRY(dev_alloc(&ctx->order_off, (size_t)max_m));
+    TRY(dev_alloc(&ctx->type_segment, (size_t)MF_MAX_TYPES + 1));
     TRY(dev_alloc(&ctx->pairs_evaluated, 1));
     TRY(hipHostMalloc((void **)&ctx->h_pairs_evaluated, sizeof(unsigned long long)));
     TRY(dev_alloc(&ctx->wt, (size_t)max_m * ldt));
@@ -123,7 +138,7 @@ int mf_destroy(mf_ctx *ctx)
     if (!ctx) return MF_ERR_ARG;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->order_on, ctx->order_off, ctx->pairs_evaluated, ctx->wt, ctx->price,
+    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->order_on, ctx->order_off, ctx->type_segment, ctx->pairs_evaluated, ctx->wt, ctx->price,
                    ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
@@ -144,7 +159,7 @@ int mf_score_pairs(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, int
     if (n > ctx->max_n || m > ctx->max_m) return MF_ERR_SHAPE;
     MF_HIP(hipSetDevice(ctx->device));
     clear_timings(ctx);
-    return mf_launch_score(ctx, pred, d_on, n, d_off, m, d_W, ldw, d_sigma);
+    return mf_launch_score(ctx, pred, 1, nullptr, d_on, n, d_off, m, d_W, ldw, d_sigma);
 }
 
 int mf_solve_assignment(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
@@ -195,7 +210,42 @@ int mf_schedule_round(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, 
     MF_HIP(hipSetDevice(ctx->device));
     clear_timings(ctx);
     memset(h_res, 0, sizeof(*h_res));
-    rc = mf_launch_score(ctx, pred, d_on, n, d_off, m, d_W, ldw, nullptr);
+    rc = mf_launch_score(ctx, pred, 1, nullptr, d_on, n, d_off, m, d_W, ldw, nullptr);
+    if (rc == MF_OK) rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, false, nullptr, 0);
+    if (rc == MF_OK || rc == MF_ERR_CERT) {
+        int rt = finish_score_timing(ctx);
+        if (rt != MF_OK) rc = rt;
+    }
+    h_res->status = rc;
+    return rc;
+}
+
+int mf_score_pairs_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types, const int32_t *d_type_on,
+                         const float *d_on, int n, const float *d_off, int m,
+                         int32_t *d_W, int64_t ldw, float *d_sigma)
+{
+    if (!ctx || !d_type_on || !d_on || !d_off || !d_W || n <= 0 || m <= 0 || ldw < m) return MF_ERR_ARG;
+    int rc = check_predictors(preds, n_types);
+    if (rc != MF_OK) return rc;
+    if (n > ctx->max_n || m > ctx->max_m) return MF_ERR_SHAPE;
+    MF_HIP(hipSetDevice(ctx->device));
+    clear_timings(ctx);
+    return mf_launch_score(ctx, preds, n_types, d_type_on, d_on, n, d_off, m, d_W, ldw, d_sigma);
+}
+
+int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types, const int32_t *d_type_on,
+                            const float *d_on, int n, const float *d_off, int m, int32_t *d_W, int64_t ldw,
+                            int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res)
+{
+    if (!d_type_on || !d_on || !d_off || !d_row2col || !d_u || !d_v || !h_res) return MF_ERR_ARG;
+    int rc = check_matrix(ctx, d_W, n, m, ldw);
+    if (rc != MF_OK) return rc;
+    rc = check_predictors(preds, n_types);
+    if (rc != MF_OK) return rc;
+    MF_HIP(hipSetDevice(ctx->device));
+    clear_timings(ctx);
+    memset(h_res, 0, sizeof(*h_res));
+    rc = mf_launch_score(ctx, preds, n_types, d_type_on, d_on, n, d_off, m, d_W, ldw, nullptr);
     if (rc == MF_OK) rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, false, nullptr, 0);
     if (rc == MF_OK || rc == MF_ERR_CERT) {
         int rt = finish_score_timing(ctx);

@@ -20,6 +20,7 @@
 #define MF_ID_MASK ((1ull << MF_ID_BITS) - 1ull)
 #define MF_MAX_DIM ((1 << MF_ID_BITS) - 2)
 #define MF_MAX_DUAL (1ll << 43)
+#define MF_MAX_TYPES 64
 
 enum { T_PROJ = 0, T_PAIR, T_BID_BULK, T_BID_BULK_LAUNCHES, T_TRANSPOSE, T_DUALS, T_CERT, T_SOLVE,
        T_BID_BULK_BYTES, T_PAIR_EVALUATED, T_COUNT = 16 };
@@ -56,7 +57,8 @@ struct mf_ctx {
     // scoring scratch
     float *proj_on, *proj_off;      // [max_n][H], [max_m][H]
     float *mem_on, *mem_off;        // [max_n], [max_m]
-    int32_t *order_on, *order_off;  // workloads by ascending memory fraction
+    int32_t *order_on, *order_off;  // workloads by ascending memory fraction (online: by type first)
+    int32_t *type_segment;          // [MF_MAX_TYPES + 1] first position of each type in order_on
     unsigned long long *pairs_evaluated, *h_pairs_evaluated;   // pairs the last scoring pass ran the MLP on (device, pinned)
     double pairs_total;             // ... out of this many
     bool fit_order;                 // score in memory order and skip pairs that cannot fit
@@ -91,8 +93,9 @@ struct mf_ctx {
 };
 
 // score.hip
-int mf_launch_score(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, int n,
-                    const float *d_off, int m, int32_t *d_W, int64_t ldw, float *d_sigma);
+int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const int32_t *d_type,
+                    const float *d_on, int n, const float *d_off, int m, int32_t *d_W, int64_t ldw,
+                    float *d_sigma);
 int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, int n, const float *d_off,
                       int m, int32_t *d_W, int64_t ldw, const int32_t *d_rows, int n_rows,
                       const int32_t *d_cols, int n_cols);

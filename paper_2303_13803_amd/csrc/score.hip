@@ -20,8 +20,7 @@ namespace {
 
 __global__ void project_kernel(const float *__restrict__ X, int rows, int F,
                                const float *__restrict__ W1, int col_off,
-                               const float *__restrict__ bias, int H, float *__restrict__ P,
-                               int mem_feature, float *__restrict__ mem)
+                               const float *__restrict__ bias, int H, float *__restrict__ P)
 {
     long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long)rows * H) return;
@@ -31,7 +30,6 @@ __global__ void project_kernel(const float *__restrict__ X, int rows, int F,
     float s = bias ? bias[k] : 0.0f;
     for (int t = 0; t < F; ++t) s = fmaf(x[t], w[t], s);
     P[idx] = s;
-    if (k == 0) mem[r] = x[mem_feature];
 }
 
 // order[k] = the workload with the k-th smallest key (ties by index).  Keys are
@@ -49,30 +47,45 @@ constexpr int RANK_THREADS = 256, RANK_TILE = 2048;
 
 // rank[i] += number of keys in [first, last) that sort before key i.  The y
 // extent of the grid splits the comparisons into slices so that a few thousand
-// keys still fill the device; rank[] starts at zero.
-__global__ __launch_bounds__(RANK_THREADS) void rank_count_kernel(const float *__restrict__ key, int count,
+// keys still fill the device; rank[] starts at zero.  With GROUPED the order is
+// by group first (group[i] in [0, 2^15)) and by key within a group.
+template <bool GROUPED>
+__global__ __launch_bounds__(RANK_THREADS) void rank_count_kernel(const float *__restrict__ key,
+                                                                  const int32_t *__restrict__ group, int count,
                                                                   int slice, int32_t *__restrict__ rank)
 {
     __shared__ __align__(16) unsigned tile[RANK_TILE];
+    __shared__ __align__(16) int gtile[GROUPED ? RANK_TILE : 4];
     const int i = blockIdx.x * RANK_THREADS + threadIdx.x;
     const unsigned mine = i < count ? ordered_bits(key[i]) : 0u;
+    const int gmine = (GROUPED && i < count) ? group[i] : 0;
     const int first = blockIdx.y * slice, last = min(count, first + slice);
     const int ties_upto = min(i, last);                 // equal keys count when they sit earlier; padding never does
     int before = 0;
     for (int base = first; base < last; base += RANK_TILE) {
         const int lim = min(RANK_TILE, last - base);
         __syncthreads();
-        for (int t = threadIdx.x; t < RANK_TILE; t += RANK_THREADS)
+        for (int t = threadIdx.x; t < RANK_TILE; t += RANK_THREADS) {
             tile[t] = t < lim ? ordered_bits(key[base + t]) : 0xffffffffu;      // padding sorts after everything
+            if (GROUPED) gtile[t] = t < lim ? group[base + t] : 0x7fffffff;
+        }
         __syncthreads();
         const int upto = (lim + 3) & ~3;
         for (int t = 0; t < upto; t += 4) {
             const uint4 v = *(const uint4 *)(tile + t);
             const int at = base + t;
-            before += (v.x < mine) + ((v.x == mine) & (at < ties_upto));
-            before += (v.y < mine) + ((v.y == mine) & (at + 1 < ties_upto));
-            before += (v.z < mine) + ((v.z == mine) & (at + 2 < ties_upto));
-            before += (v.w < mine) + ((v.w == mine) & (at + 3 < ties_upto));
+            int c0 = (v.x < mine) + ((v.x == mine) & (at < ties_upto));
+            int c1 = (v.y < mine) + ((v.y == mine) & (at + 1 < ties_upto));
+            int c2 = (v.z < mine) + ((v.z == mine) & (at + 2 < ties_upto));
+            int c3 = (v.w < mine) + ((v.w == mine) & (at + 3 < ties_upto));
+            if (GROUPED) {
+                const int4 g = *(const int4 *)(gtile + t);
+                c0 = (g.x < gmine) + ((g.x == gmine) & c0);
+                c1 = (g.y < gmine) + ((g.y == gmine) & c1);
+                c2 = (g.z < gmine) + ((g.z == gmine) & c2);
+                c3 = (g.w < gmine) + ((g.w == gmine) & c3);
+            }
+            before += c0 + c1 + c2 + c3;
         }
     }
     if (i < count && before) atomicAdd(&rank[i], before);
@@ -104,6 +117,8 @@ __global__ __launch_bounds__(256) void fit_mask_kernel(const float *__restrict__
 }
 
 __global__ void clear_counter_kernel(unsigned long long *c) { *c = 0ull; }
+
+__global__ void fill_flag_kernel(int *flag) { *flag = 0; }
 
 __global__ void fill_zero_kernel(int32_t *p, int count)
 {
@@ -139,7 +154,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     const float *__restrict__ mem_off, int n, int m, float scale, float mem_limit,
     int32_t *__restrict__ W, int64_t ldw, float *__restrict__ sigma,
     const int32_t *__restrict__ row_map, const int32_t *__restrict__ col_map, int by_memory,
-    unsigned long long *__restrict__ evaluated)
+    unsigned long long *__restrict__ evaluated, const int32_t *__restrict__ segment)
 {
     using S = PairShape<H>;
     constexpr int KS = S::KS, MB = S::MB, ROWS = S::ROWS, Q = KS / 4;
@@ -152,6 +167,10 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hh = lane >> 5, nn = lane & 31;
+    if (segment) {                          // only entries [segment[0], segment[1]) of the row map
+        row_map += segment[0];
+        n = segment[1] - segment[0];
+    }
     // consecutive workgroups (which the hardware deals out to the eight XCDs in turn) share one
     // tile of offline columns and walk down the online rows, so that tile stays in every L2
     // and each XCD keeps re-reading the same eighth of the online projections
@@ -260,7 +279,8 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
 
 template <int H>
 int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
-                float *d_sigma, const int32_t *row_map, const int32_t *col_map, bool by_memory)
+                float *d_sigma, const int32_t *row_map, const int32_t *col_map, bool by_memory,
+                const int32_t *segment = nullptr)
 {
     using S = PairShape<H>;
     static bool configured = false;
@@ -274,70 +294,124 @@ int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, 
     hipLaunchKernelGGL(pair_mlp_kernel<H>, grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
                        ctx->proj_on, ctx->proj_off, p->d_W2, p->d_b2, p->d_W3, p->d_b3,
                        ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma, row_map, col_map,
-                       by_memory ? 1 : 0, ctx->pairs_evaluated);
+                       by_memory ? 1 : 0, ctx->pairs_evaluated, segment);
     MF_HIP(hipGetLastError());
     return MF_OK;
 }
 
-// order[k] = the workload with the k-th smallest key; ranks are counted in list[0]
-void order_by_memory(mf_ctx *ctx, const float *key, int count, int32_t *order)
+// order[k] = the workload with the k-th smallest (group, key); ranks are counted in list[0]
+void order_by_memory(mf_ctx *ctx, const float *key, const int32_t *group, int count, int32_t *order)
 {
     const int blocks = (count + RANK_THREADS - 1) / RANK_THREADS;
     int split = 2048 / blocks;
     split = split < 1 ? 1 : (split > 64 ? 64 : split);
     const int slice = ((count + split - 1) / split + 3) & ~3;
+    const dim3 grid(blocks, (count + slice - 1) / slice);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(RANK_THREADS), 0, ctx->stream, ctx->list[0], count);
-    hipLaunchKernelGGL(rank_count_kernel, dim3(blocks, (count + slice - 1) / slice), dim3(RANK_THREADS), 0,
-                       ctx->stream, key, count, slice, ctx->list[0]);
+    if (group)
+        hipLaunchKernelGGL(rank_count_kernel<true>, grid, dim3(RANK_THREADS), 0, ctx->stream, key, group, count,
+                           slice, ctx->list[0]);
+    else
+        hipLaunchKernelGGL(rank_count_kernel<false>, grid, dim3(RANK_THREADS), 0, ctx->stream, key, group, count,
+                           slice, ctx->list[0]);
     hipLaunchKernelGGL(order_from_rank_kernel, dim3(blocks), dim3(RANK_THREADS), 0, ctx->stream, ctx->list[0],
                        count, order);
 }
 
+__global__ void gather_feature_kernel(const float *__restrict__ X, int rows, int F, int feature,
+                                      float *__restrict__ out)
+{
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < rows) out[r] = X[(size_t)r * F + feature];
+}
+
+// segment[t] = number of workloads whose type is below t (t = 0..n_types); *bad is raised for
+// a type outside [0, n_types).  One workgroup: the type counts are a few dozen integers.
+__global__ __launch_bounds__(1024) void type_segments_kernel(const int32_t *__restrict__ type, int count,
+                                                             int n_types, int32_t *__restrict__ segment, int *bad)
+{
+    __shared__ int hist[MF_MAX_TYPES];
+    for (int t = threadIdx.x; t < MF_MAX_TYPES; t += blockDim.x) hist[t] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < count; i += blockDim.x) {
+        const int t = type[i];
+        if (t < 0 || t >= n_types) atomicExch(bad, 1);
+        else atomicAdd(&hist[t], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int t = 0; t <= n_types; ++t) { segment[t] = run; if (t < n_types) run += hist[t]; }
+    }
+}
+
 }  // namespace
 
-int mf_launch_score(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int n,
-                    const float *d_off, int m, int32_t *d_W, int64_t ldw, float *d_sigma)
+// preds[0..n_types): with d_type == nullptr there is one predictor for everybody; otherwise
+// online workload i is scored by preds[d_type[i]] (all of them agree on F, the memory feature,
+// the memory limit and the scale; the hidden width may differ).  Per type: project everybody
+// with that type's first layer, then run the pair kernel on that type's rows - a contiguous
+// segment of the row map, which lists the online workloads by (type, memory fraction).
+int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const int32_t *d_type,
+                    const float *d_on, int n, const float *d_off, int m, int32_t *d_W, int64_t ldw,
+                    float *d_sigma)
 {
-    const int H = p->H, F = p->F;
-    MF_HIP(hipEventRecord(ctx->ev[0], ctx->stream));
-    {
-        long tot = (long)n * H;
-        hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
-                           d_on, n, F, p->d_W1, 0, p->d_b1, H, ctx->proj_on, p->mem_feature, ctx->mem_on);
-        tot = (long)m * H;
-        hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
-                           d_off, m, F, p->d_W1, F, (const float *)nullptr, H, ctx->proj_off,
-                           p->mem_feature, ctx->mem_off);
+    const mf_predictor *p0 = &preds[0];
+    const int F = p0->F;
+    const bool typed = d_type != nullptr;
+    if (typed) {
+        hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->colmark);
+        hipLaunchKernelGGL(type_segments_kernel, dim3(1), dim3(1024), 0, ctx->stream, d_type, n, n_types,
+                           ctx->type_segment, ctx->colmark);
         MF_HIP(hipGetLastError());
+        int bad = 0;
+        MF_HIP(hipMemcpyAsync(&bad, ctx->colmark, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+        MF_HIP(hipStreamSynchronize(ctx->stream));
+        if (bad) return MF_ERR_ARG;
     }
+    MF_HIP(hipEventRecord(ctx->ev[0], ctx->stream));
+    hipLaunchKernelGGL(gather_feature_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, d_on, n, F,
+                       p0->mem_feature, ctx->mem_on);
+    hipLaunchKernelGGL(gather_feature_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, d_off, m, F,
+                       p0->mem_feature, ctx->mem_off);
     // Pairs whose memory fractions do not fit get no score, so unless the caller wants every
     // score, walk rows and columns in memory order: the pairs that cannot fit then form one
     // corner of the tile grid and the kernel leaves them out.  Results land at the same places.
     const bool by_memory = ctx->fit_order && !d_sigma;
     hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->pairs_evaluated);
+    if (by_memory || typed) order_by_memory(ctx, ctx->mem_on, d_type, n, ctx->order_on);
     if (by_memory) {
-        order_by_memory(ctx, ctx->mem_on, n, ctx->order_on);
-        order_by_memory(ctx, ctx->mem_off, m, ctx->order_off);
+        order_by_memory(ctx, ctx->mem_off, nullptr, m, ctx->order_off);
         const int chunks = (m + 4095) / 4096 < 16 ? (m + 4095) / 4096 : 16;
         const int wide = ((uintptr_t)d_W & 15u) == 0 && (ldw & 3) == 0;
         hipLaunchKernelGGL(fit_mask_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->mem_on, ctx->mem_off,
-                           n, m, p->mem_limit, d_W, ldw, wide);
-        MF_HIP(hipGetLastError());
+                           n, m, p0->mem_limit, d_W, ldw, wide);
     }
+    MF_HIP(hipGetLastError());
     ctx->pairs_total = (double)n * (double)m;
-    MF_HIP(hipEventRecord(ctx->ev[1], ctx->stream));
-    const int32_t *rmap = by_memory ? ctx->order_on : nullptr, *cmap = by_memory ? ctx->order_off : nullptr;
-    int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, d_W, ldw, d_sigma, rmap, cmap, by_memory)
-                       : launch_pair<128>(ctx, p, n, m, d_W, ldw, d_sigma, rmap, cmap, by_memory);
-    if (rc != MF_OK) return rc;
+    const int32_t *rmap = (by_memory || typed) ? ctx->order_on : nullptr, *cmap = by_memory ? ctx->order_off : nullptr;
+    for (int t = 0; t < n_types; ++t) {
+        const mf_predictor *p = &preds[t];
+        const int H = p->H;
+        long tot = (long)n * H;
+        hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
+                           d_on, n, F, p->d_W1, 0, p->d_b1, H, ctx->proj_on);
+        tot = (long)m * H;
+        hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
+                           d_off, m, F, p->d_W1, F, (const float *)nullptr, H, ctx->proj_off);
+        MF_HIP(hipGetLastError());
+        if (t == 0) MF_HIP(hipEventRecord(ctx->ev[1], ctx->stream));      // later types' projections count as scoring
+        const int32_t *segment = typed ? ctx->type_segment + t : nullptr;
+        int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, d_W, ldw, d_sigma, rmap, cmap, by_memory, segment)
+                           : launch_pair<128>(ctx, p, n, m, d_W, ldw, d_sigma, rmap, cmap, by_memory, segment);
+        if (rc != MF_OK) return rc;
+    }
     MF_HIP(hipEventRecord(ctx->ev[2], ctx->stream));
     ctx->score_pending = true;
     return MF_OK;
 }
 
 namespace {
-
-__global__ void fill_flag_kernel(int *flag) { *flag = 0; }
 
 __global__ void check_indices_kernel(const int32_t *__restrict__ list, int count, int limit, int *bad)
 {
@@ -372,10 +446,13 @@ int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int
     MF_HIP(hipEventRecord(ctx->ev[0], ctx->stream));
     long tot = (long)n * H;
     hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
-                       d_on, n, F, p->d_W1, 0, p->d_b1, H, ctx->proj_on, p->mem_feature, ctx->mem_on);
+                       d_on, n, F, p->d_W1, 0, p->d_b1, H, ctx->proj_on);
     tot = (long)m * H;
     hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
-                       d_off, m, F, p->d_W1, F, (const float *)nullptr, H, ctx->proj_off,
+                       d_off, m, F, p->d_W1, F, (const float *)nullptr, H, ctx->proj_off);
+    hipLaunchKernelGGL(gather_feature_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, d_on, n, F,
+                       p->mem_feature, ctx->mem_on);
+    hipLaunchKernelGGL(gather_feature_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, d_off, m, F,
                        p->mem_feature, ctx->mem_off);
     MF_HIP(hipGetLastError());
     hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->pairs_evaluated);

@@ -106,6 +106,20 @@ def predictor_params(seed, F, H):
     }
 
 
+def gpu_types(seed, n, n_types):
+    """GPU type of each online workload's device: type t has a share proportional to 1/(t+1)
+    (a cluster holds a few GPU generations in uneven numbers).  Returns int32 [n]."""
+    share = 1.0 / np.arange(1, n_types + 1)
+    edges = np.cumsum(share / share.sum())
+    u = rng.uniform53(seed, rng.STREAM_TYPE, n)
+    return np.minimum(np.searchsorted(edges, u, side="right"), n_types - 1).astype(np.int32)
+
+
+def typed_predictors(seed, F, hidden):
+    """One predictor per GPU type, hidden[t] wide, drawn from seeds seed, seed + 1000, ..."""
+    return [predictor_params(seed + 1000 * t, F, H) for t, H in enumerate(hidden)]
+
+
 def scheduling_round(config, seed, n=None, m=None):
     """Feature matrices and predictor for one named configuration.
 

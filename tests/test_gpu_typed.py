@@ -1,0 +1,97 @@
+"""GPU parity: one predictor per GPU type (mf_score_pairs_typed, mf_schedule_round_typed)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from gpu_util import dev, dev_params, empty_matrix, weight_tolerance
+
+pytestmark = pytest.mark.gpu
+INF = synth.INFEASIBLE
+
+
+@pytest.fixture(scope="module")
+def mm():
+    import paper_2303_13803_amd as mm
+    return mm
+
+
+def _case(cfg, seed, n, m, hidden):
+    r = synth.scheduling_round(cfg, seed, n=n, m=m)
+    r["plist"] = synth.typed_predictors(seed + 7, r["cfg"].F, hidden)
+    r["types"] = synth.gpu_types(seed, r["n"], len(hidden))
+    return r
+
+
+@pytest.mark.parametrize("cfg,n,m,hidden", [("C1", None, None, [64, 64]), ("C3", 150, 700, [128, 64, 128]),
+                                            ("C4", 300, 1031, [128, 128, 128, 64]), ("C5", 257, 300, [64, 128]),
+                                            ("C2", 5, 9, [64, 128, 64])])
+def test_typed_scores_match_checker(mm, orc, cfg, n, m, hidden):
+    r = _case(cfg, 3, n, m, hidden)
+    n, m, S = r["n"], r["m"], r["cfg"].scale
+    ctx = mm.Context(n, m)
+    preds = [ctx.predictor(dev_params(p), S) for p in r["plist"]]
+    x_on, x_off, types = dev(r["x_on"]), dev(r["x_off"]), dev(r["types"])
+    sig, W = orc.score_pairs_typed(r["x_on"], r["x_off"], r["plist"], r["types"], S)
+    ok = W != INF
+    # every score, natural column order
+    Wd = empty_matrix(n, m); sg = torch.empty((n, m), dtype=torch.float32, device="cuda")
+    ctx.score_pairs_typed(preds, types, x_on, x_off, Wd, sg)
+    torch.cuda.synchronize()
+    Wg = Wd.cpu().numpy()
+    assert (Wg[:, m:] == -7).all()
+    Wg = Wg[:, :m]
+    assert ((Wg == INF) == (W == INF)).all(), "mask bits differ"
+    rel = np.abs(sg.cpu().numpy().astype(np.float64) - sig) / sig
+    assert rel.max() <= 1e-5, f"score relative error {rel.max():.3e}"
+    assert np.abs(Wg[ok].astype(np.int64) - W[ok].astype(np.int64)).max() <= weight_tolerance(S)
+    # weights only: memory order with skipping gives the same matrix
+    Wd2 = empty_matrix(n, m)
+    ctx.score_pairs_typed(preds, types, x_on, x_off, Wd2)
+    torch.cuda.synchronize()
+    assert (Wd2.cpu().numpy()[:, :m] == Wg).all()
+    assert ok.mean() - 1e-6 <= ctx.last_timings()["pairs_evaluated_fraction"] <= 1.0
+    ctx.close()
+
+
+def test_one_type_equals_the_plain_call(mm):
+    r = _case("C3", 2, 200, 333, [128])
+    ctx = mm.Context(200, 333)
+    pred = ctx.predictor(dev_params(r["plist"][0]), r["cfg"].scale)
+    x_on, x_off = dev(r["x_on"]), dev(r["x_off"])
+    A, B = empty_matrix(200, 333), empty_matrix(200, 333)
+    ctx.score_pairs(pred, x_on, x_off, A)
+    ctx.score_pairs_typed([pred], dev(np.zeros(200, np.int32)), x_on, x_off, B)
+    torch.cuda.synchronize()
+    assert torch.equal(A, B)
+    ctx.close()
+
+
+def test_typed_round_and_errors(mm, orc):
+    r = _case("C3", 5, 400, 900, [128, 64, 128])
+    n, m, S = r["n"], r["m"], r["cfg"].scale
+    ctx = mm.Context(n, m)
+    preds = [ctx.predictor(dev_params(p), S) for p in r["plist"]]
+    W = empty_matrix(n, m)
+    r2c = torch.empty(n, dtype=torch.int32, device="cuda")
+    u = torch.empty(n, dtype=torch.int64, device="cuda"); v = torch.empty(m, dtype=torch.int64, device="cuda")
+    res = ctx.schedule_round_typed(preds, dev(r["types"]), dev(r["x_on"]), dev(r["x_off"]), W, r2c, u, v)
+    Wg = W.cpu().numpy()[:, :m]
+    _, Wc = orc.score_pairs_typed(r["x_on"], r["x_off"], r["plist"], r["types"], S)
+    assert ((Wg == INF) == (Wc == INF)).all()
+    okm = Wc != INF
+    assert np.abs(Wg[okm].astype(np.int64) - Wc[okm].astype(np.int64)).max() <= weight_tolerance(S)
+    assert res.cert_ok == 1 and res.primal == orc.max_weight_matching(Wg)[0]
+    code, P, D = orc.check_certificate(Wg, r2c.cpu().numpy(), u.cpu().numpy(), v.cpu().numpy(), res.K)
+    assert code == 0 and (P, D) == (res.primal, res.dual)
+    # a type outside [0, n_types)
+    bad = r["types"].copy(); bad[17] = 3
+    with pytest.raises(mm.MuxmatchError) as e:
+        ctx.score_pairs_typed(preds, dev(bad), dev(r["x_on"]), dev(r["x_off"]), W)
+    assert e.value.code == mm.ERR_ARG
+    # predictors that disagree on the quantisation scale
+    other = ctx.predictor(dev_params(r["plist"][1]), 255.0)
+    with pytest.raises(mm.MuxmatchError) as e:
+        ctx.score_pairs_typed([preds[0], other], dev(np.zeros(n, np.int32)), dev(r["x_on"]), dev(r["x_off"]), W)
+    assert e.value.code == mm.ERR_ARG
+    ctx.close()

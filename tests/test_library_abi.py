@@ -21,7 +21,7 @@ def test_header_declares_the_three_named_calls():
 
 
 def test_library_exports_every_declared_function():
-    assert os.path.exists(LIB), "build the library first: python -m paper_2303_13803_amd.build"
+    assert os.path.exists(LIB), "build the library first: python paper_2303_13803_amd/build.py"
     lib = C.CDLL(LIB)
     for name in _declared_functions():
         assert hasattr(lib, name), f"{name} is declared in muxmatch.h but not exported"

@@ -108,3 +108,23 @@ def test_uniform_mask_fraction_matches_closed_form():
         assert abs((2 - 1 / c) ** 2 / 2 - target) < 0.01
         realised = ((r["x_on"][:, 0][:, None] + r["x_off"][:, 0][None, :]) > np.float32(1)).mean()
         assert abs(realised - target) < 2e-3
+
+
+def test_typed_scoring_is_a_per_row_choice_of_predictor(orc):
+    """Pins score_pairs_typed: with one type it is score_pairs; with several, each row equals a
+    one-row call under its own type's parameters (checked row by row)."""
+    F, n, m = 16, 23, 31
+    x_on = synth.uniform_features(5, 0, n, F); x_off = synth.uniform_features(5, 1, m, F)
+    plist = synth.typed_predictors(9, F, [64, 128, 64])
+    types = synth.gpu_types(5, n, 3)
+    assert set(types.tolist()) == {0, 1, 2} and (np.bincount(types)[0] > np.bincount(types)[2])
+    S = float(2 ** 20)
+    s1, w1 = orc.score_pairs_typed(x_on, x_off, plist[:1], np.zeros(n, np.int32), S)
+    s0, w0 = orc.score_pairs(x_on, x_off, plist[0], S)
+    assert (s1 == s0).all() and (w1 == w0).all()
+    st, wt = orc.score_pairs_typed(x_on, x_off, plist, types, S)
+    for i in range(n):
+        si, wi = orc.score_pairs(x_on[i:i + 1], x_off, plist[types[i]], S)
+        assert (st[i] == si[0]).all() and (wt[i] == wi[0]).all()
+    with pytest.raises(ValueError):
+        orc.score_pairs_typed(x_on, x_off, plist, np.full(n, 3, np.int32), S)
