@@ -143,7 +143,7 @@ def main():
         "stage_ms": {k: avg[k] for k in ("projections_ms", "pair_scoring_ms", "transpose_ms", "auction_ms",
                                          "duals_ms", "certificate_ms")},
         "auction": {"phases": res.phases, "rounds": res.rounds, "bids": res.bids,
-                    "bytes_scanned": res.bytes_scanned, "chain_bids": res.chain_bids, "chain_depth": res.chain_depth, "chain_retries": res.chain_retries, "team_bids": res.team_bids, "matched": res.matched,
+                    "bytes_scanned": res.bytes_scanned, "chain_bids": res.chain_bids, "chain_depth": res.chain_depth, "chain_retries": res.chain_retries, "team_bids": res.team_bids, "path_steps": res.path_steps, "path_scans": res.path_scans, "matched": res.matched,
                     "primal": res.primal, "cert_ok": res.cert_ok},
         "roofline": {"bound": "mfma", "kernel": "pair_mlp_kernel", "achieved": achieved / 1e12,
                      "peak": MFMA_FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_FP32_PEAK,

@@ -97,6 +97,8 @@ typedef struct {
     int64_t chain_depth;        /* longest per-workgroup bid sequence, summed over them */
     int64_t chain_retries;      /* chain bids that lost and were redone                 */
     int64_t team_bids;          /* chain bids evaluated by several workgroups together  */
+    int64_t path_steps;         /* super-steps of the shortest-augmenting-path searches */
+    int64_t path_scans;         /* line scans those searches made                       */
     int32_t matched;            /* rows with a partner                                  */
     int32_t phases;             /* epsilon-scaling phases                               */
     int32_t cert_ok;            /* 1: matching valid, duals feasible, 0 <= D - K*P < K  */
@@ -213,13 +215,18 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
 
 /* Solver knobs: "theta" (epsilon divisor per phase, default 8), "max_rounds" (limit on
  * evaluated bids, default 4,000,000,000), "tail_max" (bidder count at or below which one
- * kernel follows the remaining eviction chains to their end, default 512), "chain_grid"
- * (workgroups of that kernel, default 256), "warm_eps_units" (0, the default: mf_schedule_round_update
- * matches from scratch; > 0: from the previous prices at that epsilon, in weight units), "warm_reset_cols", "team_size" / "team_threads"
- * (workgroups per chain and threads per workgroup of the kernel that shares chains, default
- * 16 / 1024), "team_max" (chains at or below which it takes over, default 8), "bulk_shape" (0..4: threads x lines per workgroup
- * in rounds with many bidders: 256x1, 64x4 (default), 64x2, 128x4, 256x4), "fit_order" (1, the default:
- * scoring skips pairs that cannot fit in memory; 0: every pair goes through the MLP). */
+ * kernel follows the remaining eviction chains, default 1024), "chain_grid" (workgroups of
+ * that kernel, default 256), "team_max" (chains at or below which several workgroups share
+ * each chain, default 8), "team_size" / "team_threads" (workgroups per chain and threads per
+ * workgroup there, default 16 / 1024), "path_max" (bidders at or below which each is placed by
+ * a device-wide shortest-augmenting-path search once the chains have gone on for "path_after"
+ * steps, defaults 8 and 256; path_max 0 turns the searches off), "path_width" (widest label
+ * window of a search step, in epsilons, default 1024), "bulk_shape" (0..4: threads x lines
+ * per workgroup in rounds with many bidders: 256x1, 64x4 (default), 64x2, 128x4, 256x4),
+ * "warm_eps_units" (0, the default: mf_schedule_round_update matches from scratch; > 0: from
+ * the previous prices at that epsilon, in weight units), "warm_reset_cols", "fit_order" (1,
+ * the default: scoring skips pairs that cannot fit in memory; 0: every pair goes through the
+ * MLP). */
 int mf_set_option(mf_ctx *ctx, const char *name, int64_t value);
 
 /*

@@ -85,7 +85,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->max_m = max_m;
     ctx->theta = 8;
     ctx->max_rounds = 4000000000ll;
-    ctx->tail_max = 512;
+    ctx->tail_max = 1024;
     ctx->warm_eps_units = 0;
     ctx->warm_reset_cols = true;
     ctx->chain_grid = 256;
@@ -94,6 +94,13 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->team_size = 16;
     ctx->team_threads = 1024;
     ctx->fit_order = true;
+    ctx->path_max = 8;
+    ctx->path_width = 1024;
+    ctx->path_after = 256;
+    {
+        hipDeviceProp_t prop;
+        ctx->n_cus = hipGetDeviceProperties(&prop, device) == hipSuccess ? prop.multiProcessorCount : 0;
+    }
     const size_t nm = (size_t)(max_n > max_m ? max_n : max_m);   // either side may be the one that bids first
     const size_t ldt = ((size_t)max_n + 3) & ~(size_t)3;
     hipError_t e = hipSuccess;
@@ -115,6 +122,14 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->row2col, nm));
     TRY(dev_alloc(&ctx->col2row, nm));
     TRY(hipMalloc(&ctx->team_ctl, 32 * 1024));
+    TRY(hipMalloc(&ctx->path_ctl, 16384));
+    TRY(dev_alloc(&ctx->path_label, nm));
+    TRY(dev_alloc(&ctx->path_expanded, nm));
+    for (int k = 0; k < 2; ++k) {
+        TRY(dev_alloc(&ctx->path_pair[k], nm));
+        TRY(dev_alloc(&ctx->path_dist[k], nm));
+    }
+    TRY(dev_alloc(&ctx->path_held, nm));
     TRY(dev_alloc(&ctx->list[0], nm));
     TRY(dev_alloc(&ctx->list[1], nm));
     TRY(dev_alloc(&ctx->colmark, (size_t)max_m));
@@ -139,7 +154,7 @@ int mf_destroy(mf_ctx *ctx)
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->order_on, ctx->order_off, ctx->type_segment, ctx->pairs_evaluated, ctx->wt, ctx->price,
-                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
+                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_pair[0], ctx->path_pair[1], ctx->path_dist[0], ctx->path_dist[1], ctx->path_held, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (ctx->h_stats) (void)hipHostFree(ctx->h_stats);
@@ -297,6 +312,9 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "team_size")) { if (value < 2 || value > 32) return MF_ERR_ARG; ctx->team_size = (int)value; return MF_OK; }
     if (!strcmp(name, "team_threads")) { if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return MF_ERR_ARG; ctx->team_threads = (int)value; return MF_OK; }
     if (!strcmp(name, "chain_grid")) { if (value < 1 || value > 4096) return MF_ERR_ARG; ctx->chain_grid = (int)value; return MF_OK; }
+    if (!strcmp(name, "path_max")) { if (value < 0 || value > 4096) return MF_ERR_ARG; ctx->path_max = (int)value; return MF_OK; }
+    if (!strcmp(name, "path_after")) { if (value < 0) return MF_ERR_ARG; ctx->path_after = value; return MF_OK; }
+    if (!strcmp(name, "path_width")) { if (value < 1 || value > (1 << 30)) return MF_ERR_ARG; ctx->path_width = (int)value; return MF_OK; }
     if (!strcmp(name, "fit_order")) { ctx->fit_order = value != 0; return MF_OK; }
     if (!strcmp(name, "max_rounds")) { if (value < 1) return MF_ERR_ARG; ctx->max_rounds = value; return MF_OK; }
     return MF_ERR_ARG;

@@ -629,6 +629,336 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
     }
 }
 
+// The last bidders of a run, placed by shortest augmenting paths.
+//
+// A chain of bids is a greedy walk: every evicted holder moves to its own best
+// alternative, and with one or two bidders left such a walk takes thousands of
+// dependent steps to reach a free line.  The shortest way to make room is far
+// shorter in hops, and finding it is a breadth-type search whose every step is
+// wide.  For a bidder r, in the notation of the header of this file with
+// "rows" the bidding side, let rc(i,k) = pi_i + p_k - K W_ik + eps >= 0 (I1)
+// for every assigned row i and for r (pi_r = best value of r - eps); assigned
+// pairs have rc = eps.  A path r -> k1, holder(k1) -> k2, ... that ends in a
+// column nobody holds, or in a row giving up its column for profit 0 (at extra
+// length pi_i), frees a place for r; label(k) is the length sum(rc) of the
+// shortest such path to column k and d the length of the shortest complete
+// one.  Raising p_k by d - label(k) on every column with label(k) < d (their
+// holders' profits drop by as much) keeps I1 and I2 and makes the shortest
+// path tight; re-assigning along it, each row paying eps more for its new
+// column, keeps them too and leaves one bidder fewer.  Prices only rise, so
+// this mixes freely with bids.  (The successive-shortest-path step of the
+// Hungarian method, on costs relaxed by eps.)
+//
+// All compute units run the search together: labels are corrected in
+// super-steps - every row whose column's label dropped into the current
+// window [low, low + width) is scanned against all columns, in parallel, with
+// an atomic minimum per improved label - separated by grid-wide barriers.
+// Data shared between workgroups moves only through atomics and uncached
+// loads/stores.  Every wait is bounded; if one runs out all workgroups leave,
+// nothing half-done (the price update alone is a valid state), and the host
+// falls back to the chain kernels.
+constexpr int PATH_THREADS = 1024;
+constexpr int PATH_MAX_SLICES = 1024;
+constexpr unsigned PATH_SPIN_LIMIT = 1u << 22;
+constexpr int PATH_GROUP = 16, PATH_MAX_GROUPS = 64;      // up to 1024 workgroups
+constexpr unsigned long long PATH_INF = ~0ull;
+constexpr int PATH_FRONTIER_LOW = 128, PATH_FRONTIER_HIGH = 1024;
+
+struct alignas(128) PathCtl {
+    unsigned long long sink;        // shortest complete path: length << 21 | kind << 20 | id (kind 1: row id gives up)
+    unsigned long long low[2];      // smallest label still to be expanded, per parity
+    unsigned long long first_value; // best value of the current bidder (bits of a double)
+    unsigned int count[2];          // frontier length per parity
+    unsigned int arrive, generation, abort, pad;
+    unsigned long long steps, scans;
+    struct alignas(128) { unsigned int arrive; } group[PATH_MAX_GROUPS];
+};
+
+struct PathBuffers {
+    unsigned long long *label;      // [len] length << 20 | predecessor row
+    unsigned long long *expanded;   // [len] label at which the column's holder was last scanned
+    unsigned long long *fr_pair[2]; // frontier: (column held + 1) << 32 | row
+    double *fr_dist[2];             //           and the row's distance
+    int *held;                      // [rows] column a frontier row holds
+};
+
+// Grid-wide barrier in two levels: workgroups arrive at their group's counter, the last of a
+// group at the top counter, the last of all opens the barrier by advancing `generation`.
+// (Hundreds of atomics on one address take turns; sixteen groups of sixteen do not.)  Counters
+// only ever grow: a level is complete whenever its count is a multiple of its size.
+// Returns false when the wait ran out or another workgroup gave up.
+__device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned &generation)
+{
+    __shared__ int s_ok;
+    // every thread's writes (uncached stores and atomics) are acknowledged by memory before its
+    // workgroup reports in
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int ok = 1;
+        const unsigned groups = (workgroups + PATH_GROUP - 1) / PATH_GROUP;
+        const unsigned g = blockIdx.x / PATH_GROUP;
+        const unsigned size = min((unsigned)PATH_GROUP, workgroups - g * PATH_GROUP);
+        bool opened = false;
+        if ((atomicAdd(&ctl->group[g].arrive, 1u) + 1u) % size == 0u)
+            if ((atomicAdd(&ctl->arrive, 1u) + 1u) % groups == 0u) { atomicAdd(&ctl->generation, 1u); opened = true; }
+        if (!opened) {
+            unsigned spins = 0;
+            while (load_fresh_u32(&ctl->generation) == generation) {
+                ++spins;
+                if (spins > PATH_SPIN_LIMIT || ((spins & 255u) == 0u && load_fresh_u32(&ctl->abort))) { ok = 0; break; }
+            }
+        }
+        if (!ok) atomicExch(&ctl->abort, 1u);
+        else if (load_fresh_u32(&ctl->abort)) ok = 0;
+        s_ok = ok;
+    }
+    ++generation;
+    __syncthreads();
+    return s_ok != 0;
+}
+
+__global__ void path_begin_kernel(mf_device_stats *stats, PathCtl *ctl, int ring)
+{
+    ctl->arrive = 0u; ctl->generation = 0u; ctl->abort = 0u; ctl->steps = 0ull; ctl->scans = 0ull;
+    for (int g = 0; g < PATH_MAX_GROUPS; ++g) ctl->group[g].arrive = 0u;
+    stats->cnt[(ring + 1) & 3] = 0;
+    stats->cnt[(ring + 2) & 3] = 0;
+    stats->rounds += 1ull;
+    stats->chain_depth += stats->launch_max;
+    stats->launch_max = 0;
+}
+
+__device__ inline void store_dual(const SideArgs &s, int k, double dual, int holder_plus_one)
+{
+    store_through(&s.otherword[k], pack_word(dual, holder_plus_one));
+    store_through((unsigned long long *)&s.other_dual[k], (unsigned long long)__double_as_longlong(dual));
+}
+
+__global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const int *__restrict__ list,
+                                                            int *__restrict__ out_list, mf_device_stats *stats,
+                                                            PathCtl *ctl, PathBuffers buf, int ring, int rows,
+                                                            double width_max)
+{
+    __shared__ Top2 red[PATH_THREADS / 64];
+    __shared__ unsigned s_pushes, s_base;
+    __shared__ unsigned long long s_sink, s_low;
+    const unsigned G = gridDim.x;
+    const int wg = blockIdx.x, tid = threadIdx.x;
+    const int gtid = wg * PATH_THREADS + tid, gsize = (int)G * PATH_THREADS;
+    const int count = stats->cnt[ring & 3];
+    unsigned generation = 0;
+    int item = 0;
+    bool alive = true;
+    for (; item < count && alive; ++item) {
+        const int r0 = list[item];
+        // ---- clear the labels; workgroup 0 finds the bidder's best value ----
+        for (int k = gtid; k < s.len; k += gsize) {
+            store_through(&buf.label[k], PATH_INF);
+            store_through(&buf.expanded[k], PATH_INF);
+        }
+        if (wg == 0) {
+            const Top2 t = block_scan<PATH_THREADS>(s.A + (size_t)r0 * s.pitch, s.other_dual, s.len, s.Kd, true,
+                                                    red, 0, 0);
+            if (tid == 0) {
+                const double v1 = t.b1;
+                store_through(&ctl->first_value, (unsigned long long)__double_as_longlong(v1));
+                store_through(&ctl->low[0], PATH_INF);
+                store_through(&ctl->low[1], PATH_INF);
+                __hip_atomic_store(&ctl->count[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&ctl->count[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (v1 > s.eps) {
+                    const double profit = v1 - s.eps;                   // pi_r: rc(r, best column) = 0
+                    store_through(&ctl->sink, ((unsigned long long)(long long)profit << 21) | (1ull << 20) |
+                                                  (unsigned long long)r0);
+                    store_through(&buf.fr_pair[0][0], (unsigned long long)r0);       // holds no column
+                    store_through((unsigned long long *)&buf.fr_dist[0][0], 0ull);
+                    __hip_atomic_store(&buf.held[r0], -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+        if (!grid_barrier(ctl, G, generation)) { alive = false; break; }
+        // duals stand still during a search: drop what the caches hold of them from before the
+        // last re-assignment once, then read them through the caches
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        const double v1 = __longlong_as_double((long long)load_fresh_u64(&ctl->first_value));
+        if (v1 <= s.eps) continue;                                      // rests with dual 0: nothing to move
+        const double first_profit = v1 - s.eps;
+
+        // ---- label-correcting search ----
+        int parity = 0;
+        double low = 0.0;
+        // The window of labels expanded per super-step adapts to what it yields: wide enough to
+        // keep the device busy, narrow enough that rows are not scanned long before their label
+        // is final (every workgroup derives the same width from the same counters).
+        double width = 4.0 * s.eps;
+        unsigned long long my_steps = 0, my_scans = 0;
+        for (;;) {
+            const int nf = (int)load_fresh_u32(&ctl->count[parity]);
+            const double bound = (double)(long long)(load_fresh_u64(&ctl->sink) >> 21);
+            if (nf > PATH_FRONTIER_HIGH) width = fmax(s.eps, width * 0.5);
+            else if (nf < PATH_FRONTIER_LOW) width = fmin(width_max, width * 2.0);
+            if (nf > 0) {
+                // one wavefront per (row, slice of columns): enough independent loads in flight to
+                // stream the rows at memory speed whether the frontier holds one row or thousands
+                constexpr int WAVES = PATH_THREADS / 64;
+                const int total_waves = (int)G * WAVES, wave_id = wg * WAVES + (tid >> 6), lane = tid & 63;
+                int slices = total_waves / nf;
+                slices = slices < 1 ? 1 : (slices > PATH_MAX_SLICES ? PATH_MAX_SLICES : slices);
+                const int span = (((s.len + slices - 1) / slices) + 255) & ~255;
+                slices = (s.len + span - 1) / span;
+                const int items = nf * slices;
+                for (int it = wave_id; it < items; it += total_waves) {
+                    const int e = it / slices, sl = it - e * slices;
+                    const unsigned long long pair = load_fresh_u64(&buf.fr_pair[parity][e]);
+                    const double dist = load_fresh(&buf.fr_dist[parity][e]);
+                    const int i = (int)(pair & 0xffffffffull), mine_col = (int)(pair >> 32) - 1;
+                    const int32_t *row = s.A + (size_t)i * s.pitch;
+                    // the row's profit: what it holds minus that column's dual (the bidder holds nothing)
+                    const double profit = mine_col < 0 ? first_profit
+                                                       : s.Kd * (double)row[mine_col] - s.other_dual[mine_col];
+                    const double base = dist + profit + s.eps;
+                    if (sl == 0 && lane == 0 && mine_col >= 0 && dist + profit < bound)     // it may also give up and rest
+                        atomicMin(&ctl->sink, ((unsigned long long)(long long)(dist + profit) << 21) | (1ull << 20) |
+                                                  (unsigned long long)i);
+                    const int from = sl * span, to = min(s.len, from + span);
+#pragma unroll 2
+                    for (int k = from + lane * 4; k < to; k += 256) {
+                        const int4 w4 = *(const int4 *)(row + k);
+                        const double2 p01 = *(const double2 *)(s.other_dual + k);
+                        const double2 p23 = *(const double2 *)(s.other_dual + k + 2);
+                        const int32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
+                        const double pr[4] = {p01.x, p01.y, p23.x, p23.y};
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const double cand = base - fma(s.Kd, (double)w[q], -pr[q]);
+                            if (k + q < to && w[q] != MF_INFEASIBLE && cand < bound) {
+                                const unsigned long long mine = ((unsigned long long)(long long)cand << MF_ID_BITS) |
+                                                                (unsigned long long)i;
+                                // a cached label is never below the true one (labels only fall during a
+                                // search and the caches were emptied at its start): a safe first test
+                                if (mine < buf.label[k + q]) atomicMin(&buf.label[k + q], mine);
+                            }
+                        }
+                    }
+                    if (sl == 0 && lane == 0) ++my_scans;
+                }
+            }
+            ++my_steps;
+            if (!grid_barrier(ctl, G, generation)) { alive = false; break; }
+
+            // ---- which holders have to be scanned next ----
+            const double sink_now = (double)(long long)(load_fresh_u64(&ctl->sink) >> 21);
+            const double limit = fmin(low + width, sink_now);
+            const int np = parity ^ 1;
+            // Pushes, the sink and the window's next start all meet in single words: every workgroup
+            // first combines its threads' contributions in LDS and then sends one atomic of each.
+            for (int first = 0; first < s.len; first += gsize) {
+                const int k = first + gtid;
+                if (tid == 0) { s_pushes = 0u; s_sink = PATH_INF; s_low = PATH_INF; }
+                __syncthreads();
+                int holder = -1;
+                unsigned slot = 0;
+                unsigned long long d_int = 0;
+                if (k < s.len) {
+                    const unsigned long long lw = load_fresh_u64(&buf.label[k]);
+                    const unsigned long long ex = load_fresh_u64(&buf.expanded[k]);
+                    const unsigned long long cw = load_fresh_u64(&s.otherword[k]);
+                    d_int = lw >> MF_ID_BITS;
+                    const double d = (double)(long long)d_int;
+                    if (lw != PATH_INF && d < sink_now && d_int < ex) {
+                        if (d >= limit) {
+                            atomicMin(&s_low, d_int);
+                        } else if (word_id(cw) < 0) {                       // a column nobody holds ends a path
+                            atomicMin(&s_sink, (d_int << 21) | (unsigned long long)k);
+                        } else {
+                            holder = word_id(cw);
+                            slot = atomicAdd(&s_pushes, 1u);
+                        }
+                    }
+                }
+                __syncthreads();
+                if (tid == 0) {
+                    s_base = s_pushes ? atomicAdd(&ctl->count[np], s_pushes) : 0u;
+                    if (s_sink != PATH_INF) atomicMin(&ctl->sink, s_sink);
+                    if (s_low != PATH_INF) atomicMin(&ctl->low[np], s_low);
+                }
+                __syncthreads();
+                if (holder >= 0) {
+                    const unsigned pos = s_base + slot;
+                    store_through(&buf.expanded[k], d_int);
+                    store_through(&buf.fr_pair[np][pos], ((unsigned long long)(k + 1) << 32) | (unsigned long long)holder);
+                    store_through((unsigned long long *)&buf.fr_dist[np][pos],
+                                  (unsigned long long)__double_as_longlong((double)(long long)d_int));
+                    __hip_atomic_store(&buf.held[holder], k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            if (gtid == 0) {                                                // this parity is refilled after the next barrier
+                __hip_atomic_store(&ctl->count[parity], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                store_through(&ctl->low[parity], PATH_INF);
+            }
+            if (!grid_barrier(ctl, G, generation)) { alive = false; break; }
+            parity = np;
+            if (load_fresh_u32(&ctl->count[parity]) == 0u) {
+                const unsigned long long lo = load_fresh_u64(&ctl->low[parity]);
+                const unsigned long long sk = load_fresh_u64(&ctl->sink) >> 21;
+                if (lo == PATH_INF || lo >= sk) break;                      // every label below the sink is final
+                low = (double)(long long)lo;                                // jump to the next window with work
+            }
+        }
+        if (!alive) break;
+
+        // ---- make the shortest path tight, then re-assign along it ----
+        // Workgroup 0 does both on its own, and only behind one more barrier: passing it proves
+        // that every workgroup finished its share of the search, so no wait that runs out can
+        // leave the duals half-updated or updated from incomplete labels.
+        if (!grid_barrier(ctl, G, generation)) { alive = false; break; }      // r0 not placed: handed back below
+        if (wg == 0) {
+            const unsigned long long sink = load_fresh_u64(&ctl->sink);
+            const unsigned long long d_star = sink >> 21;
+            for (int k = tid; k < s.len; k += PATH_THREADS) {
+                const unsigned long long lw = load_fresh_u64(&buf.label[k]);
+                if (lw == PATH_INF) continue;
+                const unsigned long long d_int = lw >> MF_ID_BITS;
+                if (d_int < d_star) {
+                    const unsigned long long cw = load_fresh_u64(&s.otherword[k]);
+                    store_dual(s, k, word_dual(cw) + (double)(long long)(d_star - d_int), (int)(cw & MF_ID_MASK));
+                }
+            }
+            __threadfence();
+            __syncthreads();
+            if (tid == 0) {
+                const int id = (int)(sink & 0xfffffull);
+                int k = ((sink >> 20) & 1ull) ? (id == r0 ? -1 : __hip_atomic_load(&buf.held[id], __ATOMIC_RELAXED,
+                                                                                     __HIP_MEMORY_SCOPE_AGENT))
+                                              : id;
+                int guard = 0;
+                while (k >= 0 && guard++ <= rows) {
+                    const int i = (int)(load_fresh_u64(&buf.label[k]) & MF_ID_MASK);
+                    const int before = __hip_atomic_load(&buf.held[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    store_dual(s, k, word_dual(load_fresh_u64(&s.otherword[k])) + s.eps, i + 1);
+                    k = (i == r0) ? -1 : before;
+                }
+                atomicAdd(&ctl->steps, my_steps);
+            }
+        }
+        if ((tid & 63) == 0 && my_scans) atomicAdd(&ctl->scans, my_scans);
+        if (!grid_barrier(ctl, G, generation)) { alive = false; ++item; break; }   // r0 is placed
+    }
+    if (gtid == 0) {
+        for (int rest = item; rest < count; ++rest)                         // whoever was not served bids again
+            out_list[atomicAdd(&stats->cnt[(ring + 1) & 3], 1)] = list[rest];
+        if (!alive) atomicExch(&stats->team_abort, 2);
+        const unsigned long long steps = load_fresh_u64(&ctl->steps), scans = load_fresh_u64(&ctl->scans);
+        stats->launch_max = steps;
+        stats->bids += scans;
+        stats->chain_bids += scans;
+        stats->path_steps += steps;
+        stats->path_scans += scans;
+        stats->bytes += scans * (unsigned long long)s.len * 4ull;
+    }
+}
+
 // Start of an epsilon phase: drop the assignment, keep the duals, all rows bid.
 __global__ void reset_kernel(int n, int m, const double *__restrict__ price,
                              unsigned long long *colword, int *row2col, int *col2row, int *list,
@@ -841,7 +1171,7 @@ __global__ void init_solver_kernel(int n, int m, double *price, double *profit, 
     if (i < m + 4 && (!keep_prices || i >= m)) price[i] = 0.0;
     if (i == 0) {
         stats->rounds = 0; stats->bids = 0; stats->bytes = 0; stats->head = 0;
-        stats->chain_bids = 0; stats->chain_depth = 0; stats->launch_max = 0; stats->chain_retries = 0; stats->team_bids = 0; stats->team_abort = 0; stats->active = 0; stats->max_weight = 0;
+        stats->chain_bids = 0; stats->chain_depth = 0; stats->launch_max = 0; stats->chain_retries = 0; stats->team_bids = 0; stats->path_steps = 0; stats->path_scans = 0; stats->team_abort = 0; stats->active = 0; stats->max_weight = 0;
         stats->cnt[0] = 0; stats->cnt[1] = 0; stats->cnt[2] = 0; stats->cnt[3] = 0;
     }
 }
@@ -871,8 +1201,11 @@ void launch_round(mf_ctx *ctx, const SideArgs &s, int count, int ring)
 int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
 {
     int ring = 0;
+    // Short chains are cheapest followed step by step; a chain that is still going after
+    // `path_after` steps is ended by shortest-path searches instead.
+    long long team_steps = 0;
     while (count > 0) {
-        bool timed = false;
+        bool timed = false, ran_teams = false;
         const long long left = ctx->max_rounds - (long long)ctx->h_stats->bids;
         if (left <= 0) return MF_ERR_NOT_CONVERGED;
         if (count > ctx->tail_max) {
@@ -883,9 +1216,25 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
                 if (time_first && r == 0) MF_HIP(hipEventRecord(ctx->ev[7], ctx->stream));
                 ++ring;
             }
+        } else if (ctx->path_max > 0 && count <= ctx->path_max && !ctx->path_off && ctx->n_cus > 0 &&
+                   (team_steps >= ctx->path_after || count > ctx->team_max || ctx->team_max == 0 || ctx->team_off)) {
+            // few enough bidders, and chains long enough, to place each bidder by a shortest-path
+            // search over the whole device
+            PathBuffers buf{ctx->path_label, ctx->path_expanded, {ctx->path_pair[0], ctx->path_pair[1]},
+                            {ctx->path_dist[0], ctx->path_dist[1]}, ctx->path_held};
+            hipLaunchKernelGGL(path_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats,
+                               (PathCtl *)ctx->path_ctl, ring);
+            hipLaunchKernelGGL(path_kernel, dim3(ctx->n_cus), dim3(PATH_THREADS), 0, ctx->stream, s,
+                               ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, (PathCtl *)ctx->path_ctl,
+                               buf, ring, ctx->max_n > ctx->max_m ? ctx->max_n : ctx->max_m,
+                               (double)ctx->path_width * s.eps);
+            ++ring;
         } else if (count > ctx->team_max || ctx->team_max == 0 || ctx->team_off) {
             const int grid = count < ctx->chain_grid ? count : ctx->chain_grid;
-            const int hand_back = ctx->team_off ? -1 : ctx->team_max;
+            const bool paths = ctx->path_max > 0 && !ctx->path_off && ctx->n_cus > 0;
+            const bool teams = ctx->team_max > 0 && !ctx->team_off;
+            const int hand_back = (paths && (!teams || ctx->path_max > ctx->team_max)) ? ctx->path_max
+                                                                                       : (teams ? ctx->team_max : -1);
             hipLaunchKernelGGL(chain_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats, ring, grid);
             hipLaunchKernelGGL(chain_kernel, dim3(grid), dim3(CHAIN_THREADS), 0, ctx->stream, s,
                                ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, ring,
@@ -893,29 +1242,33 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
             ++ring;
         } else {
             const int teams = count < ctx->team_max ? count : ctx->team_max;
+            const bool paths = ctx->path_max > 0 && !ctx->path_off && ctx->n_cus > 0 && count <= ctx->path_max;
+            long long team_cap = left / teams + 1;
+            if (paths && ctx->path_after - team_steps < team_cap) team_cap = ctx->path_after - team_steps;
+            ran_teams = true;
             hipLaunchKernelGGL(team_begin_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->stats,
                                (TeamCtl *)ctx->team_ctl, ring);
             const dim3 grid(teams * ctx->team_size);
             if (ctx->team_threads == 64)
                 hipLaunchKernelGGL(team_kernel<64>, grid, dim3(64), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   left / teams + 1, ctx->team_size);
+                                   team_cap, ctx->team_size);
             else if (ctx->team_threads == 128)
                 hipLaunchKernelGGL(team_kernel<128>, grid, dim3(128), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   left / teams + 1, ctx->team_size);
+                                   team_cap, ctx->team_size);
             else if (ctx->team_threads == 256)
                 hipLaunchKernelGGL(team_kernel<256>, grid, dim3(256), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   left / teams + 1, ctx->team_size);
+                                   team_cap, ctx->team_size);
             else if (ctx->team_threads == 512)
                 hipLaunchKernelGGL(team_kernel<512>, grid, dim3(512), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   left / teams + 1, ctx->team_size);
+                                   team_cap, ctx->team_size);
             else
                 hipLaunchKernelGGL(team_kernel<1024>, grid, dim3(1024), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   left / teams + 1, ctx->team_size);
+                                   team_cap, ctx->team_size);
             ++ring;
         }
         MF_HIP(hipGetLastError());
@@ -930,7 +1283,9 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
         }
         time_first = false;
         count = ctx->h_stats->cnt[ring & 3];
-        if (ctx->h_stats->team_abort) ctx->team_off = true;   // a bounded wait ran out: one workgroup per chain from now on
+        if (ran_teams) team_steps += (long long)ctx->h_stats->launch_max;     // the longest any leader went
+        if (ctx->h_stats->team_abort == 1) ctx->team_off = true;   // a bounded wait ran out: one workgroup per chain from now on
+        if (ctx->h_stats->team_abort == 2) ctx->path_off = true;   // ... or no more shortest-path searches
     }
     return MF_OK;
 }
@@ -1079,6 +1434,8 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     h_res->chain_bids = (int64_t)ctx->h_stats->chain_bids;
     h_res->chain_retries = (int64_t)ctx->h_stats->chain_retries;
     h_res->team_bids = (int64_t)ctx->h_stats->team_bids;
+    h_res->path_steps = (int64_t)ctx->h_stats->path_steps;
+    h_res->path_scans = (int64_t)ctx->h_stats->path_scans;
     h_res->chain_depth = (int64_t)(ctx->h_stats->chain_depth + ctx->h_stats->launch_max);
     h_res->phases = phases;
     h_res->ms_solve = ms_solve;

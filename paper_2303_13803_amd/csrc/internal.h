@@ -33,12 +33,14 @@ struct mf_device_stats {            // lives in device memory, cleared per solve
     unsigned long long chain_depth; // sum over chain kernels of the most bids any one workgroup evaluated
     unsigned long long chain_retries; // chain bids that lost and were redone with uncached dual reads
     unsigned long long team_bids;   // chain bids evaluated by several workgroups together
+    unsigned long long path_steps;  // super-steps of the shortest-path searches
+    unsigned long long path_scans;  // line scans those searches made
     unsigned long long launch_max;  // scratch: that maximum for the chain kernel in flight
     int max_weight;
     int cnt[4];                     // ring of bidder-list lengths: round r reads cnt[r & 3]
     int head;                       // next unclaimed entry of the list a chain kernel works through
     int active;                     // workgroups of the running chain kernel still following a chain
-    int team_abort;                 // a bounded wait between cooperating workgroups ran out
+    int team_abort;                 // a bounded wait between cooperating workgroups ran out (1: chain teams, 2: path search)
 };
 
 struct mf_cert_out {                // lives in device memory, cleared per check
@@ -76,6 +78,16 @@ struct mf_ctx {
     int team_size, team_threads;    // workgroups per chain, threads per such workgroup
     bool team_off;                  // set after a team wait ran out
     void *team_ctl;                 // control blocks of the cooperating workgroups
+    void *path_ctl;                 // control block of the shortest-path search
+    unsigned long long *path_label, *path_expanded;   // [max(max_n, max_m)] each
+    unsigned long long *path_pair[2];
+    double *path_dist[2];
+    int *path_held;
+    int path_max;                   // bidders at or below which shortest-path searches place them (0: never)
+    long long path_after;           // chain steps per run after which the searches take over
+    int path_width;                 // label window of one super-step, in epsilons
+    bool path_off;                  // set after a wait of the search ran out
+    int n_cus;                      // compute units of the device
     int chain_grid;                 // workgroups of that kernel
     int *list[2];
     int *colmark;                   // [max_m]
