@@ -221,7 +221,9 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
  * workgroup there, default 16 / 1024), "path_max" (bidders at or below which each is placed by
  * a device-wide shortest-augmenting-path search once the chains have gone on for "path_after"
  * steps, defaults 8 and 256; path_max 0 turns the searches off), "path_width" (widest label
- * window of a search step, in epsilons, default 1024), "bulk_shape" (0..4: threads x lines
+ * window of a search step, in epsilons, default 1024), "path_spin_limit" (polls a workgroup of a
+ * search waits for the others before all give up and the chains take over again, default 2^22;
+ * setting it also re-arms the searches after such a fallback), "bulk_shape" (0..4: threads x lines
  * per workgroup in rounds with many bidders: 256x1, 64x4 (default), 64x2, 128x4, 256x4),
  * "warm_eps_units" (0, the default: mf_schedule_round_update matches from scratch; > 0: from
  * the previous prices at that epsilon, in weight units), "warm_reset_cols", "fit_order" (1,

@@ -97,6 +97,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->path_max = 8;
     ctx->path_width = 1024;
     ctx->path_after = 256;
+    ctx->path_spin_limit = 1u << 22;
     {
         hipDeviceProp_t prop;
         ctx->n_cus = hipGetDeviceProperties(&prop, device) == hipSuccess ? prop.multiProcessorCount : 0;
@@ -313,6 +314,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "team_threads")) { if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return MF_ERR_ARG; ctx->team_threads = (int)value; return MF_OK; }
     if (!strcmp(name, "chain_grid")) { if (value < 1 || value > 4096) return MF_ERR_ARG; ctx->chain_grid = (int)value; return MF_OK; }
     if (!strcmp(name, "path_max")) { if (value < 0 || value > 4096) return MF_ERR_ARG; ctx->path_max = (int)value; return MF_OK; }
+    if (!strcmp(name, "path_spin_limit")) { if (value < 0 || value > (1ll << 30)) return MF_ERR_ARG; ctx->path_spin_limit = (unsigned)value; ctx->path_off = false; return MF_OK; }
     if (!strcmp(name, "path_after")) { if (value < 0) return MF_ERR_ARG; ctx->path_after = value; return MF_OK; }
     if (!strcmp(name, "path_width")) { if (value < 1 || value > (1 << 30)) return MF_ERR_ARG; ctx->path_width = (int)value; return MF_OK; }
     if (!strcmp(name, "fit_order")) { ctx->fit_order = value != 0; return MF_OK; }

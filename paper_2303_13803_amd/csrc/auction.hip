@@ -659,7 +659,6 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
 // falls back to the chain kernels.
 constexpr int PATH_THREADS = 1024;
 constexpr int PATH_MAX_SLICES = 1024;
-constexpr unsigned PATH_SPIN_LIMIT = 1u << 22;
 constexpr int PATH_GROUP = 16, PATH_MAX_GROUPS = 64;      // up to 1024 workgroups
 constexpr unsigned long long PATH_INF = ~0ull;
 constexpr int PATH_FRONTIER_LOW = 128, PATH_FRONTIER_HIGH = 1024;
@@ -687,7 +686,7 @@ struct PathBuffers {
 // (Hundreds of atomics on one address take turns; sixteen groups of sixteen do not.)  Counters
 // only ever grow: a level is complete whenever its count is a multiple of its size.
 // Returns false when the wait ran out or another workgroup gave up.
-__device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned &generation)
+__device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned &generation, unsigned spin_limit)
 {
     __shared__ int s_ok;
     // every thread's writes (uncached stores and atomics) are acknowledged by memory before its
@@ -706,7 +705,7 @@ __device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned 
             unsigned spins = 0;
             while (load_fresh_u32(&ctl->generation) == generation) {
                 ++spins;
-                if (spins > PATH_SPIN_LIMIT || ((spins & 255u) == 0u && load_fresh_u32(&ctl->abort))) { ok = 0; break; }
+                if (spins > spin_limit || ((spins & 255u) == 0u && load_fresh_u32(&ctl->abort))) { ok = 0; break; }
             }
         }
         if (!ok) atomicExch(&ctl->abort, 1u);
@@ -738,7 +737,7 @@ __device__ inline void store_dual(const SideArgs &s, int k, double dual, int hol
 __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const int *__restrict__ list,
                                                             int *__restrict__ out_list, mf_device_stats *stats,
                                                             PathCtl *ctl, PathBuffers buf, int ring, int rows,
-                                                            double width_max)
+                                                            double width_max, unsigned spin_limit)
 {
     __shared__ Top2 red[PATH_THREADS / 64];
     __shared__ unsigned s_pushes, s_base;
@@ -777,7 +776,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                 }
             }
         }
-        if (!grid_barrier(ctl, G, generation)) { alive = false; break; }
+        if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
         // duals stand still during a search: drop what the caches hold of them from before the
         // last re-assignment once, then read them through the caches
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -845,7 +844,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                 }
             }
             ++my_steps;
-            if (!grid_barrier(ctl, G, generation)) { alive = false; break; }
+            if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
 
             // ---- which holders have to be scanned next ----
             const double sink_now = (double)(long long)(load_fresh_u64(&ctl->sink) >> 21);
@@ -897,7 +896,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                 __hip_atomic_store(&ctl->count[parity], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 store_through(&ctl->low[parity], PATH_INF);
             }
-            if (!grid_barrier(ctl, G, generation)) { alive = false; break; }
+            if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
             parity = np;
             if (load_fresh_u32(&ctl->count[parity]) == 0u) {
                 const unsigned long long lo = load_fresh_u64(&ctl->low[parity]);
@@ -912,7 +911,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         // Workgroup 0 does both on its own, and only behind one more barrier: passing it proves
         // that every workgroup finished its share of the search, so no wait that runs out can
         // leave the duals half-updated or updated from incomplete labels.
-        if (!grid_barrier(ctl, G, generation)) { alive = false; break; }      // r0 not placed: handed back below
+        if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }      // r0 not placed: handed back below
         if (wg == 0) {
             const unsigned long long sink = load_fresh_u64(&ctl->sink);
             const unsigned long long d_star = sink >> 21;
@@ -943,7 +942,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
             }
         }
         if ((tid & 63) == 0 && my_scans) atomicAdd(&ctl->scans, my_scans);
-        if (!grid_barrier(ctl, G, generation)) { alive = false; ++item; break; }   // r0 is placed
+        if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; ++item; break; }   // r0 is placed
     }
     if (gtid == 0) {
         for (int rest = item; rest < count; ++rest)                         // whoever was not served bids again
@@ -1227,7 +1226,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
             hipLaunchKernelGGL(path_kernel, dim3(ctx->n_cus), dim3(PATH_THREADS), 0, ctx->stream, s,
                                ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, (PathCtl *)ctx->path_ctl,
                                buf, ring, ctx->max_n > ctx->max_m ? ctx->max_n : ctx->max_m,
-                               (double)ctx->path_width * s.eps);
+                               (double)ctx->path_width * s.eps, ctx->path_spin_limit);
             ++ring;
         } else if (count > ctx->team_max || ctx->team_max == 0 || ctx->team_off) {
             const int grid = count < ctx->chain_grid ? count : ctx->chain_grid;

@@ -86,6 +86,7 @@ struct mf_ctx {
     int path_max;                   // bidders at or below which shortest-path searches place them (0: never)
     long long path_after;           // chain steps per run after which the searches take over
     int path_width;                 // label window of one super-step, in epsilons
+    unsigned path_spin_limit;       // polls a workgroup waits at a barrier of the search before it gives up
     bool path_off;                  // set after a wait of the search ran out
     int n_cus;                      // compute units of the device
     int chain_grid;                 // workgroups of that kernel

@@ -1,0 +1,93 @@
+"""GPU parity for the end of a run: bidders placed by shortest-augmenting-path searches.
+
+The searches replace chains of bids, so the optimum (bit-exact against the exact CPU solver), the
+validity of the matching and the host-verified duals are the whole contract; the cases force the
+searches on from the first chain step, widen them to many bidders, and cut their waits short so
+that they give up half-way and the chains take over again."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from gpu_util import padded_matrix
+
+pytestmark = pytest.mark.gpu
+INF = synth.INFEASIBLE
+
+
+@pytest.fixture(scope="module")
+def mm():
+    import paper_2303_13803_amd as mm
+    return mm
+
+
+def _solve_and_verify(ctx, orc, W, expect):
+    n, m = W.shape
+    r2c = torch.empty(n, dtype=torch.int32, device="cuda")
+    u = torch.empty(n, dtype=torch.int64, device="cuda")
+    v = torch.empty(m, dtype=torch.int64, device="cuda")
+    res = ctx.solve_assignment(padded_matrix(W), n, m, r2c, u, v)
+    code, P, D = orc.check_certificate(W, r2c.cpu().numpy(), u.cpu().numpy(), v.cpu().numpy(), res.K)
+    assert code == 0 and res.cert_ok == 1
+    assert (P, D) == (res.primal, res.dual)
+    assert res.primal == expect
+    return res
+
+
+def _cases():
+    yield "uniform square", synth.uniform_matrix(41, 700, 700, 2 ** 20, 0.1)
+    yield "uniform wide, reverse rounds", synth.uniform_matrix(42, 400, 900, 2 ** 24, 0.3)
+    yield "more rows than columns", synth.uniform_matrix(43, 900, 350, 2 ** 20, 0.2)
+    yield "few levels, nested neighbourhoods", synth.threshold_matrix(44, 500, 800, 256, 0.9)
+    yield "rank one", synth.rank_one_matrix(45, 300, 450, 2 ** 20)[0]
+    yield "planted", synth.planted_matrix(46, 300, 400, 2 ** 20)[0]
+    yield "constant", np.full((200, 300), 77, np.int32)
+    yield "single row", synth.uniform_matrix(47, 1, 50, 1000, 0.0)
+    yield "nothing feasible", np.full((60, 70), INF, np.int32)
+
+
+def _optimum(orc, W):
+    n, m = W.shape
+    return orc.max_weight_matching(W if n <= m else np.ascontiguousarray(W.T))[0]
+
+
+@pytest.mark.parametrize("options", [{"path_after": 0}, {"path_after": 0, "path_max": 64, "team_max": 0},
+                                     {"path_after": 0, "path_width": 1}, {"path_after": 40}])
+def test_searches_reach_the_optimum(mm, orc, options):
+    used = 0
+    for name, W in _cases():
+        ctx = mm.Context(*W.shape)
+        for k, val in options.items():
+            ctx.set_option(k, val)
+        res = _solve_and_verify(ctx, orc, W, _optimum(orc, W))
+        used += res.path_steps
+        ctx.close()
+    assert used > 0, "no search ran: the cases no longer exercise this path"
+
+
+def test_scored_round_with_searches_only(mm, orc):
+    r = synth.scheduling_round("C4", 3, n=1500, m=1500)
+    W = orc.score_pairs(r["x_on"], r["x_off"], r["params"], r["cfg"].scale, wide=False)[1]
+    ctx = mm.Context(1500, 1500)
+    ctx.set_option("path_after", 0)
+    res = _solve_and_verify(ctx, orc, W, orc.max_weight_matching(W)[0])
+    assert res.path_steps > 0 and res.team_bids == 0
+    ctx.close()
+
+
+@pytest.mark.parametrize("polls", [0, 3, 40])
+def test_a_search_that_gives_up_hands_back_to_the_chains(mm, orc, polls):
+    """The waits between the workgroups of a search are bounded; with a bound of a few polls they
+    run out at arbitrary points.  Whatever was reached must still be a valid state: the chains
+    finish the run and the result is the exact optimum."""
+    W = synth.uniform_matrix(48, 800, 800, 2 ** 20, 0.1)
+    expect = orc.max_weight_matching(W)[0]
+    ctx = mm.Context(800, 800)
+    ctx.set_option("path_after", 0)
+    for attempt in range(3):
+        ctx.set_option("path_spin_limit", polls)          # also re-arms the searches
+        _solve_and_verify(ctx, orc, W, expect)
+    ctx.set_option("path_spin_limit", 1 << 22)
+    res = _solve_and_verify(ctx, orc, W, expect)
+    assert res.path_steps > 0
+    ctx.close()
