@@ -28,7 +28,7 @@ def lib():
         _lib.orc_score_pairs.restype = C.c_int
         _lib.orc_score_pairs.argtypes = [_f32p, C.c_int, _f32p, C.c_int, C.c_int, C.c_int,
                                          _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, C.c_float,
-                                         C.c_int, C.c_float, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+                                         C.c_int, C.c_float, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         _lib.orc_max_weight_matching.restype = C.c_int
         _lib.orc_max_weight_matching.argtypes = [_i32p, C.c_int, C.c_int, C.c_int64, _i32p, _i64p,
                                                  _i64p, C.POINTER(C.c_int64)]
@@ -47,9 +47,12 @@ def threads():
     return int(lib().orc_threads())
 
 
-def score_pairs(x_on, x_off, params, scale, mem_feature=0, mem_limit=1.0, wide=True, nthreads=0):
+def score_pairs(x_on, x_off, params, scale, mem_feature=0, mem_limit=1.0, wide=True, nthreads=0, sm=None):
     """Scores and quantised weights for every (online, offline) pair.
 
+    sm = (online feature, offline feature): the SM share depends on the pair,
+    sm(u, v) = min(1 - x_u[online feature], x_v[offline feature]), and is a third input of the
+    predictor; params["W1"] then has 2F + 1 columns.
     Returns (sigma float32 [n,m], W int32 [n,m]); masked pairs hold INFEASIBLE in W."""
     x_on = np.ascontiguousarray(x_on, np.float32)
     x_off = np.ascontiguousarray(x_off, np.float32)
@@ -58,12 +61,13 @@ def score_pairs(x_on, x_off, params, scale, mem_feature=0, mem_limit=1.0, wide=T
     assert x_off.shape[1] == F
     p = {k: np.ascontiguousarray(v, np.float32) for k, v in params.items()}
     H = p["b1"].shape[0]
-    assert p["W1"].shape == (H, 2 * F) and p["W2"].shape == (H, H) and p["W3"].shape == (H,)
+    sm_on, sm_off = (-1, -1) if sm is None else (int(sm[0]), int(sm[1]))
+    assert p["W1"].shape == (H, 2 * F + (sm is not None)) and p["W2"].shape == (H, H) and p["W3"].shape == (H,)
     sigma = np.empty((n, m), np.float32)
     w = np.empty((n, m), np.int32)
     rc = lib().orc_score_pairs(x_on, n, x_off, m, F, H, p["W1"], p["b1"], p["W2"], p["b2"],
                                p["W3"], p["b3"], float(scale), int(mem_feature), float(mem_limit),
-                               1 if wide else 0, int(nthreads), sigma.ctypes.data, w.ctypes.data)
+                               sm_on, sm_off, 1 if wide else 0, int(nthreads), sigma.ctypes.data, w.ctypes.data)
     if rc != 0:
         raise ValueError("orc_score_pairs: bad arguments")
     return sigma, w

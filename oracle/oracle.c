@@ -31,10 +31,17 @@
  * offline workload are the input, the normalised shared throughput of the
  * offline workload is the output; Section "Implementation": four layers of
  * units with two hidden layers).  Input x = [online features ; offline
- * features] in the argument order of CalcNormTput(u, v, sm); the SM share is
- * a function of the online workload alone (Section "Dynamic SM allocation")
- * and therefore one of its features.  Hidden activations are ReLU, the output
- * is squashed by a logistic function so that it reads as a fraction in (0,1).
+ * features] in the argument order of CalcNormTput(u, v, sm).  The SM share
+ * sm = DynamicSM(u, v) comes in one of two readings.  sm_on < 0: it is a
+ * function of the online workload alone (Section "Dynamic SM allocation":
+ * complementary to the online workload's SM activity) and therefore one of
+ * its features.  sm_on >= 0: it depends on both workloads - the offline
+ * workload gets the complement of the online workload's SM activity (online
+ * feature sm_on) but no more than it can use (offline feature sm_off),
+ *     sm = min(1 - x_u[sm_on], x_v[sm_off])   (float32 subtraction and minimum)
+ * - and is a third input: x = [online ; offline ; sm], W1 has 2F + 1 columns.
+ * Hidden activations are ReLU, the output is squashed by a logistic function
+ * so that it reads as a fraction in (0,1).
  *
  * sigma_out (optional) receives the score before quantisation; w_out
  * (optional) receives rint(sigma * scale) as int32, or ORC_INFEASIBLE when
@@ -45,19 +52,22 @@
  *            to float at the end (the order-independent reference).
  * wide == 0: the same loops entirely in float (shows float32's own noise).
  * ---------------------------------------------------------------------- */
-static void score_row_wide(const float *xu, const float *x_off, int m, int F, int H,
+static void score_row_wide(const float *xu, const float *x_off, int m, int F, int H, int sm_on, int sm_off,
                            const float *W1, const float *b1, const float *W2, const float *b2,
                            const float *W3, const float *b3, float *sig_row)
 {
     double *h1 = (double *)malloc(sizeof(double) * (size_t)H);
     double *h2 = (double *)malloc(sizeof(double) * (size_t)H);
+    const int ld1 = 2 * F + (sm_on >= 0 ? 1 : 0);
     for (int j = 0; j < m; ++j) {
         const float *xv = x_off + (size_t)j * F;
+        const float sm = sm_on >= 0 ? fminf(1.0f - xu[sm_on], xv[sm_off]) : 0.0f;
         for (int k = 0; k < H; ++k) {
             double s = (double)b1[k];
-            const float *w = W1 + (size_t)k * 2 * F;
+            const float *w = W1 + (size_t)k * (size_t)ld1;
             for (int t = 0; t < F; ++t) s += (double)w[t] * (double)xu[t];
             for (int t = 0; t < F; ++t) s += (double)w[F + t] * (double)xv[t];
+            if (sm_on >= 0) s += (double)w[2 * F] * (double)sm;
             h1[k] = s > 0.0 ? s : 0.0;
         }
         for (int k = 0; k < H; ++k) {
@@ -74,19 +84,22 @@ static void score_row_wide(const float *xu, const float *x_off, int m, int F, in
     free(h2);
 }
 
-static void score_row_narrow(const float *xu, const float *x_off, int m, int F, int H,
+static void score_row_narrow(const float *xu, const float *x_off, int m, int F, int H, int sm_on, int sm_off,
                              const float *W1, const float *b1, const float *W2, const float *b2,
                              const float *W3, const float *b3, float *sig_row)
 {
     float *h1 = (float *)malloc(sizeof(float) * (size_t)H);
     float *h2 = (float *)malloc(sizeof(float) * (size_t)H);
+    const int ld1 = 2 * F + (sm_on >= 0 ? 1 : 0);
     for (int j = 0; j < m; ++j) {
         const float *xv = x_off + (size_t)j * F;
+        const float sm = sm_on >= 0 ? fminf(1.0f - xu[sm_on], xv[sm_off]) : 0.0f;
         for (int k = 0; k < H; ++k) {
             float s = b1[k];
-            const float *w = W1 + (size_t)k * 2 * F;
+            const float *w = W1 + (size_t)k * (size_t)ld1;
             for (int t = 0; t < F; ++t) s += w[t] * xu[t];
             for (int t = 0; t < F; ++t) s += w[F + t] * xv[t];
+            if (sm_on >= 0) s += w[2 * F] * sm;
             h1[k] = s > 0.0f ? s : 0.0f;
         }
         for (int k = 0; k < H; ++k) {
@@ -106,9 +119,11 @@ static void score_row_narrow(const float *xu, const float *x_off, int m, int F, 
 int orc_score_pairs(const float *x_on, int n, const float *x_off, int m, int F, int H,
                     const float *W1, const float *b1, const float *W2, const float *b2,
                     const float *W3, const float *b3, float scale, int mem_feature,
-                    float mem_limit, int wide, int threads, float *sigma_out, int32_t *w_out)
+                    float mem_limit, int sm_on, int sm_off, int wide, int threads, float *sigma_out,
+                    int32_t *w_out)
 {
     if (n < 0 || m < 0 || F <= 0 || H <= 0 || mem_feature < 0 || mem_feature >= F) return -1;
+    if (sm_on >= F || sm_off >= F || (sm_on >= 0) != (sm_off >= 0)) return -1;
 #ifdef _OPENMP
     if (threads > 0) omp_set_num_threads(threads);
 #else
@@ -118,8 +133,8 @@ int orc_score_pairs(const float *x_on, int n, const float *x_off, int m, int F, 
     for (int i = 0; i < n; ++i) {
         const float *xu = x_on + (size_t)i * F;
         float *sig = (float *)malloc(sizeof(float) * (size_t)(m > 0 ? m : 1));
-        if (wide) score_row_wide(xu, x_off, m, F, H, W1, b1, W2, b2, W3, b3, sig);
-        else      score_row_narrow(xu, x_off, m, F, H, W1, b1, W2, b2, W3, b3, sig);
+        if (wide) score_row_wide(xu, x_off, m, F, H, sm_on, sm_off, W1, b1, W2, b2, W3, b3, sig);
+        else      score_row_narrow(xu, x_off, m, F, H, sm_on, sm_off, W1, b1, W2, b2, W3, b3, sig);
         for (int j = 0; j < m; ++j) {
             if (sigma_out) sigma_out[(size_t)i * m + j] = sig[j];
             if (w_out) {

@@ -1028,27 +1028,41 @@ __global__ void clear_counts_kernel(mf_device_stats *stats)
 }
 
 // W^T (for the reverse rounds' coalesced column scans) and the largest weight.
-__global__ void transpose_kernel(const int32_t *__restrict__ W, int n, int m, int64_t ldw,
-                                 int32_t *__restrict__ WT, int64_t ldt, mf_device_stats *stats)
+// 64 x 64 tiles through LDS, 16-byte loads and stores on both sides.  wide: both
+// matrices allow 16-byte accesses (pitches multiples of four, bases aligned).
+__global__ __launch_bounds__(256) void transpose_kernel(const int32_t *__restrict__ W, int n, int m, int64_t ldw,
+                                                        int32_t *__restrict__ WT, int64_t ldt,
+                                                        mf_device_stats *stats)
 {
     __shared__ int32_t tile[64][65];
     const int bx = blockIdx.x * 64, by = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;     // 256 threads: 4 rows per pass
+    const int q4 = (threadIdx.x & 15) * 4, rr = threadIdx.x >> 4;       // 16 threads per line, 16 lines per pass
     int mx = 0;
-    for (int r = ty; r < 64; r += 4) {
-        const int i = by + r, j = bx + tx;
-        int32_t w = MF_INFEASIBLE;
-        if (i < n && j < m) w = W[(size_t)i * ldw + j];
-        tile[r][tx] = w;
-        mx = max(mx, w);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int r = p * 16 + rr, i = by + r, j = bx + q4;
+        int32_t w[4] = {MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE};
+        if (i < n) {
+            const int32_t *src = W + (size_t)i * ldw + j;
+            if (j + 3 < m) { const int4 v = *(const int4 *)src; w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w; }
+            else for (int e = 0; j + e < m; ++e) w[e] = src[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { tile[r][q4 + e] = w[e]; mx = max(mx, w[e]); }
     }
     __syncthreads();
-    for (int r = ty; r < 64; r += 4) {
-        const int j = bx + r, i = by + tx;
-        if (j < m && i < n) WT[(size_t)j * ldt + i] = tile[tx][r];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int r = p * 16 + rr, j = bx + r, i = by + q4;
+        if (j < m && i < n) {
+            int32_t *dst = WT + (size_t)j * ldt + i;
+            if (i + 3 < n) *(int4 *)dst = make_int4(tile[q4][r], tile[q4 + 1][r], tile[q4 + 2][r], tile[q4 + 3][r]);
+            else for (int e = 0; i + e < n; ++e) dst[e] = tile[q4 + e][r];
+        }
     }
     for (int off = 32; off >= 1; off >>= 1) mx = max(mx, __shfl_xor(mx, off));
-    if ((threadIdx.x & 63) == 0 && mx > 0) atomicMax(&stats->max_weight, mx);
+    // the maximum only grows, so an outdated (smaller) cached value at worst costs a redundant atomic
+    if ((threadIdx.x & 63) == 0 && mx > stats->max_weight) atomicMax(&stats->max_weight, mx);
 }
 
 // Duals handed to the caller: v_j = p_j and the tightest row dual the prices

@@ -106,6 +106,17 @@ def predictor_params(seed, F, H):
     }
 
 
+def with_sm_input(params, seed):
+    """The same predictor with one more input column for a pair-dependent SM share: W1 becomes
+    [H, 2F + 1]; the new column is drawn like the others (Xavier-uniform for the wider layer)."""
+    H, two_f = params["W1"].shape
+    a = np.sqrt(6.0 / (two_f + 1 + H))
+    col = ((2.0 * rng.uniform53(seed, rng.STREAM_SM, H) - 1.0) * a).astype(np.float32)
+    out = dict(params)
+    out["W1"] = np.ascontiguousarray(np.concatenate([params["W1"], col[:, None]], axis=1))
+    return out
+
+
 def gpu_types(seed, n, n_types):
     """GPU type of each online workload's device: type t has a share proportional to 1/(t+1)
     (a cluster holds a few GPU generations in uneven numbers).  Returns int32 [n]."""

@@ -128,3 +128,44 @@ def test_typed_scoring_is_a_per_row_choice_of_predictor(orc):
         assert (st[i] == si[0]).all() and (wt[i] == wi[0]).all()
     with pytest.raises(ValueError):
         orc.score_pairs_typed(x_on, x_off, plist, np.full(n, 3, np.int32), S)
+
+
+def test_pair_dependent_sm_input(orc):
+    """Pins the reading sm(u, v) = min(1 - x_u[a], x_v[d]) as a third predictor input."""
+    F, H, S = 6, 8, float(2 ** 20)
+    x_on = synth.uniform_features(4, 0, 11, F); x_off = synth.uniform_features(4, 1, 13, F)
+    base = synth.predictor_params(4, F, H)
+    # (i) a zero weight on the new input changes nothing, bit for bit
+    p0 = synth.with_sm_input(base, 4); p0["W1"][:, -1] = 0.0
+    s_plain, w_plain = orc.score_pairs(x_on, x_off, base, S)
+    s_zero, w_zero = orc.score_pairs(x_on, x_off, p0, S, sm=(2, 3))
+    assert (s_plain == s_zero).all() and (w_plain == w_zero).all()
+    # (ii) a network that passes only the new input through: z = sm(u, v), by plain arithmetic
+    p = {"W1": np.zeros((H, 2 * F + 1), np.float32), "b1": np.zeros(H, np.float32),
+         "W2": np.zeros((H, H), np.float32), "b2": np.zeros(H, np.float32),
+         "W3": np.zeros(H, np.float32), "b3": np.zeros(1, np.float32)}
+    p["W1"][0, 2 * F] = 1.0; p["W2"][0, 0] = 1.0; p["W3"][0] = 1.0
+    sig, _ = orc.score_pairs(x_on, x_off, p, S, sm=(2, 3))
+    sm = np.minimum(np.float32(1.0) - x_on[:, 2][:, None], x_off[:, 3][None, :])
+    assert sm.dtype == np.float32 and (sm > 0).any()
+    np.testing.assert_allclose(sig, 1 / (1 + np.exp(-np.maximum(sm.astype(np.float64), 0))), rtol=1e-7)
+    # the online and the offline feature index are not interchangeable
+    other, _ = orc.score_pairs(x_on, x_off, p, S, sm=(3, 2))
+    assert not np.allclose(other, sig)
+    # (iii) black box: a float64 library MLP on the explicit concatenation [x_u ; x_v ; sm]
+    pp = synth.with_sm_input(base, 9)
+    got, _ = orc.score_pairs(x_on, x_off, pp, S, sm=(2, 3))
+    lin1 = torch.nn.Linear(2 * F + 1, H, dtype=torch.float64); lin2 = torch.nn.Linear(H, H, dtype=torch.float64)
+    lin3 = torch.nn.Linear(H, 1, dtype=torch.float64)
+    with torch.no_grad():
+        lin1.weight.copy_(torch.from_numpy(pp["W1"]).double()); lin1.bias.copy_(torch.from_numpy(pp["b1"]).double())
+        lin2.weight.copy_(torch.from_numpy(pp["W2"]).double()); lin2.bias.copy_(torch.from_numpy(pp["b2"]).double())
+        lin3.weight.copy_(torch.from_numpy(pp["W3"]).double()[None, :]); lin3.bias.copy_(torch.from_numpy(pp["b3"]).double())
+        net = torch.nn.Sequential(lin1, torch.nn.ReLU(), lin2, torch.nn.ReLU(), lin3, torch.nn.Sigmoid())
+        xo = torch.from_numpy(x_on).double(); xf = torch.from_numpy(x_off).double()
+        pairs = torch.cat([xo[:, None, :].expand(-1, 13, -1), xf[None, :, :].expand(11, -1, -1),
+                           torch.from_numpy(sm).double()[:, :, None]], dim=2)
+        ref = net(pairs)[..., 0].numpy()
+    np.testing.assert_allclose(got.astype(np.float64), ref, rtol=1e-7)
+    with pytest.raises(ValueError):
+        orc.score_pairs(x_on, x_off, pp, S, sm=(2, F))
