@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="C4")
     ap.add_argument("--seed", type=int, default=1)
-    ap.add_argument("--cpu-rows", type=int, default=192)
+    ap.add_argument("--cpu-rows", type=int, default=1280)
     ap.add_argument("--cpu-block", type=int, default=1536)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--update-rounds", type=int, default=3,
@@ -66,6 +66,8 @@ def main():
                     help="also time scoring with this many per-GPU-type predictors (0: skip)")
     ap.add_argument("--calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (reference for hardware byte counters)")
+    ap.add_argument("--no-sm-input", dest="sm_input", action="store_false",
+                    help="skip timing the scorer with the pair-dependent SM input")
     ap.add_argument("--opt", action="append", default=[], help="solver option name=value (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -155,9 +157,10 @@ def main():
                               "traffic": MEASURED_TRAFFIC.get((cfg.name, "round_kernel"))},
         # the chain-following kernels take most of the auction's time but are bound by the latency of
         # dependent steps, not by bandwidth: reported as steps and microseconds per step
-        "auction_tail": {"kernels": "chain_kernel + team_kernel", "bound": "latency",
-                         "sequential_steps": res.chain_depth, "bids": res.chain_bids,
-                         "us_per_sequential_step": (avg["auction_ms"] * 1e3 / res.chain_depth) if res.chain_depth else None},
+        "auction_tail": {"kernels": "chain_kernel + team_kernel (dependent bids), path_kernel (search super-steps)",
+                         "bound": "latency", "sequential_steps": res.chain_depth, "bids": res.chain_bids,
+                         "path_super_steps": res.path_steps, "path_row_scans": res.path_scans,
+                         "chain_steps": res.chain_depth - res.path_steps},
     }
     if args.update_rounds > 0:
         # follow-up rounds: a share of the online and offline workloads is replaced by fresh draws,
@@ -197,6 +200,22 @@ def main():
         out["typed_scoring"] = {"gpu_types": args.types, "ms": float(np.median(ms)),
                                 "pairs_per_s": n * m / (float(np.median(ms)) * 1e-3),
                                 "pairs_evaluated_fraction": tm["pairs_evaluated_fraction"]}
+        del W2
+    if args.sm_input:
+        # the pair-dependent SM share as a third predictor input (same network plus one layer-1 column)
+        full = synth.with_sm_input(r["params"], args.seed + 3)
+        sp = dict(params)
+        sp["W1sm"] = dev(full["W1"][:, -1])
+        spred = ctx.predictor(sp, cfg.scale, sm=(2, 3))
+        W2 = torch.empty_like(W)
+        ms = []
+        for _ in range(3):
+            ctx.score_pairs(spred, x_on, x_off, W2)
+            torch.cuda.synchronize()
+            tm = ctx.last_timings()
+            ms.append(tm["pair_scoring_ms"] + tm["projections_ms"])
+        out["sm_input_scoring"] = {"ms": float(np.median(ms)), "pairs_per_s": n * m / (float(np.median(ms)) * 1e-3),
+                                   "pairs_evaluated_fraction": tm["pairs_evaluated_fraction"]}
         del W2
     if not args.no_cpu:
         blk = min(args.cpu_block, n)

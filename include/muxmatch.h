@@ -68,6 +68,14 @@ typedef struct mf_ctx mf_ctx;
  * A pair whose memory fractions add up (one float32 addition) to more than
  * mem_limit is infeasible: feature index mem_feature of each side is that
  * fraction (paper: Section "Implementation", the offline memory quota).
+ * Optional third input (paper: Algorithm "Scheduling algorithm", sm = DynamicSM(u, v)
+ * is an argument of CalcNormTput; Section "Dynamic SM allocation"): with d_W1sm
+ * not NULL the SM share of the pair,
+ *   sm(u, v) = min(1 - x_u[sm_on_feature], x_v[sm_off_feature])   (float32),
+ * the complement of the online workload's SM activity capped by what the
+ * offline workload can use, enters layer 1 with weights d_W1sm[H] (the column
+ * 2F of a [H][2F+1] first layer).  With d_W1sm NULL the two indices are ignored
+ * and the SM share is whatever feature of the online workload carries it.
  * All parameter pointers are DEVICE pointers to float32, row-major.
  */
 typedef struct {
@@ -82,6 +90,9 @@ typedef struct {
     const float *d_b2;          /* [H]                                                  */
     const float *d_W3;          /* [H]                                                  */
     const float *d_b3;          /* [1]                                                  */
+    const float *d_W1sm;        /* [H] or NULL: weights of the pair-dependent SM input  */
+    int32_t sm_on_feature;      /* online feature: SM activity of the online workload   */
+    int32_t sm_off_feature;     /* offline feature: SM share the offline one can use    */
 } mf_predictor;
 
 /* Filled on the host by the solving calls. */

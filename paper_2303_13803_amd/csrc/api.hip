@@ -27,6 +27,9 @@ int check_predictor(const mf_predictor *p)
     if (!(p->scale > 0.0f) || p->scale > 1073741824.0f) return MF_ERR_ARG;
     if (p->mem_feature < 0 || p->mem_feature >= p->F) return MF_ERR_ARG;
     if (!aligned16(p->d_W2) || !aligned16(p->d_b2) || !aligned16(p->d_W3)) return MF_ERR_ARG;
+    if (p->d_W1sm && (!aligned16(p->d_W1sm) || p->sm_on_feature < 0 || p->sm_on_feature >= p->F ||
+                      p->sm_off_feature < 0 || p->sm_off_feature >= p->F))
+        return MF_ERR_ARG;
     return MF_OK;
 }
 
@@ -38,7 +41,10 @@ int check_predictors(const mf_predictor *preds, int n_types)
         const int rc = check_predictor(&preds[t]);
         if (rc != MF_OK) return rc;
         if (preds[t].F != preds[0].F || preds[t].mem_feature != preds[0].mem_feature ||
-            preds[t].mem_limit != preds[0].mem_limit || preds[t].scale != preds[0].scale)
+            preds[t].mem_limit != preds[0].mem_limit || preds[t].scale != preds[0].scale ||
+            (preds[t].d_W1sm != nullptr) != (preds[0].d_W1sm != nullptr) ||
+            (preds[0].d_W1sm && (preds[t].sm_on_feature != preds[0].sm_on_feature ||
+                                 preds[t].sm_off_feature != preds[0].sm_off_feature)))
             return MF_ERR_ARG;
     }
     return MF_OK;
@@ -110,6 +116,8 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->proj_off, (size_t)max_m * 128));
     TRY(dev_alloc(&ctx->mem_on, (size_t)max_n));
     TRY(dev_alloc(&ctx->mem_off, (size_t)max_m));
+    TRY(dev_alloc(&ctx->sm_on, (size_t)max_n));
+    TRY(dev_alloc(&ctx->sm_off, (size_t)max_m));
     TRY(dev_alloc(&ctx->order_on, (size_t)max_n));
     TRY(dev_alloc(&ctx->order_off, (size_t)max_m));
     TRY(dev_alloc(&ctx->type_segment, (size_t)MF_MAX_TYPES + 1));
@@ -154,7 +162,7 @@ int mf_destroy(mf_ctx *ctx)
     if (!ctx) return MF_ERR_ARG;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->order_on, ctx->order_off, ctx->type_segment, ctx->pairs_evaluated, ctx->wt, ctx->price,
+    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->type_segment, ctx->pairs_evaluated, ctx->wt, ctx->price,
                    ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_pair[0], ctx->path_pair[1], ctx->path_dist[0], ctx->path_dist[1], ctx->path_held, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);

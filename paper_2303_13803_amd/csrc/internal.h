@@ -59,6 +59,7 @@ struct mf_ctx {
     // scoring scratch
     float *proj_on, *proj_off;      // [max_n][H], [max_m][H]
     float *mem_on, *mem_off;        // [max_n], [max_m]
+    float *sm_on, *sm_off;          // SM activity / SM demand features (pair-dependent SM input)
     int32_t *order_on, *order_off;  // workloads by ascending memory fraction (online: by type first)
     int32_t *type_segment;          // [MF_MAX_TYPES + 1] first position of each type in order_on
     unsigned long long *pairs_evaluated, *h_pairs_evaluated;   // pairs the last scoring pass ran the MLP on (device, pinned)

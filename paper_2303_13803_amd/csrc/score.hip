@@ -134,7 +134,7 @@ template <int H> struct PairShape {
     static constexpr int ROWS = 64;                        // online rows per workgroup
     static constexpr int KS = H / 2;                       // k-steps of the 32x32x2 tile
     static constexpr int MB = H / 32;                      // 32-row blocks of the hidden layer
-    static constexpr size_t LDS_BYTES = sizeof(float) * ((size_t)H * H + (size_t)ROWS * H + 2 * H + ROWS);
+    static constexpr size_t LDS_BYTES = sizeof(float) * ((size_t)H * H + (size_t)ROWS * H + 3 * H + 2 * ROWS);
 };
 
 // One wavefront owns 32 offline columns (lane & 31) and walks down the online
@@ -146,7 +146,9 @@ template <int H> struct PairShape {
 // slots of step s be hidden features s and H/2 + s, so each half-wave streams
 // a contiguous half of the projections.  Accumulator register r of lane l is
 // D[8*(r/4) + 4*(l/32) + r%4][l%32].
-template <int H>
+// PAIR_SM: the predictor has a third input, the SM share of the pair
+// min(1 - sm_on[i], sm_off[j]); its layer-1 weights w_sm[H] add w_sm[k] * share to hidden unit k.
+template <int H, bool PAIR_SM>
 __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     const float *__restrict__ P_on, const float *__restrict__ P_off,
     const float *__restrict__ W2, const float *__restrict__ b2, const float *__restrict__ W3,
@@ -154,7 +156,8 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     const float *__restrict__ mem_off, int n, int m, float scale, float mem_limit,
     int32_t *__restrict__ W, int64_t ldw, float *__restrict__ sigma,
     const int32_t *__restrict__ row_map, const int32_t *__restrict__ col_map, int by_memory,
-    unsigned long long *__restrict__ evaluated, const int32_t *__restrict__ segment)
+    unsigned long long *__restrict__ evaluated, const int32_t *__restrict__ segment,
+    const float *__restrict__ w_sm, const float *__restrict__ sm_on, const float *__restrict__ sm_off)
 {
     using S = PairShape<H>;
     constexpr int KS = S::KS, MB = S::MB, ROWS = S::ROWS, Q = KS / 4;
@@ -164,6 +167,8 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     float *b2_lds = pon_lds + ROWS * H;
     float *w3_lds = b2_lds + H;
     float *mon_lds = w3_lds + H;                           // [ROWS] memory fraction of the tile's rows
+    float *wsm_lds = mon_lds + ROWS;                       // [H] layer-1 weights of the SM share
+    float *son_lds = wsm_lds + H;                          // [ROWS] 1 - SM activity of the tile's rows
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hh = lane >> 5, nn = lane & 31;
@@ -196,6 +201,10 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     }
     if (tid < H) { b2_lds[tid] = b2[tid]; w3_lds[tid] = W3[tid]; }
     if (tid < nrows) mon_lds[tid] = mem_on[row_map ? row_map[row0 + tid] : row0 + tid];
+    if (PAIR_SM) {
+        if (tid < H) wsm_lds[tid] = w_sm[tid];
+        if (tid < nrows) son_lds[tid] = 1.0f - sm_on[row_map ? row_map[row0 + tid] : row0 + tid];
+    }
     __syncthreads();
     if (j0 >= m) return;
 
@@ -208,6 +217,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
         poff[4 * q] = t.x; poff[4 * q + 1] = t.y; poff[4 * q + 2] = t.z; poff[4 * q + 3] = t.w;
     }
     const float moff = mem_off[jc];
+    const float soff = PAIR_SM ? sm_off[jc] : 0.0f;
     const float bias3 = b3[0];
     // by_memory: the maps list rows and columns by ascending memory fraction, so this
     // wavefront's first column has its smallest one, and once a row does not fit next to
@@ -229,14 +239,23 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
                 acc[mb][4 * g + 2] = bv.z; acc[mb][4 * g + 3] = bv.w;
             }
         const float *pon = pon_lds + r * H + hh * KS;
+        const float share = PAIR_SM ? fminf(son_lds[r], soff) : 0.0f;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             float4 pv = *(const float4 *)(pon + 4 * q);
             float h1[4];
-            h1[0] = fmaxf(pv.x + poff[4 * q], 0.0f);
-            h1[1] = fmaxf(pv.y + poff[4 * q + 1], 0.0f);
-            h1[2] = fmaxf(pv.z + poff[4 * q + 2], 0.0f);
-            h1[3] = fmaxf(pv.w + poff[4 * q + 3], 0.0f);
+            if (PAIR_SM) {
+                const float4 ws = *(const float4 *)(wsm_lds + hh * KS + 4 * q);
+                h1[0] = fmaxf(fmaf(ws.x, share, pv.x + poff[4 * q]), 0.0f);
+                h1[1] = fmaxf(fmaf(ws.y, share, pv.y + poff[4 * q + 1]), 0.0f);
+                h1[2] = fmaxf(fmaf(ws.z, share, pv.z + poff[4 * q + 2]), 0.0f);
+                h1[3] = fmaxf(fmaf(ws.w, share, pv.w + poff[4 * q + 3]), 0.0f);
+            } else {
+                h1[0] = fmaxf(pv.x + poff[4 * q], 0.0f);
+                h1[1] = fmaxf(pv.y + poff[4 * q + 1], 0.0f);
+                h1[2] = fmaxf(pv.z + poff[4 * q + 2], 0.0f);
+                h1[3] = fmaxf(pv.w + poff[4 * q + 3], 0.0f);
+            }
             float4 av[MB];
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) av[mb] = a_lds[(mb * Q + q) * 64 + lane];
@@ -277,26 +296,35 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     if (evaluated && lane == 0 && r > 0) atomicAdd(evaluated, (unsigned long long)r * (unsigned)min(32, m - j0));
 }
 
-template <int H>
-int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
-                float *d_sigma, const int32_t *row_map, const int32_t *col_map, bool by_memory,
-                const int32_t *segment = nullptr)
+template <int H, bool PAIR_SM>
+int launch_pair_variant(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
+                        float *d_sigma, const int32_t *row_map, const int32_t *col_map, bool by_memory,
+                        const int32_t *segment)
 {
     using S = PairShape<H>;
     static bool configured = false;
     if (!configured) {
-        MF_HIP(hipFuncSetAttribute((const void *)pair_mlp_kernel<H>,
+        MF_HIP(hipFuncSetAttribute((const void *)pair_mlp_kernel<H, PAIR_SM>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS_BYTES));
         configured = true;
     }
     // x padded to a multiple of 8: every XCD then meets the same row tiles for each column tile
     dim3 grid((((n + S::ROWS - 1) / S::ROWS) + 7) & ~7, (m + PAIR_COLS - 1) / PAIR_COLS);
-    hipLaunchKernelGGL(pair_mlp_kernel<H>, grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
+    hipLaunchKernelGGL((pair_mlp_kernel<H, PAIR_SM>), grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
                        ctx->proj_on, ctx->proj_off, p->d_W2, p->d_b2, p->d_W3, p->d_b3,
                        ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma, row_map, col_map,
-                       by_memory ? 1 : 0, ctx->pairs_evaluated, segment);
+                       by_memory ? 1 : 0, ctx->pairs_evaluated, segment, p->d_W1sm, ctx->sm_on, ctx->sm_off);
     MF_HIP(hipGetLastError());
     return MF_OK;
+}
+
+template <int H>
+int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
+                float *d_sigma, const int32_t *row_map, const int32_t *col_map, bool by_memory,
+                const int32_t *segment = nullptr)
+{
+    return p->d_W1sm ? launch_pair_variant<H, true>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment)
+                     : launch_pair_variant<H, false>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment);
 }
 
 // order[k] = the workload with the k-th smallest (group, key); ranks are counted in list[0]
@@ -374,6 +402,12 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
                        p0->mem_feature, ctx->mem_on);
     hipLaunchKernelGGL(gather_feature_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, d_off, m, F,
                        p0->mem_feature, ctx->mem_off);
+    if (p0->d_W1sm) {
+        hipLaunchKernelGGL(gather_feature_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, d_on, n, F,
+                           p0->sm_on_feature, ctx->sm_on);
+        hipLaunchKernelGGL(gather_feature_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, d_off, m, F,
+                           p0->sm_off_feature, ctx->sm_off);
+    }
     // Pairs whose memory fractions do not fit get no score, so unless the caller wants every
     // score, walk rows and columns in memory order: the pairs that cannot fit then form one
     // corner of the tile grid and the kernel leaves them out.  Results land at the same places.
@@ -454,6 +488,12 @@ int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int
                        p->mem_feature, ctx->mem_on);
     hipLaunchKernelGGL(gather_feature_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, d_off, m, F,
                        p->mem_feature, ctx->mem_off);
+    if (p->d_W1sm) {
+        hipLaunchKernelGGL(gather_feature_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, d_on, n, F,
+                           p->sm_on_feature, ctx->sm_on);
+        hipLaunchKernelGGL(gather_feature_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, d_off, m, F,
+                           p->sm_off_feature, ctx->sm_off);
+    }
     MF_HIP(hipGetLastError());
     hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->pairs_evaluated);
     ctx->pairs_total = (double)n_rows * (double)m + (double)n * (double)n_cols;
