@@ -62,9 +62,11 @@ int finish_score_timing(mf_ctx *ctx)
                           hipMemcpyDeviceToHost, ctx->stream));
     MF_HIP(hipStreamSynchronize(ctx->stream));
     float a = 0.0f, b = 0.0f;
+    float c = 0.0f;
     MF_HIP(hipEventElapsedTime(&a, ctx->ev[0], ctx->ev[1]));
     MF_HIP(hipEventElapsedTime(&b, ctx->ev[1], ctx->ev[2]));
-    ctx->timings[T_PROJ] = a;
+    MF_HIP(hipEventElapsedTime(&c, ctx->ev[2], ctx->ev[8]));      // putting the columns back in place
+    ctx->timings[T_PROJ] = a + c;
     ctx->timings[T_PAIR] = b;
     ctx->timings[T_PAIR_EVALUATED] = ctx->pairs_total > 0 ? (float)((double)*ctx->h_pairs_evaluated / ctx->pairs_total) : 0.0f;
     ctx->score_pending = false;
@@ -120,10 +122,15 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->sm_off, (size_t)max_m));
     TRY(dev_alloc(&ctx->order_on, (size_t)max_n));
     TRY(dev_alloc(&ctx->order_off, (size_t)max_m));
+    TRY(dev_alloc(&ctx->rank_off, (size_t)max_m));
     TRY(dev_alloc(&ctx->type_segment, (size_t)MF_MAX_TYPES + 1));
     TRY(dev_alloc(&ctx->pairs_evaluated, 1));
     TRY(hipHostMalloc((void **)&ctx->h_pairs_evaluated, sizeof(unsigned long long)));
-    TRY(dev_alloc(&ctx->wt, (size_t)max_m * ldt));
+    {   // holds W^T for the solver ([m][n padded]) and, while scoring, W with its columns in memory order ([n][m padded])
+        const size_t ldo = ((size_t)max_m + 3) & ~(size_t)3;
+        const size_t a = (size_t)max_m * ldt, b = (size_t)max_n * ldo;
+        TRY(dev_alloc(&ctx->wt, a > b ? a : b));
+    }
     TRY(dev_alloc(&ctx->price, nm + 8));
     TRY(dev_alloc(&ctx->profit, nm + 8));
     TRY(dev_alloc(&ctx->colword, nm));
@@ -146,7 +153,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->cert, 1));
     TRY(hipHostMalloc((void **)&ctx->h_stats, sizeof(mf_device_stats)));
     TRY(hipHostMalloc((void **)&ctx->h_cert, sizeof(mf_cert_out)));
-    for (int i = 0; i < 8; ++i) TRY(hipEventCreate(&ctx->ev[i]));
+    for (int i = 0; i < 10; ++i) TRY(hipEventCreate(&ctx->ev[i]));
 #undef TRY
     if (e != hipSuccess) {
         ctx->hip_error = e;
@@ -162,14 +169,14 @@ int mf_destroy(mf_ctx *ctx)
     if (!ctx) return MF_ERR_ARG;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->type_segment, ctx->pairs_evaluated, ctx->wt, ctx->price,
+    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->rank_off, ctx->type_segment, ctx->pairs_evaluated, ctx->wt, ctx->price,
                    ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_pair[0], ctx->path_pair[1], ctx->path_dist[0], ctx->path_dist[1], ctx->path_held, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (ctx->h_stats) (void)hipHostFree(ctx->h_stats);
     if (ctx->h_cert) (void)hipHostFree(ctx->h_cert);
     if (ctx->h_pairs_evaluated) (void)hipHostFree(ctx->h_pairs_evaluated);
-    for (int i = 0; i < 8; ++i) if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+    for (int i = 0; i < 10; ++i) if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
     delete ctx;
     return MF_OK;
 }

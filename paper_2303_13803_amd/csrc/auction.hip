@@ -1045,7 +1045,11 @@ __global__ __launch_bounds__(256) void transpose_kernel(const int32_t *__restric
         if (i < n) {
             const int32_t *src = W + (size_t)i * ldw + j;
             if (j + 3 < m) { const int4 v = *(const int4 *)src; w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w; }
-            else for (int e = 0; j + e < m; ++e) w[e] = src[e];
+            else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (j + e < m) w[e] = src[e];
+            }
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) { tile[r][q4 + e] = w[e]; mx = max(mx, w[e]); }
@@ -1057,7 +1061,11 @@ __global__ __launch_bounds__(256) void transpose_kernel(const int32_t *__restric
         if (j < m && i < n) {
             int32_t *dst = WT + (size_t)j * ldt + i;
             if (i + 3 < n) *(int4 *)dst = make_int4(tile[q4][r], tile[q4 + 1][r], tile[q4 + 2][r], tile[q4 + 3][r]);
-            else for (int e = 0; i + e < n; ++e) dst[e] = tile[q4 + e][r];
+            else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (i + e < n) dst[e] = tile[q4 + e][r];
+            }
         }
     }
     for (int off = 32; off >= 1; off >>= 1) mx = max(mx, __shfl_xor(mx, off));

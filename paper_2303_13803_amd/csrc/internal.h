@@ -61,6 +61,7 @@ struct mf_ctx {
     float *mem_on, *mem_off;        // [max_n], [max_m]
     float *sm_on, *sm_off;          // SM activity / SM demand features (pair-dependent SM input)
     int32_t *order_on, *order_off;  // workloads by ascending memory fraction (online: by type first)
+    int32_t *rank_off;              // position of each offline workload in order_off
     int32_t *type_segment;          // [MF_MAX_TYPES + 1] first position of each type in order_on
     unsigned long long *pairs_evaluated, *h_pairs_evaluated;   // pairs the last scoring pass ran the MLP on (device, pinned)
     double pairs_total;             // ... out of this many
@@ -101,7 +102,7 @@ struct mf_ctx {
     // options
     int64_t theta, max_rounds;
     // timing
-    hipEvent_t ev[8];
+    hipEvent_t ev[10];              // 0..2 and 8: scoring stages; 3..7: solver stages
     float timings[T_COUNT];
     bool score_pending;             // score events recorded but not yet read
 };

@@ -97,22 +97,88 @@ __global__ void order_from_rank_kernel(const int32_t *__restrict__ rank, int cou
     if (i < count) order[rank[i]] = i;
 }
 
-// Marks every pair that cannot fit (paper: Section "Implementation", the memory quota) and
-// clears the rest, in whole coalesced lines, before the pair kernel fills in the scores.
-__global__ __launch_bounds__(256) void fit_mask_kernel(const float *__restrict__ mem_on,
-                                                       const float *__restrict__ mem_off, int n, int m,
-                                                       float mem_limit, int32_t *__restrict__ W, int64_t ldw,
-                                                       int wide_stores)
+// The memory-ordered pass leaves row i of the scores in `sorted` with its columns in memory
+// order (whole-line stores; entries of pairs it skipped were never written).  This puts them in
+// place: W[i][j] = sorted[i][rank[j]], or MF_INFEASIBLE where the memory rule (paper: Section
+// "Implementation", the memory quota) says the pair cannot share - the rule alone decides, so
+// unwritten entries are never used.  A row of `sorted` is read back in scattered 4-byte pieces,
+// but every piece of it is used by the same workgroup while it sits in the caches.
+__global__ __launch_bounds__(256) void place_columns_kernel(const int32_t *__restrict__ sorted, int64_t lds,
+                                                            const int32_t *__restrict__ rank,
+                                                            const float *__restrict__ mem_on,
+                                                            const float *__restrict__ mem_off, int n, int m,
+                                                            float mem_limit, int32_t *__restrict__ W, int64_t ldw,
+                                                            int wide_stores)
 {
     const int i = blockIdx.x;
     const float mon = mem_on[i];
+    const int32_t *src = sorted + (size_t)i * lds;
     int32_t *row = W + (size_t)i * ldw;
     for (int j = (blockIdx.y * 256 + threadIdx.x) * 4; j < m; j += gridDim.y * 1024) {
         int32_t w[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (j + e < m && mon + mem_off[j + e] > mem_limit) ? MF_INFEASIBLE : 0;
-        if (wide_stores && j + 3 < m) *(int4 *)(row + j) = make_int4(w[0], w[1], w[2], w[3]);
-        else for (int e = 0; j + e < m; ++e) row[j + e] = w[e];
+        for (int e = 0; e < 4; ++e)
+            w[e] = j + e < m ? ((mon + mem_off[j + e] > mem_limit) ? MF_INFEASIBLE : src[rank[j + e]]) : 0;
+        if (wide_stores && j + 3 < m) {
+            *(int4 *)(row + j) = make_int4(w[0], w[1], w[2], w[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (j + e < m) row[j + e] = w[e];
+        }
+    }
+}
+
+// The same through LDS, for rows of up to PLACE_MAX_COLS entries (one chunk; measured faster than
+// the kernel above there, slower beyond): a workgroup per row loads the row's memory-ordered
+// scores in whole lines, picks each output's entry out of LDS, and stores the row in whole lines
+// - no scattered access reaches the caches.
+constexpr int PLACE_THREADS = 1024, PLACE_CHUNK = 32768, PLACE_GROUPS = 8;
+constexpr int PLACE_MAX_COLS = PLACE_THREADS * PLACE_GROUPS * 4;
+
+__global__ __launch_bounds__(PLACE_THREADS) void place_columns_lds_kernel(
+    const int32_t *__restrict__ sorted, int64_t lds, const int32_t *__restrict__ rank,
+    const float *__restrict__ mem_on, const float *__restrict__ mem_off, int n, int m, float mem_limit,
+    int32_t *__restrict__ W, int64_t ldw, int wide_stores)
+{
+    extern __shared__ int32_t staged[];
+    const int i = blockIdx.x, tid = threadIdx.x;
+    const float mon = mem_on[i];
+    const int32_t *src = sorted + (size_t)i * lds;       // lds is a multiple of four, the buffer 16-byte aligned
+    int32_t *row = W + (size_t)i * ldw;
+    int32_t val[PLACE_GROUPS][4];
+    for (int c0 = 0; c0 < m; c0 += PLACE_CHUNK) {
+        const int cn = min(PLACE_CHUNK, m - c0);
+        __syncthreads();
+        for (int t = tid * 4; t < cn; t += PLACE_THREADS * 4) *(int4 *)(staged + t) = *(const int4 *)(src + c0 + t);
+        __syncthreads();
+#pragma unroll
+        for (int g = 0; g < PLACE_GROUPS; ++g) {
+            const int j = (g * PLACE_THREADS + tid) * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (j + e < m) {
+                    const int at = rank[j + e] - c0;
+                    if (at >= 0 && at < cn) val[g][e] = staged[at];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < PLACE_GROUPS; ++g) {
+        const int j = (g * PLACE_THREADS + tid) * 4;
+        if (j >= m) break;
+        int32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            w[e] = (j + e < m && mon + mem_off[j + e] > mem_limit) ? MF_INFEASIBLE : val[g][e];
+        if (wide_stores && j + 3 < m) {
+            *(int4 *)(row + j) = make_int4(w[0], w[1], w[2], w[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (j + e < m) row[j + e] = w[e];
+        }
     }
 }
 
@@ -187,7 +253,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     const int nrows = min(ROWS, n - row0);
     const int j0 = (blockIdx.y * PAIR_WAVES + wave) * 32;
     // in memory order the tile's first row and first column are its smallest: if they do not
-    // fit together, nothing in the tile does, and it already holds its marks
+    // fit together, nothing in the tile does
     if (by_memory && mem_on[row_map[row0]] + mem_off[col_map[blockIdx.y * PAIR_COLS]] > mem_limit) return;
 
     for (int idx = tid; idx < MB * Q * 64; idx += PAIR_THREADS) {
@@ -286,13 +352,19 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
             float q = rintf(sg * scale);
             q = fminf(fmaxf(q, 0.0f), scale);
             int32_t w = (int32_t)q;
-            const float memsum = mon_lds[r] + moff;
-            if (memsum > mem_limit) w = MF_INFEASIBLE;
-            W[(size_t)i * ldw + jc] = w;
-            if (sigma) sigma[(size_t)i * m + jc] = sg;
+            if (by_memory) {
+                // row i of the staging matrix, columns in memory order: one whole line per wave;
+                // the memory rule is applied when the columns are put back in place
+                W[(size_t)i * ldw + j] = w;
+            } else {
+                const float memsum = mon_lds[r] + moff;
+                if (memsum > mem_limit) w = MF_INFEASIBLE;
+                W[(size_t)i * ldw + jc] = w;
+                if (sigma) sigma[(size_t)i * m + jc] = sg;
+            }
         }
     }
-    // rows the loop left early hold the "cannot fit" marks fit_mask_kernel wrote
+    // rows the loop left early get their "cannot fit" marks when the columns are put back in place
     if (evaluated && lane == 0 && r > 0) atomicAdd(evaluated, (unsigned long long)r * (unsigned)min(32, m - j0));
 }
 
@@ -327,22 +399,23 @@ int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, 
                      : launch_pair_variant<H, false>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment);
 }
 
-// order[k] = the workload with the k-th smallest (group, key); ranks are counted in list[0]
-void order_by_memory(mf_ctx *ctx, const float *key, const int32_t *group, int count, int32_t *order)
+// order[k] = the workload with the k-th smallest (group, key); rank[i] = its position k
+void order_by_memory(mf_ctx *ctx, const float *key, const int32_t *group, int count, int32_t *order,
+                     int32_t *rank)
 {
     const int blocks = (count + RANK_THREADS - 1) / RANK_THREADS;
     int split = 2048 / blocks;
     split = split < 1 ? 1 : (split > 64 ? 64 : split);
     const int slice = ((count + split - 1) / split + 3) & ~3;
     const dim3 grid(blocks, (count + slice - 1) / slice);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(RANK_THREADS), 0, ctx->stream, ctx->list[0], count);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(RANK_THREADS), 0, ctx->stream, rank, count);
     if (group)
         hipLaunchKernelGGL(rank_count_kernel<true>, grid, dim3(RANK_THREADS), 0, ctx->stream, key, group, count,
-                           slice, ctx->list[0]);
+                           slice, rank);
     else
         hipLaunchKernelGGL(rank_count_kernel<false>, grid, dim3(RANK_THREADS), 0, ctx->stream, key, group, count,
-                           slice, ctx->list[0]);
-    hipLaunchKernelGGL(order_from_rank_kernel, dim3(blocks), dim3(RANK_THREADS), 0, ctx->stream, ctx->list[0],
+                           slice, rank);
+    hipLaunchKernelGGL(order_from_rank_kernel, dim3(blocks), dim3(RANK_THREADS), 0, ctx->stream, rank,
                        count, order);
 }
 
@@ -413,17 +486,14 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
     // corner of the tile grid and the kernel leaves them out.  Results land at the same places.
     const bool by_memory = ctx->fit_order && !d_sigma;
     hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->pairs_evaluated);
-    if (by_memory || typed) order_by_memory(ctx, ctx->mem_on, d_type, n, ctx->order_on);
-    if (by_memory) {
-        order_by_memory(ctx, ctx->mem_off, nullptr, m, ctx->order_off);
-        const int chunks = (m + 4095) / 4096 < 16 ? (m + 4095) / 4096 : 16;
-        const int wide = ((uintptr_t)d_W & 15u) == 0 && (ldw & 3) == 0;
-        hipLaunchKernelGGL(fit_mask_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->mem_on, ctx->mem_off,
-                           n, m, p0->mem_limit, d_W, ldw, wide);
-    }
+    if (by_memory || typed) order_by_memory(ctx, ctx->mem_on, d_type, n, ctx->order_on, ctx->list[0]);
+    if (by_memory) order_by_memory(ctx, ctx->mem_off, nullptr, m, ctx->order_off, ctx->rank_off);
     MF_HIP(hipGetLastError());
     ctx->pairs_total = (double)n * (double)m;
     const int32_t *rmap = (by_memory || typed) ? ctx->order_on : nullptr, *cmap = by_memory ? ctx->order_off : nullptr;
+    // in memory order the scores go to a staging matrix (the solver's transposed-copy buffer, idle now)
+    int32_t *out = by_memory ? ctx->wt : d_W;
+    const int64_t ldo = by_memory ? (((int64_t)m + 3) & ~3ll) : ldw;
     for (int t = 0; t < n_types; ++t) {
         const mf_predictor *p = &preds[t];
         const int H = p->H;
@@ -436,11 +506,32 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
         MF_HIP(hipGetLastError());
         if (t == 0) MF_HIP(hipEventRecord(ctx->ev[1], ctx->stream));      // later types' projections count as scoring
         const int32_t *segment = typed ? ctx->type_segment + t : nullptr;
-        int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, d_W, ldw, d_sigma, rmap, cmap, by_memory, segment)
-                           : launch_pair<128>(ctx, p, n, m, d_W, ldw, d_sigma, rmap, cmap, by_memory, segment);
+        int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, out, ldo, d_sigma, rmap, cmap, by_memory, segment)
+                           : launch_pair<128>(ctx, p, n, m, out, ldo, d_sigma, rmap, cmap, by_memory, segment);
         if (rc != MF_OK) return rc;
     }
     MF_HIP(hipEventRecord(ctx->ev[2], ctx->stream));
+    if (by_memory) {
+        const int chunks = (m + 4095) / 4096 < 16 ? (m + 4095) / 4096 : 16;
+        const int wide = ((uintptr_t)d_W & 15u) == 0 && (ldw & 3) == 0;
+        if (m <= PLACE_MAX_COLS) {
+            static bool configured = false;
+            const size_t bytes = sizeof(int32_t) * (size_t)(m < PLACE_CHUNK ? ((m + 3) & ~3) : PLACE_CHUNK);
+            if (!configured) {
+                MF_HIP(hipFuncSetAttribute((const void *)place_columns_lds_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)(sizeof(int32_t) * PLACE_CHUNK)));
+                configured = true;
+            }
+            hipLaunchKernelGGL(place_columns_lds_kernel, dim3(n), dim3(PLACE_THREADS), bytes, ctx->stream, ctx->wt, ldo,
+                               ctx->rank_off, ctx->mem_on, ctx->mem_off, n, m, p0->mem_limit, d_W, ldw, wide);
+        } else {
+            hipLaunchKernelGGL(place_columns_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->wt, ldo,
+                               ctx->rank_off, ctx->mem_on, ctx->mem_off, n, m, p0->mem_limit, d_W, ldw, wide);
+        }
+        MF_HIP(hipGetLastError());
+    }
+    MF_HIP(hipEventRecord(ctx->ev[8], ctx->stream));
     ctx->score_pending = true;
     return MF_OK;
 }
@@ -507,6 +598,7 @@ int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int
                        : launch_pair<128>(ctx, p, n, n_cols, d_W, ldw, nullptr, nullptr, d_cols, false);
     if (rc != MF_OK) return rc;
     MF_HIP(hipEventRecord(ctx->ev[2], ctx->stream));
+    MF_HIP(hipEventRecord(ctx->ev[8], ctx->stream));
     ctx->score_pending = true;
     return MF_OK;
 }

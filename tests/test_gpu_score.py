@@ -68,7 +68,8 @@ def test_scores_other_seeds_and_scales(mm, orc):
 
 
 @pytest.mark.parametrize("cfg,n,m", [("C1", None, None), ("C2", 130, 517), ("C4", 300, 1031), ("C5", 257, 700),
-                                     ("C3", 65, 257), ("C5", 1, 40), ("C3", 700, 90)])
+                                     ("C3", 65, 257), ("C5", 1, 40), ("C3", 700, 90), ("C3", 3, 40001),
+                                     ("C5", 2, 70003)])
 def test_memory_ordered_pass_gives_the_same_matrix(mm, orc, cfg, n, m):
     """Without a score buffer the kernel walks rows and columns by memory fraction and leaves out
     pairs that cannot fit: the matrix must equal the all-pairs pass bit for bit, and the checker's."""
