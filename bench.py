@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--update-rounds", type=int, default=3,
                     help="also time this many follow-up rounds with --churn of the workloads replaced")
     ap.add_argument("--churn", type=float, default=0.02)
+    ap.add_argument("--other-seeds", default="2,3",
+                    help="also run one warm-up and two rounds on these input seeds and report the median "
+                         "round time over all seeds ('' to skip)")
     ap.add_argument("--types", type=int, default=3,
                     help="also time scoring with this many per-GPU-type predictors (0: skip)")
     ap.add_argument("--calib-mib", type=int, default=0,
@@ -162,6 +165,22 @@ def main():
                          "path_super_steps": res.path_steps, "path_row_scans": res.path_scans,
                          "chain_steps": res.chain_depth - res.path_steps},
     }
+    if args.other_seeds:
+        # the same round on other draws of the workload: per-seed round time and the median over seeds
+        per_seed = {str(args.seed): ms_per_step}
+        for sd in [int(x) for x in args.other_seeds.split(",") if x]:
+            rs = synth.scheduling_round(args.config, sd)
+            ps = ctx.predictor({k: dev(v) for k, v in rs["params"].items()}, cfg.scale)
+            xo_s, xf_s = dev(rs["x_on"]), dev(rs["x_off"])
+            ctx.schedule_round(ps, xo_s, xf_s, W, r2c, u, v)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(2):
+                assert ctx.schedule_round(ps, xo_s, xf_s, W, r2c, u, v).cert_ok == 1
+            torch.cuda.synchronize()
+            per_seed[str(sd)] = (time.perf_counter() - t0) * 1e3 / 2
+            del rs, ps, xo_s, xf_s
+        out["seeds"] = {"round_ms": per_seed, "median_round_ms": float(np.median(list(per_seed.values())))}
     if args.update_rounds > 0:
         # follow-up rounds: a share of the online and offline workloads is replaced by fresh draws,
         # only their rows/columns are re-scored and the matching starts from the previous prices

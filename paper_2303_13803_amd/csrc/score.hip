@@ -13,6 +13,7 @@
 // coalesced int32 store.
 #include "internal.h"
 #include <math.h>
+#include <type_traits>
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -290,79 +291,112 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     // that column (float addition is monotone) no later row of the tile fits any of its columns
     const float moff_least = by_memory ? __shfl(moff, 0) : 0.0f;
 
-    int r = 0;
-    for (; r < nrows; ++r) {
-        // W2 does not fit in registers next to the accumulators: keep its loads inside the row loop
-        asm volatile("" ::: "memory");
-        if (by_memory && mon_lds[r] + moff_least > mem_limit) break;
-        floatx16 acc[MB];
+    // NR rows of the tile at once against this wavefront's 32 columns.  Two rows share every
+    // W2 operand fetched from LDS and give the matrix pipe two independent accumulator sets.
+    auto score_rows = [&](auto nr_tag, const int r) {
+        constexpr int NR = decltype(nr_tag)::value;
+        floatx16 acc[NR][MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 float4 bv = *(const float4 *)(b2_lds + mb * 32 + 8 * g + 4 * hh);
-                acc[mb][4 * g] = bv.x; acc[mb][4 * g + 1] = bv.y;
-                acc[mb][4 * g + 2] = bv.z; acc[mb][4 * g + 3] = bv.w;
+#pragma unroll
+                for (int x = 0; x < NR; ++x) {
+                    acc[x][mb][4 * g] = bv.x; acc[x][mb][4 * g + 1] = bv.y;
+                    acc[x][mb][4 * g + 2] = bv.z; acc[x][mb][4 * g + 3] = bv.w;
+                }
             }
-        const float *pon = pon_lds + r * H + hh * KS;
-        const float share = PAIR_SM ? fminf(son_lds[r], soff) : 0.0f;
+        float share[NR];
+#pragma unroll
+        for (int x = 0; x < NR; ++x) share[x] = PAIR_SM ? fminf(son_lds[r + x], soff) : 0.0f;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            float4 pv = *(const float4 *)(pon + 4 * q);
-            float h1[4];
-            if (PAIR_SM) {
-                const float4 ws = *(const float4 *)(wsm_lds + hh * KS + 4 * q);
-                h1[0] = fmaxf(fmaf(ws.x, share, pv.x + poff[4 * q]), 0.0f);
-                h1[1] = fmaxf(fmaf(ws.y, share, pv.y + poff[4 * q + 1]), 0.0f);
-                h1[2] = fmaxf(fmaf(ws.z, share, pv.z + poff[4 * q + 2]), 0.0f);
-                h1[3] = fmaxf(fmaf(ws.w, share, pv.w + poff[4 * q + 3]), 0.0f);
-            } else {
-                h1[0] = fmaxf(pv.x + poff[4 * q], 0.0f);
-                h1[1] = fmaxf(pv.y + poff[4 * q + 1], 0.0f);
-                h1[2] = fmaxf(pv.z + poff[4 * q + 2], 0.0f);
-                h1[3] = fmaxf(pv.w + poff[4 * q + 3], 0.0f);
+            float h1[NR][4];
+#pragma unroll
+            for (int x = 0; x < NR; ++x) {
+                const float4 pv = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 4 * q);
+                if (PAIR_SM) {
+                    const float4 ws = *(const float4 *)(wsm_lds + hh * KS + 4 * q);
+                    h1[x][0] = fmaxf(fmaf(ws.x, share[x], pv.x + poff[4 * q]), 0.0f);
+                    h1[x][1] = fmaxf(fmaf(ws.y, share[x], pv.y + poff[4 * q + 1]), 0.0f);
+                    h1[x][2] = fmaxf(fmaf(ws.z, share[x], pv.z + poff[4 * q + 2]), 0.0f);
+                    h1[x][3] = fmaxf(fmaf(ws.w, share[x], pv.w + poff[4 * q + 3]), 0.0f);
+                } else {
+                    h1[x][0] = fmaxf(pv.x + poff[4 * q], 0.0f);
+                    h1[x][1] = fmaxf(pv.y + poff[4 * q + 1], 0.0f);
+                    h1[x][2] = fmaxf(pv.z + poff[4 * q + 2], 0.0f);
+                    h1[x][3] = fmaxf(pv.w + poff[4 * q + 3], 0.0f);
+                }
             }
             float4 av[MB];
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) av[mb] = a_lds[(mb * Q + q) * 64 + lane];
+            // consecutive matrix instructions go to different accumulators: none waits for the one before
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].x, h1[0], acc[mb], 0, 0, 0);
-                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].y, h1[1], acc[mb], 0, 0, 0);
-                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].z, h1[2], acc[mb], 0, 0, 0);
-                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].w, h1[3], acc[mb], 0, 0, 0);
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int x = 0; x < NR; ++x)
+                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].x, h1[x][0], acc[x][mb], 0, 0, 0);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int x = 0; x < NR; ++x)
+                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].y, h1[x][1], acc[x][mb], 0, 0, 0);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int x = 0; x < NR; ++x)
+                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].z, h1[x][2], acc[x][mb], 0, 0, 0);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int x = 0; x < NR; ++x)
+                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].w, h1[x][3], acc[x][mb], 0, 0, 0);
+        }
+#pragma unroll
+        for (int x = 0; x < NR; ++x) {
+            // output layer on this lane's 16*MB hidden units, then add the other half-wave's
+            float zp = 0.0f;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float4 wv = *(const float4 *)(w3_lds + mb * 32 + 8 * g + 4 * hh);
+                    zp = fmaf(wv.x, fmaxf(acc[x][mb][4 * g], 0.0f), zp);
+                    zp = fmaf(wv.y, fmaxf(acc[x][mb][4 * g + 1], 0.0f), zp);
+                    zp = fmaf(wv.z, fmaxf(acc[x][mb][4 * g + 2], 0.0f), zp);
+                    zp = fmaf(wv.w, fmaxf(acc[x][mb][4 * g + 3], 0.0f), zp);
+                }
+            const float z = zp + __shfl_xor(zp, 32) + bias3;
+            const float sg = 1.0f / (1.0f + expf(-z));
+            if (hh == 0 && j < m) {
+                const int i = row_map ? row_map[row0 + r + x] : row0 + r + x;
+                float qv = rintf(sg * scale);
+                qv = fminf(fmaxf(qv, 0.0f), scale);
+                int32_t w = (int32_t)qv;
+                if (by_memory) {
+                    // row i of the staging matrix, columns in memory order: one whole line per wave;
+                    // the memory rule is applied when the columns are put back in place
+                    W[(size_t)i * ldw + j] = w;
+                } else {
+                    const float memsum = mon_lds[r + x] + moff;
+                    if (memsum > mem_limit) w = MF_INFEASIBLE;
+                    W[(size_t)i * ldw + jc] = w;
+                    if (sigma) sigma[(size_t)i * m + jc] = sg;
+                }
             }
         }
-        // output layer on this lane's 16*MB hidden units, then add the other half-wave's
-        float zp = 0.0f;
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float4 wv = *(const float4 *)(w3_lds + mb * 32 + 8 * g + 4 * hh);
-                zp = fmaf(wv.x, fmaxf(acc[mb][4 * g], 0.0f), zp);
-                zp = fmaf(wv.y, fmaxf(acc[mb][4 * g + 1], 0.0f), zp);
-                zp = fmaf(wv.z, fmaxf(acc[mb][4 * g + 2], 0.0f), zp);
-                zp = fmaf(wv.w, fmaxf(acc[mb][4 * g + 3], 0.0f), zp);
-            }
-        const float z = zp + __shfl_xor(zp, 32) + bias3;
-        const float sg = 1.0f / (1.0f + expf(-z));
-        if (hh == 0 && j < m) {
-            const int i = row_map ? row_map[row0 + r] : row0 + r;
-            float q = rintf(sg * scale);
-            q = fminf(fmaxf(q, 0.0f), scale);
-            int32_t w = (int32_t)q;
-            if (by_memory) {
-                // row i of the staging matrix, columns in memory order: one whole line per wave;
-                // the memory rule is applied when the columns are put back in place
-                W[(size_t)i * ldw + j] = w;
-            } else {
-                const float memsum = mon_lds[r] + moff;
-                if (memsum > mem_limit) w = MF_INFEASIBLE;
-                W[(size_t)i * ldw + jc] = w;
-                if (sigma) sigma[(size_t)i * m + jc] = sg;
-            }
-        }
+    };
+
+    int r = 0;
+    while (r < nrows) {
+        // W2 does not fit in registers next to the accumulators: keep its loads inside the row loop
+        asm volatile("" ::: "memory");
+        if (by_memory && mon_lds[r] + moff_least > mem_limit) break;
+        const bool pair_of_rows = r + 1 < nrows && !(by_memory && mon_lds[r + 1] + moff_least > mem_limit);
+        if (pair_of_rows) { score_rows(std::integral_constant<int, 2>{}, r); r += 2; }
+        else { score_rows(std::integral_constant<int, 1>{}, r); r += 1; }
     }
     // rows the loop left early get their "cannot fit" marks when the columns are put back in place
     if (evaluated && lane == 0 && r > 0) atomicAdd(evaluated, (unsigned long long)r * (unsigned)min(32, m - j0));

@@ -106,6 +106,31 @@ def test_more_online_than_offline_workloads(mm, orc):
     ctx.close()
 
 
+def test_largest_dimension_the_packed_words_allow(mm, orc):
+    """m = 2^20 - 2 columns (holder ids fill the 20-bit field of a packed word), a few rows:
+    scored, matched, certified; and the transposed shape, where the ids are the bidders'."""
+    m = (1 << 20) - 2
+    r = synth.scheduling_round("C2", 8, n=3, m=m)
+    ctx = mm.Context(3, m)
+    pred = ctx.predictor(dev_params(r["params"]), r["cfg"].scale)
+    Wd = empty_matrix(3, m)
+    r2c = torch.empty(3, dtype=torch.int32, device="cuda")
+    u = torch.empty(3, dtype=torch.int64, device="cuda"); v = torch.empty(m, dtype=torch.int64, device="cuda")
+    res = ctx.schedule_round(pred, dev(r["x_on"]), dev(r["x_off"]), Wd, r2c, u, v)
+    W = Wd[:, :m].cpu().numpy()
+    _, Wc = orc.score_pairs(r["x_on"], r["x_off"], r["params"], r["cfg"].scale)
+    assert ((W == INF) == (Wc == INF)).all()
+    ok = Wc != INF
+    assert np.abs(W[ok].astype(np.int64) - Wc[ok].astype(np.int64)).max() <= weight_tolerance(r["cfg"].scale)
+    _verify(orc, W, res, r2c.cpu().numpy(), u.cpu().numpy(), v.cpu().numpy(), orc.max_weight_matching(W)[0])
+    ctx.close()
+    Wt = np.ascontiguousarray(W.T)                                    # 1,048,574 rows x 3 columns
+    ctx = mm.Context(m, 3)
+    res, r2c, u, v = _solve(mm, ctx, Wt)
+    _verify(orc, Wt, res, r2c, u, v, orc.max_weight_matching(W)[0])
+    ctx.close()
+
+
 def test_degenerate_matrices(mm, orc):
     ctx = mm.Context(300, 400)
     n, m, S = 300, 400, 2 ** 20
