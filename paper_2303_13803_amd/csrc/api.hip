@@ -142,10 +142,10 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->path_label, nm));
     TRY(dev_alloc(&ctx->path_expanded, nm));
     for (int k = 0; k < 2; ++k) {
-        TRY(dev_alloc(&ctx->path_pair[k], nm));
-        TRY(dev_alloc(&ctx->path_dist[k], nm));
+        TRY(dev_alloc(&ctx->path_frontier[k], nm * 16));
     }
     TRY(dev_alloc(&ctx->path_held, nm));
+    TRY(dev_alloc(&ctx->path_stamp, nm));
     TRY(dev_alloc(&ctx->list[0], nm));
     TRY(dev_alloc(&ctx->list[1], nm));
     TRY(dev_alloc(&ctx->colmark, (size_t)max_m));
@@ -170,7 +170,7 @@ int mf_destroy(mf_ctx *ctx)
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->rank_off, ctx->type_segment, ctx->pairs_evaluated, ctx->wt, ctx->price,
-                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_pair[0], ctx->path_pair[1], ctx->path_dist[0], ctx->path_dist[1], ctx->path_held, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
+                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_frontier[0], ctx->path_frontier[1], ctx->path_stamp, ctx->path_held, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (ctx->h_stats) (void)hipHostFree(ctx->h_stats);

@@ -660,24 +660,29 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
 constexpr int PATH_THREADS = 1024;
 constexpr int PATH_MAX_SLICES = 1024;
 constexpr int PATH_GROUP = 16, PATH_MAX_GROUPS = 64;      // up to 1024 workgroups
+constexpr int PATH_SEGMENTS = 16, PATH_PUSH_BUFFER = 4096;
 constexpr unsigned long long PATH_INF = ~0ull;
 constexpr int PATH_FRONTIER_LOW = 128, PATH_FRONTIER_HIGH = 1024;
 
 struct alignas(128) PathCtl {
     unsigned long long sink;        // shortest complete path: length << 21 | kind << 20 | id (kind 1: row id gives up)
-    unsigned long long low[2];      // smallest label still to be expanded, per parity
+    unsigned long long low[3];      // smallest label still to be expanded, per slot
     unsigned long long first_value; // best value of the current bidder (bits of a double)
-    unsigned int count[2];          // frontier length per parity
     unsigned int arrive, generation, abort, pad;
     unsigned long long steps, scans;
     struct alignas(128) { unsigned int arrive; } group[PATH_MAX_GROUPS];
+    // Frontier lengths: one counter per segment (a segment collects the pushes of sixteen
+    // workgroups, so no counter is hit by more than sixteen atomics per step), in three slots:
+    // step t reads slot t % 3, fills slot (t + 1) % 3 and clears slot (t + 2) % 3, which every
+    // workgroup finished reading before the barrier that ended step t - 1.
+    struct alignas(128) { unsigned int count; } seg[3][PATH_SEGMENTS];
 };
 
 struct PathBuffers {
     unsigned long long *label;      // [len] length << 20 | predecessor row
     unsigned long long *expanded;   // [len] label at which the column's holder was last scanned
-    unsigned long long *fr_pair[2]; // frontier: (column held + 1) << 32 | row
-    double *fr_dist[2];             //           and the row's distance
+    unsigned int *stamp;            // [len] last step in which the column was put on a frontier
+    int *fr_col[2];                 // frontiers (by step parity): PATH_SEGMENTS segments of len columns each
     int *held;                      // [rows] column a frontier row holds
 };
 
@@ -740,8 +745,9 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                                                             double width_max, unsigned spin_limit)
 {
     __shared__ Top2 red[PATH_THREADS / 64];
-    __shared__ unsigned s_pushes, s_base;
+    __shared__ unsigned s_pushes, s_base, s_first[PATH_SEGMENTS + 1];
     __shared__ unsigned long long s_sink, s_low;
+    __shared__ int s_list[PATH_PUSH_BUFFER];
     const unsigned G = gridDim.x;
     const int wg = blockIdx.x, tid = threadIdx.x;
     const int gtid = wg * PATH_THREADS + tid, gsize = (int)G * PATH_THREADS;
@@ -755,49 +761,96 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         for (int k = gtid; k < s.len; k += gsize) {
             store_through(&buf.label[k], PATH_INF);
             store_through(&buf.expanded[k], PATH_INF);
+            __hip_atomic_store(&buf.stamp[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (wg == 0) {
             const Top2 t = block_scan<PATH_THREADS>(s.A + (size_t)r0 * s.pitch, s.other_dual, s.len, s.Kd, true,
                                                     red, 0, 0);
+            if (tid < 3 * PATH_SEGMENTS)
+                __hip_atomic_store(&ctl->seg[tid / PATH_SEGMENTS][tid % PATH_SEGMENTS].count, 0u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
             if (tid == 0) {
                 const double v1 = t.b1;
                 store_through(&ctl->first_value, (unsigned long long)__double_as_longlong(v1));
                 store_through(&ctl->low[0], PATH_INF);
                 store_through(&ctl->low[1], PATH_INF);
-                __hip_atomic_store(&ctl->count[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(&ctl->count[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (v1 > s.eps) {
-                    const double profit = v1 - s.eps;                   // pi_r: rc(r, best column) = 0
-                    store_through(&ctl->sink, ((unsigned long long)(long long)profit << 21) | (1ull << 20) |
+                store_through(&ctl->low[2], PATH_INF);
+                if (v1 > s.eps) {                                       // pi_r = v1 - eps: rc(r, best column) = 0
+                    store_through(&ctl->sink, ((unsigned long long)(long long)(v1 - s.eps) << 21) | (1ull << 20) |
                                                   (unsigned long long)r0);
-                    store_through(&buf.fr_pair[0][0], (unsigned long long)r0);       // holds no column
-                    store_through((unsigned long long *)&buf.fr_dist[0][0], 0ull);
                     __hip_atomic_store(&buf.held[r0], -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
         }
         if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
-        // duals stand still during a search: drop what the caches hold of them from before the
-        // last re-assignment once, then read them through the caches
+        // duals and holders stand still during a search: drop what the caches hold of them from
+        // before the last re-assignment once, then read them through the caches
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         const double v1 = __longlong_as_double((long long)load_fresh_u64(&ctl->first_value));
         if (v1 <= s.eps) continue;                                      // rests with dual 0: nothing to move
         const double first_profit = v1 - s.eps;
 
-        // ---- label-correcting search ----
-        int parity = 0;
+        // ---- label-correcting search, one grid barrier per super-step ----
+        // A step scans the rows on the current frontier; a label that falls inside the window
+        // puts its column on the next frontier at once (claimed through a per-step stamp, so once
+        // per step), whose holder is scanned in the next step from the label the column has by
+        // then.  Only when a frontier comes up empty does a pass over all columns pick up the
+        // labels that fell outside earlier windows, or move the window on.
         double low = 0.0;
-        // The window of labels expanded per super-step adapts to what it yields: wide enough to
-        // keep the device busy, narrow enough that rows are not scanned long before their label
-        // is final (every workgroup derives the same width from the same counters).
+        // The window adapts to what it yields: wide enough to keep the device busy, narrow enough
+        // that rows are not scanned long before their label is final (every workgroup derives the
+        // same width from the same counters).
         double width = 4.0 * s.eps;
         unsigned long long my_steps = 0, my_scans = 0;
+        const int segment = wg / PATH_GROUP % PATH_SEGMENTS;
+        unsigned step = 0;
+        bool swept = false;                      // the previous step was a pass over all columns
         for (;;) {
-            const int nf = (int)load_fresh_u32(&ctl->count[parity]);
-            const double bound = (double)(long long)(load_fresh_u64(&ctl->sink) >> 21);
+            ++step;
+            const unsigned c = step % 3u, p = (step + 1u) % 3u, z = (step + 2u) % 3u;
+            // frontier of this step: its segments' lengths (the very first holds just the bidder)
+            if (tid < 64) {
+                unsigned n_seg = 0;
+                if (tid < PATH_SEGMENTS && step > 1u) n_seg = load_fresh_u32(&ctl->seg[c][tid].count);
+                unsigned run = n_seg;                               // inclusive prefix sums over 16 lanes
+                for (int d = 1; d < PATH_SEGMENTS; d <<= 1) {
+                    const unsigned o = __shfl_up(run, d);
+                    if ((int)tid >= d) run += o;
+                }
+                if (tid < PATH_SEGMENTS) s_first[tid + 1] = run;
+                if (tid == 0) { s_first[0] = 0u; s_pushes = 0u; s_sink = PATH_INF; s_low = PATH_INF; }
+            }
+            __syncthreads();
+            const int nf = step == 1u ? 1 : (int)s_first[PATH_SEGMENTS];
+            const unsigned long long sink_word = load_fresh_u64(&ctl->sink);
+            const double bound = (double)(long long)(sink_word >> 21);
+            if (step > 1u && swept && nf == 0) {
+                const unsigned long long lo = load_fresh_u64(&ctl->low[c]);
+                if (lo == PATH_INF || lo >= (sink_word >> 21)) break;       // every label below the sink is final
+                low = (double)(long long)lo;                                // move the window to the next label
+            }
             if (nf > PATH_FRONTIER_HIGH) width = fmax(s.eps, width * 0.5);
             else if (nf < PATH_FRONTIER_LOW) width = fmin(width_max, width * 2.0);
+            const double limit = fmin(low + width, bound);
+            if (gtid < PATH_SEGMENTS)
+                __hip_atomic_store(&ctl->seg[z][gtid].count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (gtid == 0) store_through(&ctl->low[z], PATH_INF);
+            const int *frontier = buf.fr_col[step & 1u];
+            int *next_frontier = buf.fr_col[(step + 1u) & 1u];
+
+            // puts column k on the next frontier (through the workgroup's LDS list while it has room)
+            auto push = [&](int k) {
+                const unsigned slot = atomicAdd(&s_pushes, 1u);
+                if (slot < (unsigned)PATH_PUSH_BUFFER) s_list[slot] = k;
+                else {
+                    const unsigned pos = atomicAdd(&ctl->seg[p][segment].count, 1u);
+                    __hip_atomic_store(&next_frontier[(size_t)segment * s.len + pos], k, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                }
+            };
+
             if (nf > 0) {
+                swept = false;
                 // one wavefront per (row, slice of columns): enough independent loads in flight to
                 // stream the rows at memory speed whether the frontier holds one row or thousands
                 constexpr int WAVES = PATH_THREADS / 64;
@@ -809,17 +862,30 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                 const int items = nf * slices;
                 for (int it = wave_id; it < items; it += total_waves) {
                     const int e = it / slices, sl = it - e * slices;
-                    const unsigned long long pair = load_fresh_u64(&buf.fr_pair[parity][e]);
-                    const double dist = load_fresh(&buf.fr_dist[parity][e]);
-                    const int i = (int)(pair & 0xffffffffull), mine_col = (int)(pair >> 32) - 1;
+                    int i, mine_col;
+                    double dist, profit;
+                    if (step == 1u) {
+                        i = r0; mine_col = -1; dist = 0.0; profit = first_profit;
+                    } else {
+                        int g = 0;
+                        while ((unsigned)e >= s_first[g + 1]) ++g;
+                        mine_col = __hip_atomic_load(&frontier[(size_t)g * s.len + (e - s_first[g])], __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+                        const unsigned long long lw = load_fresh_u64(&buf.label[mine_col]);
+                        i = word_id(s.otherword[mine_col]);
+                        dist = (double)(long long)(lw >> MF_ID_BITS);
+                        // the row's profit: what it holds minus that column's dual
+                        profit = s.Kd * (double)s.A[(size_t)i * s.pitch + mine_col] - s.other_dual[mine_col];
+                        if (sl == 0 && lane == 0) {
+                            store_through(&buf.expanded[mine_col], lw >> MF_ID_BITS);
+                            __hip_atomic_store(&buf.held[i], mine_col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if (dist + profit < bound)                      // it may also give up and rest
+                                atomicMin(&ctl->sink, ((unsigned long long)(long long)(dist + profit) << 21) |
+                                                          (1ull << 20) | (unsigned long long)i);
+                        }
+                    }
                     const int32_t *row = s.A + (size_t)i * s.pitch;
-                    // the row's profit: what it holds minus that column's dual (the bidder holds nothing)
-                    const double profit = mine_col < 0 ? first_profit
-                                                       : s.Kd * (double)row[mine_col] - s.other_dual[mine_col];
                     const double base = dist + profit + s.eps;
-                    if (sl == 0 && lane == 0 && mine_col >= 0 && dist + profit < bound)     // it may also give up and rest
-                        atomicMin(&ctl->sink, ((unsigned long long)(long long)(dist + profit) << 21) | (1ull << 20) |
-                                                  (unsigned long long)i);
                     const int from = sl * span, to = min(s.len, from + span);
 #pragma unroll 2
                     for (int k = from + lane * 4; k < to; k += 256) {
@@ -836,74 +902,50 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                                                                 (unsigned long long)i;
                                 // a cached label is never below the true one (labels only fall during a
                                 // search and the caches were emptied at its start): a safe first test
-                                if (mine < buf.label[k + q]) atomicMin(&buf.label[k + q], mine);
+                                if (mine < buf.label[k + q] && atomicMin(&buf.label[k + q], mine) > mine && cand < limit &&
+                                    atomicExch(&buf.stamp[k + q], step) != step) {
+                                    if (word_id(s.otherword[k + q]) < 0)    // a column nobody holds ends a path
+                                        atomicMin(&ctl->sink, (unsigned long long)(long long)cand << 21 |
+                                                                  (unsigned long long)(k + q));
+                                    else push(k + q);
+                                }
                             }
                         }
                     }
                     if (sl == 0 && lane == 0) ++my_scans;
                 }
-            }
-            ++my_steps;
-            if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
-
-            // ---- which holders have to be scanned next ----
-            const double sink_now = (double)(long long)(load_fresh_u64(&ctl->sink) >> 21);
-            const double limit = fmin(low + width, sink_now);
-            const int np = parity ^ 1;
-            // Pushes, the sink and the window's next start all meet in single words: every workgroup
-            // first combines its threads' contributions in LDS and then sends one atomic of each.
-            for (int first = 0; first < s.len; first += gsize) {
-                const int k = first + gtid;
-                if (tid == 0) { s_pushes = 0u; s_sink = PATH_INF; s_low = PATH_INF; }
-                __syncthreads();
-                int holder = -1;
-                unsigned slot = 0;
-                unsigned long long d_int = 0;
-                if (k < s.len) {
-                    const unsigned long long lw = load_fresh_u64(&buf.label[k]);
-                    const unsigned long long ex = load_fresh_u64(&buf.expanded[k]);
-                    const unsigned long long cw = load_fresh_u64(&s.otherword[k]);
-                    d_int = lw >> MF_ID_BITS;
-                    const double d = (double)(long long)d_int;
-                    if (lw != PATH_INF && d < sink_now && d_int < ex) {
-                        if (d >= limit) {
-                            atomicMin(&s_low, d_int);
-                        } else if (word_id(cw) < 0) {                       // a column nobody holds ends a path
-                            atomicMin(&s_sink, (d_int << 21) | (unsigned long long)k);
-                        } else {
-                            holder = word_id(cw);
-                            slot = atomicAdd(&s_pushes, 1u);
+            } else {
+                // ---- nothing on the frontier: look at every column ----
+                swept = true;
+                for (int first = 0; first < s.len; first += gsize) {
+                    const int k = first + gtid;
+                    if (k < s.len) {
+                        const unsigned long long lw = load_fresh_u64(&buf.label[k]);
+                        const unsigned long long ex = load_fresh_u64(&buf.expanded[k]);
+                        const unsigned long long d_int = lw >> MF_ID_BITS;
+                        const double d = (double)(long long)d_int;
+                        if (lw != PATH_INF && d < bound && d_int < ex) {
+                            if (d >= limit) atomicMin(&s_low, d_int);
+                            else if (word_id(s.otherword[k]) < 0) atomicMin(&s_sink, (d_int << 21) | (unsigned long long)k);
+                            else push(k);
                         }
                     }
                 }
-                __syncthreads();
-                if (tid == 0) {
-                    s_base = s_pushes ? atomicAdd(&ctl->count[np], s_pushes) : 0u;
-                    if (s_sink != PATH_INF) atomicMin(&ctl->sink, s_sink);
-                    if (s_low != PATH_INF) atomicMin(&ctl->low[np], s_low);
-                }
-                __syncthreads();
-                if (holder >= 0) {
-                    const unsigned pos = s_base + slot;
-                    store_through(&buf.expanded[k], d_int);
-                    store_through(&buf.fr_pair[np][pos], ((unsigned long long)(k + 1) << 32) | (unsigned long long)holder);
-                    store_through((unsigned long long *)&buf.fr_dist[np][pos],
-                                  (unsigned long long)__double_as_longlong((double)(long long)d_int));
-                    __hip_atomic_store(&buf.held[holder], k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
             }
-            if (gtid == 0) {                                                // this parity is refilled after the next barrier
-                __hip_atomic_store(&ctl->count[parity], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                store_through(&ctl->low[parity], PATH_INF);
+            // ---- hand the workgroup's pushes, sink and window candidates over ----
+            __syncthreads();
+            const unsigned pushed = min(s_pushes, (unsigned)PATH_PUSH_BUFFER);
+            if (tid == 0) {
+                s_base = pushed ? atomicAdd(&ctl->seg[p][segment].count, pushed) : 0u;
+                if (s_sink != PATH_INF) atomicMin(&ctl->sink, s_sink);
+                if (s_low != PATH_INF) atomicMin(&ctl->low[p], s_low);
             }
+            __syncthreads();
+            for (unsigned t = tid; t < pushed; t += PATH_THREADS)
+                __hip_atomic_store(&next_frontier[(size_t)segment * s.len + s_base + t], s_list[t], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            ++my_steps;
             if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
-            parity = np;
-            if (load_fresh_u32(&ctl->count[parity]) == 0u) {
-                const unsigned long long lo = load_fresh_u64(&ctl->low[parity]);
-                const unsigned long long sk = load_fresh_u64(&ctl->sink) >> 21;
-                if (lo == PATH_INF || lo >= sk) break;                      // every label below the sink is final
-                low = (double)(long long)lo;                                // jump to the next window with work
-            }
         }
         if (!alive) break;
 
@@ -1241,8 +1283,8 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
                    (team_steps >= ctx->path_after || count > ctx->team_max || ctx->team_max == 0 || ctx->team_off)) {
             // few enough bidders, and chains long enough, to place each bidder by a shortest-path
             // search over the whole device
-            PathBuffers buf{ctx->path_label, ctx->path_expanded, {ctx->path_pair[0], ctx->path_pair[1]},
-                            {ctx->path_dist[0], ctx->path_dist[1]}, ctx->path_held};
+            PathBuffers buf{ctx->path_label, ctx->path_expanded, ctx->path_stamp,
+                            {ctx->path_frontier[0], ctx->path_frontier[1]}, ctx->path_held};
             hipLaunchKernelGGL(path_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats,
                                (PathCtl *)ctx->path_ctl, ring);
             hipLaunchKernelGGL(path_kernel, dim3(ctx->n_cus), dim3(PATH_THREADS), 0, ctx->stream, s,

@@ -82,8 +82,8 @@ struct mf_ctx {
     void *team_ctl;                 // control blocks of the cooperating workgroups
     void *path_ctl;                 // control block of the shortest-path search
     unsigned long long *path_label, *path_expanded;   // [max(max_n, max_m)] each
-    unsigned long long *path_pair[2];
-    double *path_dist[2];
+    unsigned int *path_stamp;
+    int *path_frontier[2];          // 16 segments of max(max_n, max_m) columns each
     int *path_held;
     int path_max;                   // bidders at or below which shortest-path searches place them (0: never)
     long long path_after;           // chain steps per run after which the searches take over
