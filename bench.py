@@ -165,6 +165,12 @@ def main():
                          "path_super_steps": res.path_steps, "path_row_scans": res.path_scans,
                          "chain_steps": res.chain_depth - res.path_steps},
     }
+    # measured ceilings of this device next to the published peaks
+    ceil = ctx.measure_ceilings(W)
+    out["roofline"]["measured_ceiling"] = ceil["mfma_f32_tflops"]
+    out["roofline"]["frac_of_measured_ceiling"] = achieved / 1e12 / ceil["mfma_f32_tflops"]
+    out["roofline_bid_scan"]["measured_ceiling"] = ceil["read_gbps"]
+    out["roofline_bid_scan"]["frac_of_measured_ceiling"] = bulk_bytes / (bulk_ms * 1e-3) / 1e9 / ceil["read_gbps"]
     if args.other_seeds:
         # the same round on other draws of the workload: per-seed round time and the median over seeds
         per_seed = {str(args.seed): ms_per_step}

@@ -255,6 +255,17 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value);
  */
 int mf_last_timings(mf_ctx *ctx, float what[16]);
 
+/*
+ * Measured ceilings of the device, as second denominators next to the
+ * published peaks (diagnostic; the scheduling round does not use it):
+ * out[0] = TFLOP/s of a dependency-free stream of v_mfma_f32_32x32x2_f32 on
+ * every compute unit (the matrix instruction of the scoring kernel), out[1] its
+ * duration in ms; with d_buffer (device, 16-byte aligned, `bytes` long, only
+ * read) out[2] = GB/s of a plain streaming read of it and out[3] its duration.
+ * Waits for the stream.
+ */
+int mf_measure_ceilings(mf_ctx *ctx, const void *d_buffer, int64_t bytes, float out[4]);
+
 const char *mf_strerror(int code);
 const char *mf_last_hip_error(mf_ctx *ctx);
 

@@ -18,7 +18,7 @@ OK, ERR_ARG, ERR_SHAPE, ERR_HIP, ERR_NOT_CONVERGED, ERR_CERT, ERR_RANGE = 0, -1,
 
 EXPORTS = ["mf_create", "mf_destroy", "mf_score_pairs", "mf_solve_assignment",
            "mf_check_certificate", "mf_schedule_round", "mf_schedule_round_update", "mf_score_pairs_typed",
-           "mf_schedule_round_typed", "mf_set_option", "mf_last_timings",
+           "mf_schedule_round_typed", "mf_set_option", "mf_last_timings", "mf_measure_ceilings",
            "mf_strerror", "mf_last_hip_error"]
 
 TIMING_NAMES = ["projections_ms", "pair_scoring_ms", "bulk_bid_ms", "bulk_bid_launches",
@@ -63,6 +63,7 @@ def load_library():
     lib.mf_score_pairs_typed.argtypes = [vp, C.POINTER(Predictor), i32, vp, vp, i32, vp, i32, vp, i64, vp]
     lib.mf_schedule_round_typed.argtypes = [vp, C.POINTER(Predictor), i32, vp, vp, i32, vp, i32, vp, i64, vp, vp, vp,
                                             C.POINTER(Result)]
+    lib.mf_measure_ceilings.argtypes = [vp, vp, i64, C.POINTER(C.c_float * 4)]
     lib.mf_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.mf_last_timings.argtypes = [vp, C.POINTER(C.c_float * 16)]
     lib.mf_strerror.argtypes = [i32]
@@ -195,6 +196,14 @@ class Context:
             _ptr(x_off, torch.float32), m, _ptr(W, torch.int32), W.stride(0), _ptr(row2col, torch.int32),
             _ptr(u, torch.int64), _ptr(v, torch.int64), C.byref(res)))
         return res
+
+    def measure_ceilings(self, buffer=None):
+        """Measured fp32 MFMA rate (TFLOP/s) and, with a device tensor, streaming read rate (GB/s)."""
+        arr = (C.c_float * 4)()
+        nbytes = 0 if buffer is None else buffer.numel() * buffer.element_size()
+        self._check(_lib.mf_measure_ceilings(self._h, None if buffer is None else buffer.data_ptr(), nbytes,
+                                             C.byref(arr)))
+        return {"mfma_f32_tflops": float(arr[0]), "read_gbps": float(arr[2])}
 
     def last_timings(self):
         arr = (C.c_float * 16)()
