@@ -227,9 +227,12 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
 /* Solver knobs: "theta" (epsilon divisor per phase, default 16), "max_rounds" (limit on
  * evaluated bids, default 4,000,000,000), "tail_max" (bidder count at or below which one
  * kernel follows the remaining eviction chains, default 1024), "chain_grid" (workgroups of
- * that kernel, default 256), "team_max" (chains at or below which several workgroups share
- * each chain, default 8), "team_size" / "team_threads" (workgroups per chain and threads per
- * workgroup there, default 16 / 1024), "path_max" (bidders at or below which each is placed by
+ * that kernel, default 256), "team_wide" (chains at or below which teams of workgroups take the
+ * chains over, as many workgroups per chain as the device has per chain, default 64; 0: only at
+ * "team_max"), "team_regroup" (steps after which such teams stop so that the chains still going
+ * get larger teams, default 128), "team_max" (chains at or below which the chains' step budget
+ * "path_after" starts to count, default 8), "team_size" / "team_threads" (most workgroups per
+ * chain and threads per workgroup there, default 16 / 1024), "path_max" (bidders at or below which each is placed by
  * a device-wide shortest-augmenting-path search once the chains have gone on for "path_after"
  * steps, defaults 8 and 256; path_max 0 turns the searches off), "path_width" (widest label
  * window of a search step, in epsilons, default 1024), "path_spin_limit" (polls a workgroup of a

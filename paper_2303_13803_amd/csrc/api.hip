@@ -100,6 +100,8 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->bulk_shape = 1;
     ctx->team_max = 8;
     ctx->team_size = 16;
+    ctx->team_wide = 64;
+    ctx->team_regroup = 128;
     ctx->team_threads = 1024;
     ctx->fit_order = true;
     ctx->path_max = 8;
@@ -137,7 +139,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->roword, nm));
     TRY(dev_alloc(&ctx->row2col, nm));
     TRY(dev_alloc(&ctx->col2row, nm));
-    TRY(hipMalloc(&ctx->team_ctl, 32 * 1024));
+    TRY(hipMalloc(&ctx->team_ctl, 128 * 1024));
     TRY(hipMalloc(&ctx->path_ctl, 16384));
     TRY(dev_alloc(&ctx->path_label, nm));
     TRY(dev_alloc(&ctx->path_expanded, nm));
@@ -325,6 +327,8 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "warm_reset_cols")) { ctx->warm_reset_cols = value != 0; return MF_OK; }
     if (!strcmp(name, "warm_eps_units")) { if (value < 0 || value > (1 << 30)) return MF_ERR_ARG; ctx->warm_eps_units = value; return MF_OK; }
     if (!strcmp(name, "team_max")) { if (value < 0 || value > 16) return MF_ERR_ARG; ctx->team_max = (int)value; return MF_OK; }
+    if (!strcmp(name, "team_wide")) { if (value < 0 || value > 64) return MF_ERR_ARG; ctx->team_wide = (int)value; return MF_OK; }
+    if (!strcmp(name, "team_regroup")) { if (value < 1) return MF_ERR_ARG; ctx->team_regroup = value; return MF_OK; }
     if (!strcmp(name, "team_size")) { if (value < 2 || value > 32) return MF_ERR_ARG; ctx->team_size = (int)value; return MF_OK; }
     if (!strcmp(name, "team_threads")) { if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return MF_ERR_ARG; ctx->team_threads = (int)value; return MF_OK; }
     if (!strcmp(name, "chain_grid")) { if (value < 1 || value > 4096) return MF_ERR_ARG; ctx->chain_grid = (int)value; return MF_OK; }

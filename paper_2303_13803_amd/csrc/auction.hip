@@ -455,7 +455,7 @@ __global__ void chain_begin_kernel(mf_device_stats *stats, int ring, int workgro
 // every wait is bounded, and a wait that runs out raises `abort` so that all
 // workgroups leave and the host falls back to chain_kernel.
 constexpr int TEAM_SIZE_MAX = 32;        // workgroups per chain (run-time choice up to this)
-constexpr int TEAM_MAX = 16;             // chains served at once
+constexpr int TEAM_MAX = 64;             // chains served at once
 constexpr unsigned TEAM_SPIN_LIMIT = 1u << 21;
 
 struct alignas(128) TeamCtl {
@@ -667,7 +667,10 @@ constexpr int PATH_FRONTIER_LOW = 128, PATH_FRONTIER_HIGH = 1024;
 struct alignas(128) PathCtl {
     unsigned long long sink;        // shortest complete path: length << 21 | kind << 20 | id (kind 1: row id gives up)
     unsigned long long low[3];      // smallest label still to be expanded, per slot
-    unsigned long long first_value; // best value of the current bidder (bits of a double)
+    // best value of the current bidder (bits of a double), by parity of its position in the list:
+    // when a bidder rests, workgroup 0 may already be writing the next bidder's value while a
+    // slower workgroup has yet to read this one
+    unsigned long long first_value[2];
     unsigned int arrive, generation, abort, pad;
     unsigned long long steps, scans;
     struct alignas(128) { unsigned int arrive; } group[PATH_MAX_GROUPS];
@@ -771,7 +774,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                                    __HIP_MEMORY_SCOPE_AGENT);
             if (tid == 0) {
                 const double v1 = t.b1;
-                store_through(&ctl->first_value, (unsigned long long)__double_as_longlong(v1));
+                store_through(&ctl->first_value[item & 1], (unsigned long long)__double_as_longlong(v1));
                 store_through(&ctl->low[0], PATH_INF);
                 store_through(&ctl->low[1], PATH_INF);
                 store_through(&ctl->low[2], PATH_INF);
@@ -783,10 +786,10 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
             }
         }
         if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
-        // duals and holders stand still during a search: drop what the caches hold of them from
-        // before the last re-assignment once, then read them through the caches
+        // duals stand still during a search: drop what the caches hold of them from before the
+        // last re-assignment once, then read them through the caches
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        const double v1 = __longlong_as_double((long long)load_fresh_u64(&ctl->first_value));
+        const double v1 = __longlong_as_double((long long)load_fresh_u64(&ctl->first_value[item & 1]));
         if (v1 <= s.eps) continue;                                      // rests with dual 0: nothing to move
         const double first_profit = v1 - s.eps;
 
@@ -872,7 +875,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                         mine_col = __hip_atomic_load(&frontier[(size_t)g * s.len + (e - s_first[g])], __ATOMIC_RELAXED,
                                                      __HIP_MEMORY_SCOPE_AGENT);
                         const unsigned long long lw = load_fresh_u64(&buf.label[mine_col]);
-                        i = word_id(s.otherword[mine_col]);
+                        i = word_id(load_fresh_u64(&s.otherword[mine_col]));
                         dist = (double)(long long)(lw >> MF_ID_BITS);
                         // the row's profit: what it holds minus that column's dual
                         profit = s.Kd * (double)s.A[(size_t)i * s.pitch + mine_col] - s.other_dual[mine_col];
@@ -904,7 +907,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                                 // search and the caches were emptied at its start): a safe first test
                                 if (mine < buf.label[k + q] && atomicMin(&buf.label[k + q], mine) > mine && cand < limit &&
                                     atomicExch(&buf.stamp[k + q], step) != step) {
-                                    if (word_id(s.otherword[k + q]) < 0)    // a column nobody holds ends a path
+                                    if (word_id(load_fresh_u64(&s.otherword[k + q])) < 0)    // a column nobody holds ends a path
                                         atomicMin(&ctl->sink, (unsigned long long)(long long)cand << 21 |
                                                                   (unsigned long long)(k + q));
                                     else push(k + q);
@@ -926,7 +929,8 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                         const double d = (double)(long long)d_int;
                         if (lw != PATH_INF && d < bound && d_int < ex) {
                             if (d >= limit) atomicMin(&s_low, d_int);
-                            else if (word_id(s.otherword[k]) < 0) atomicMin(&s_sink, (d_int << 21) | (unsigned long long)k);
+                            else if (word_id(load_fresh_u64(&s.otherword[k])) < 0)
+                                atomicMin(&s_sink, (d_int << 21) | (unsigned long long)k);
                             else push(k);
                         }
                     }
@@ -1268,7 +1272,14 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
     // `path_after` steps is ended by shortest-path searches instead.
     long long team_steps = 0;
     while (count > 0) {
-        bool timed = false, ran_teams = false;
+        bool timed = false, counted_teams = false;
+        const bool paths_ok = ctx->path_max > 0 && !ctx->path_off && ctx->n_cus > 0;
+        const bool teams_ok = ctx->team_max > 0 && !ctx->team_off;
+        const int cus = ctx->n_cus > 0 ? ctx->n_cus : 256;
+        // chains at or below which teams take over from one workgroup per chain
+        int team_from = ctx->team_wide > ctx->team_max ? ctx->team_wide : ctx->team_max;
+        if (team_from > TEAM_MAX) team_from = TEAM_MAX;
+        if (team_from * 2 > cus) team_from = cus / 2;
         const long long left = ctx->max_rounds - (long long)ctx->h_stats->bids;
         if (left <= 0) return MF_ERR_NOT_CONVERGED;
         if (count > ctx->tail_max) {
@@ -1279,8 +1290,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
                 if (time_first && r == 0) MF_HIP(hipEventRecord(ctx->ev[7], ctx->stream));
                 ++ring;
             }
-        } else if (ctx->path_max > 0 && count <= ctx->path_max && !ctx->path_off && ctx->n_cus > 0 &&
-                   (team_steps >= ctx->path_after || count > ctx->team_max || ctx->team_max == 0 || ctx->team_off)) {
+        } else if (paths_ok && count <= ctx->path_max && (team_steps >= ctx->path_after || !teams_ok)) {
             // few enough bidders, and chains long enough, to place each bidder by a shortest-path
             // search over the whole device
             PathBuffers buf{ctx->path_label, ctx->path_expanded, ctx->path_stamp,
@@ -1292,46 +1302,50 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
                                buf, ring, ctx->max_n > ctx->max_m ? ctx->max_n : ctx->max_m,
                                (double)ctx->path_width * s.eps, ctx->path_spin_limit);
             ++ring;
-        } else if (count > ctx->team_max || ctx->team_max == 0 || ctx->team_off) {
+        } else if (!teams_ok || count > team_from) {
             const int grid = count < ctx->chain_grid ? count : ctx->chain_grid;
-            const bool paths = ctx->path_max > 0 && !ctx->path_off && ctx->n_cus > 0;
-            const bool teams = ctx->team_max > 0 && !ctx->team_off;
-            const int hand_back = (paths && (!teams || ctx->path_max > ctx->team_max)) ? ctx->path_max
-                                                                                       : (teams ? ctx->team_max : -1);
+            const int hand_back = teams_ok ? team_from : (paths_ok ? ctx->path_max : -1);
             hipLaunchKernelGGL(chain_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats, ring, grid);
             hipLaunchKernelGGL(chain_kernel, dim3(grid), dim3(CHAIN_THREADS), 0, ctx->stream, s,
                                ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, ring,
                                left / grid + 1, hand_back);
             ++ring;
         } else {
-            const int teams = count < ctx->team_max ? count : ctx->team_max;
-            const bool paths = ctx->path_max > 0 && !ctx->path_off && ctx->n_cus > 0 && count <= ctx->path_max;
+            // every remaining chain gets a team: the fewer chains, the more workgroups on each
+            const int teams = count;
+            int size = cus / teams;
+            size = size < 2 ? 2 : (size > ctx->team_size ? ctx->team_size : size);
+            const bool before_paths = paths_ok && count <= ctx->path_max;
             long long team_cap = left / teams + 1;
-            if (paths && ctx->path_after - team_steps < team_cap) team_cap = ctx->path_after - team_steps;
-            ran_teams = true;
+            // many chains: stop after a while to regroup the ones still going into larger teams;
+            // few: until the searches' turn
+            const long long stop_after = before_paths ? ctx->path_after - team_steps
+                                                      : (count > ctx->team_max ? ctx->team_regroup : team_cap);
+            if (stop_after < team_cap) team_cap = stop_after;
+            counted_teams = before_paths;
             hipLaunchKernelGGL(team_begin_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->stats,
                                (TeamCtl *)ctx->team_ctl, ring);
-            const dim3 grid(teams * ctx->team_size);
+            const dim3 grid(teams * size);
             if (ctx->team_threads == 64)
                 hipLaunchKernelGGL(team_kernel<64>, grid, dim3(64), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   team_cap, ctx->team_size);
+                                   team_cap, size);
             else if (ctx->team_threads == 128)
                 hipLaunchKernelGGL(team_kernel<128>, grid, dim3(128), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   team_cap, ctx->team_size);
+                                   team_cap, size);
             else if (ctx->team_threads == 256)
                 hipLaunchKernelGGL(team_kernel<256>, grid, dim3(256), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   team_cap, ctx->team_size);
+                                   team_cap, size);
             else if (ctx->team_threads == 512)
                 hipLaunchKernelGGL(team_kernel<512>, grid, dim3(512), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   team_cap, ctx->team_size);
+                                   team_cap, size);
             else
                 hipLaunchKernelGGL(team_kernel<1024>, grid, dim3(1024), 0, ctx->stream, s, ctx->list[ring & 1],
                                    ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   team_cap, ctx->team_size);
+                                   team_cap, size);
             ++ring;
         }
         MF_HIP(hipGetLastError());
@@ -1346,7 +1360,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
         }
         time_first = false;
         count = ctx->h_stats->cnt[ring & 3];
-        if (ran_teams) team_steps += (long long)ctx->h_stats->launch_max;     // the longest any leader went
+        if (counted_teams) team_steps += (long long)ctx->h_stats->launch_max;     // the longest any leader went
         if (ctx->h_stats->team_abort == 1) ctx->team_off = true;   // a bounded wait ran out: one workgroup per chain from now on
         if (ctx->h_stats->team_abort == 2) ctx->path_off = true;   // ... or no more shortest-path searches
     }

@@ -77,7 +77,9 @@ struct mf_ctx {
     int tail_max;                   // bidder count at or below which chains are followed in one kernel
     int bulk_shape;                 // workgroup shape of rounds with many bidders (see launch_round)
     int team_max;                   // chains at or below which several workgroups share each chain (0: never)
-    int team_size, team_threads;    // workgroups per chain, threads per such workgroup
+    int team_size, team_threads;    // most workgroups per chain, threads per such workgroup
+    int team_wide;                  // chains at or below which smaller teams already take over from chain_kernel
+    long long team_regroup;         // steps after which such teams stop so that the chains left can be regrouped
     bool team_off;                  // set after a team wait ran out
     void *team_ctl;                 // control blocks of the cooperating workgroups
     void *path_ctl;                 // control block of the shortest-path search

@@ -52,7 +52,9 @@ def _optimum(orc, W):
 
 
 @pytest.mark.parametrize("options", [{"path_after": 0}, {"path_after": 0, "path_max": 64, "team_max": 0},
-                                     {"path_after": 0, "path_width": 1}, {"path_after": 40}])
+                                     {"path_after": 0, "path_width": 1}, {"path_after": 40},
+                                     {"team_wide": 64, "team_regroup": 16, "path_after": 30},
+                                     {"team_wide": 24, "team_size": 4, "path_max": 0}])
 def test_searches_reach_the_optimum(mm, orc, options):
     used = 0
     for name, W in _cases():
@@ -62,7 +64,8 @@ def test_searches_reach_the_optimum(mm, orc, options):
         res = _solve_and_verify(ctx, orc, W, _optimum(orc, W))
         used += res.path_steps
         ctx.close()
-    assert used > 0, "no search ran: the cases no longer exercise this path"
+    if options.get("path_max", 8) > 0:
+        assert used > 0, "no search ran: the cases no longer exercise this path"
 
 
 def test_scored_round_with_searches_only(mm, orc):
@@ -70,6 +73,7 @@ def test_scored_round_with_searches_only(mm, orc):
     W = orc.score_pairs(r["x_on"], r["x_off"], r["params"], r["cfg"].scale, wide=False)[1]
     ctx = mm.Context(1500, 1500)
     ctx.set_option("path_after", 0)
+    ctx.set_option("team_wide", 0)                  # no teams between the chain kernel and the searches
     res = _solve_and_verify(ctx, orc, W, orc.max_weight_matching(W)[0])
     assert res.path_steps > 0 and res.team_bids == 0
     ctx.close()
