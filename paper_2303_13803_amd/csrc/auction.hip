@@ -456,6 +456,7 @@ __global__ void chain_begin_kernel(mf_device_stats *stats, int ring, int workgro
 // workgroups leave and the host falls back to chain_kernel.
 constexpr int TEAM_SIZE_MAX = 32;        // workgroups per chain (run-time choice up to this)
 constexpr int TEAM_MAX = 64;             // chains served at once
+constexpr int TEAM_WIDE_MIN_LINE = 8192; // shortest line for which many small teams pay
 constexpr unsigned TEAM_SPIN_LIMIT = 1u << 21;
 
 struct alignas(128) TeamCtl {
@@ -1277,7 +1278,9 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
         const bool teams_ok = ctx->team_max > 0 && !ctx->team_off;
         const int cus = ctx->n_cus > 0 ? ctx->n_cus : 256;
         // chains at or below which teams take over from one workgroup per chain
-        int team_from = ctx->team_wide > ctx->team_max ? ctx->team_wide : ctx->team_max;
+        // (lines short enough for one compute unit to read in a couple of microseconds gain nothing
+        // from being split: there the teams wait for the last few chains)
+        int team_from = (ctx->team_wide > ctx->team_max && s.len >= TEAM_WIDE_MIN_LINE) ? ctx->team_wide : ctx->team_max;
         if (team_from > TEAM_MAX) team_from = TEAM_MAX;
         if (team_from * 2 > cus) team_from = cus / 2;
         const long long left = ctx->max_rounds - (long long)ctx->h_stats->bids;
