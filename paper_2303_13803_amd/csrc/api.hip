@@ -91,7 +91,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->stream = (hipStream_t)hip_stream;
     ctx->max_n = max_n;
     ctx->max_m = max_m;
-    ctx->theta = 16;
+    ctx->theta = 24;
     ctx->max_rounds = 4000000000ll;
     ctx->tail_max = 1024;
     ctx->warm_eps_units = 0;
