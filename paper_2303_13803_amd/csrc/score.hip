@@ -310,49 +310,61 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
         float share[NR];
 #pragma unroll
         for (int x = 0; x < NR; ++x) share[x] = PAIR_SM ? fminf(son_lds[r + x], soff) : 0.0f;
+        // operands of step q + 1 are fetched from LDS before the matrix instructions of step q are
+        // issued, so that their latency hides behind those instead of in front of the next ones
+        float4 av[2][MB], pv[2][NR];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) av[0][mb] = a_lds[(mb * Q) * 64 + lane];
+#pragma unroll
+        for (int x = 0; x < NR; ++x) pv[0][x] = *(const float4 *)(pon_lds + (r + x) * H + hh * KS);
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
+            const int cur = q & 1, nxt = cur ^ 1;
+            if (q + 1 < Q) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) av[nxt][mb] = a_lds[(mb * Q + q + 1) * 64 + lane];
+#pragma unroll
+                for (int x = 0; x < NR; ++x)
+                    pv[nxt][x] = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 4 * (q + 1));
+            }
             float h1[NR][4];
 #pragma unroll
             for (int x = 0; x < NR; ++x) {
-                const float4 pv = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 4 * q);
+                const float4 pq = pv[cur][x];
                 if (PAIR_SM) {
                     const float4 ws = *(const float4 *)(wsm_lds + hh * KS + 4 * q);
-                    h1[x][0] = fmaxf(fmaf(ws.x, share[x], pv.x + poff[4 * q]), 0.0f);
-                    h1[x][1] = fmaxf(fmaf(ws.y, share[x], pv.y + poff[4 * q + 1]), 0.0f);
-                    h1[x][2] = fmaxf(fmaf(ws.z, share[x], pv.z + poff[4 * q + 2]), 0.0f);
-                    h1[x][3] = fmaxf(fmaf(ws.w, share[x], pv.w + poff[4 * q + 3]), 0.0f);
+                    h1[x][0] = fmaxf(fmaf(ws.x, share[x], pq.x + poff[4 * q]), 0.0f);
+                    h1[x][1] = fmaxf(fmaf(ws.y, share[x], pq.y + poff[4 * q + 1]), 0.0f);
+                    h1[x][2] = fmaxf(fmaf(ws.z, share[x], pq.z + poff[4 * q + 2]), 0.0f);
+                    h1[x][3] = fmaxf(fmaf(ws.w, share[x], pq.w + poff[4 * q + 3]), 0.0f);
                 } else {
-                    h1[x][0] = fmaxf(pv.x + poff[4 * q], 0.0f);
-                    h1[x][1] = fmaxf(pv.y + poff[4 * q + 1], 0.0f);
-                    h1[x][2] = fmaxf(pv.z + poff[4 * q + 2], 0.0f);
-                    h1[x][3] = fmaxf(pv.w + poff[4 * q + 3], 0.0f);
+                    h1[x][0] = fmaxf(pq.x + poff[4 * q], 0.0f);
+                    h1[x][1] = fmaxf(pq.y + poff[4 * q + 1], 0.0f);
+                    h1[x][2] = fmaxf(pq.z + poff[4 * q + 2], 0.0f);
+                    h1[x][3] = fmaxf(pq.w + poff[4 * q + 3], 0.0f);
                 }
             }
-            float4 av[MB];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) av[mb] = a_lds[(mb * Q + q) * 64 + lane];
             // consecutive matrix instructions go to different accumulators: none waits for the one before
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int x = 0; x < NR; ++x)
-                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].x, h1[x][0], acc[x][mb], 0, 0, 0);
+                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][mb].x, h1[x][0], acc[x][mb], 0, 0, 0);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int x = 0; x < NR; ++x)
-                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].y, h1[x][1], acc[x][mb], 0, 0, 0);
+                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][mb].y, h1[x][1], acc[x][mb], 0, 0, 0);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int x = 0; x < NR; ++x)
-                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].z, h1[x][2], acc[x][mb], 0, 0, 0);
+                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][mb].z, h1[x][2], acc[x][mb], 0, 0, 0);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int x = 0; x < NR; ++x)
-                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb].w, h1[x][3], acc[x][mb], 0, 0, 0);
+                    acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][mb].w, h1[x][3], acc[x][mb], 0, 0, 0);
         }
 #pragma unroll
         for (int x = 0; x < NR; ++x) {
