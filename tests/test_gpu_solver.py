@@ -131,6 +131,42 @@ def test_largest_dimension_the_packed_words_allow(mm, orc):
     ctx.close()
 
 
+def test_weights_at_the_edge_of_exact_arithmetic(mm, orc):
+    """Duals are exact integers below 2^43: K * max W must stay under that.  8,000 rows with a
+    weight of 2^30 still solve; 8,200 rows are refused with MF_ERR_RANGE rather than answered."""
+    for n, fits in ((8000, True), (8200, False)):
+        Wd = torch.zeros((n, n), dtype=torch.int32, device="cuda")
+        Wd[5, 7] = 2 ** 30
+        Wd[6, 7] = 2 ** 30 - 3
+        Wd[5, 9] = 11
+        ctx = mm.Context(n, n)
+        r2c = torch.empty(n, dtype=torch.int32, device="cuda")
+        u = torch.empty(n, dtype=torch.int64, device="cuda"); v = torch.empty(n, dtype=torch.int64, device="cuda")
+        if fits:
+            res = ctx.solve_assignment(Wd, n, n, r2c, u, v)
+            assert res.cert_ok == 1 and res.primal == 2 ** 30 - 3 + 11 + 0      # rows 5 and 6 swap for 8 more
+            code, P, D = orc.check_certificate(Wd.cpu().numpy(), r2c.cpu().numpy(), u.cpu().numpy(),
+                                               v.cpu().numpy(), res.K)
+            assert code == 0 and P == res.primal
+        else:
+            with pytest.raises(mm.MuxmatchError) as e:
+                ctx.solve_assignment(Wd, n, n, r2c, u, v)
+            assert e.value.code == mm.ERR_RANGE
+        ctx.close()
+
+
+def test_empty_problems_are_refused(mm):
+    ctx = mm.Context(4, 4)
+    W = torch.zeros((4, 4), dtype=torch.int32, device="cuda")
+    r2c = torch.empty(4, dtype=torch.int32, device="cuda")
+    u = torch.empty(4, dtype=torch.int64, device="cuda"); v = torch.empty(4, dtype=torch.int64, device="cuda")
+    for n, m in ((0, 4), (4, 0), (0, 0)):
+        with pytest.raises(mm.MuxmatchError) as e:
+            ctx.solve_assignment(W, n, m, r2c, u, v)
+        assert e.value.code == mm.ERR_ARG
+    ctx.close()
+
+
 def test_degenerate_matrices(mm, orc):
     ctx = mm.Context(300, 400)
     n, m, S = 300, 400, 2 ** 20
