@@ -157,7 +157,7 @@ def main():
                                "value = n*m / time of one whole round (score + match + certificate)"},
         "schedule_round_ms": ms_per_step,
         "score_pairs_per_s": n * m / ((pair_ms + avg["projections_ms"]) * 1e-3),
-        "stage_ms": {k: avg[k] for k in ("projections_ms", "pair_scoring_ms", "transpose_ms", "auction_ms",
+        "stage_ms": {k: avg[k] for k in ("projections_ms", "pair_scoring_ms", "prepare_ms", "auction_ms",
                                          "duals_ms", "certificate_ms")},
         "auction": {"phases": res.phases, "rounds": res.rounds, "bids": res.bids,
                     "bytes_scanned": res.bytes_scanned, "chain_bids": res.chain_bids, "chain_depth": res.chain_depth, "chain_retries": res.chain_retries, "team_bids": res.team_bids, "path_steps": res.path_steps, "path_scans": res.path_scans, "matched": res.matched,

@@ -250,7 +250,9 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value);
  * launched, by stage, measured with HIP events on the context's stream:
  * what[0] layer-1 projections (and the memory ordering), [1] pair scoring,
  * [2] the bidding rounds in which every line of the bidding side scans (the
- * first of each phase), [3] how many of those ran, [4] transposition,
+ * first of each phase), [3] how many of those ran, [4] preparation of the solve (largest
+ * weight; the transposed copy when it is needed up front - otherwise it is made inside [7] when a
+ * phase first needs it),
  * [5] dual extraction, [6] certificate, [7] the whole auction, [8] weight
  * bytes the rounds of [2] scanned, [9] the fraction of the n*m pairs the pair
  * kernel ran the MLP on (the rest could not fit in memory and were marked

@@ -22,7 +22,7 @@ EXPORTS = ["mf_create", "mf_destroy", "mf_score_pairs", "mf_solve_assignment",
            "mf_strerror", "mf_last_hip_error"]
 
 TIMING_NAMES = ["projections_ms", "pair_scoring_ms", "bulk_bid_ms", "bulk_bid_launches",
-                "transpose_ms", "duals_ms", "certificate_ms", "auction_ms", "bulk_bid_bytes",
+                "prepare_ms", "duals_ms", "certificate_ms", "auction_ms", "bulk_bid_bytes",
                 "pairs_evaluated_fraction"]
 
 

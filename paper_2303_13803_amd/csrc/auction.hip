@@ -1120,6 +1120,25 @@ __global__ __launch_bounds__(256) void transpose_kernel(const int32_t *__restric
     if ((threadIdx.x & 63) == 0 && mx > stats->max_weight) atomicMax(&stats->max_weight, mx);
 }
 
+// The largest weight alone (it sets the first epsilon), for solves that may never need W^T.
+__global__ __launch_bounds__(256) void max_weight_kernel(const int32_t *__restrict__ W, int n, int m, int64_t ldw,
+                                                         mf_device_stats *stats)
+{
+    int mx = 0;
+    for (int i = blockIdx.y; i < n; i += gridDim.y) {
+        const int32_t *row = W + (size_t)i * ldw;
+        for (int j = (blockIdx.x * 256 + threadIdx.x) * 4; j < m; j += gridDim.x * 1024) {
+            const int4 v = *(const int4 *)(row + j);            // the pitch is a multiple of four
+            mx = max(mx, v.x);
+            if (j + 1 < m) mx = max(mx, v.y);
+            if (j + 2 < m) mx = max(mx, v.z);
+            if (j + 3 < m) mx = max(mx, v.w);
+        }
+    }
+    for (int off = 32; off >= 1; off >>= 1) mx = max(mx, __shfl_xor(mx, off));
+    if ((threadIdx.x & 63) == 0 && mx > stats->max_weight) atomicMax(&stats->max_weight, mx);
+}
+
 // Duals handed to the caller: v_j = p_j and the tightest row dual the prices
 // allow, u_i = max(0, max_j (K W_ij - p_j)).
 __global__ __launch_bounds__(BID_THREADS) void duals_kernel(
@@ -1426,8 +1445,21 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     if (warm && n_reset_cols > 0)
         hipLaunchKernelGGL(zero_listed_kernel, dim3((n_reset_cols + 255) / 256), dim3(256), 0, ctx->stream,
                            ctx->price, d_reset_cols, n_reset_cols, m);
-    hipLaunchKernelGGL(transpose_kernel, dim3((m + 63) / 64, (n + 63) / 64), dim3(256), 0, ctx->stream,
-                       d_W, n, m, ldw, ctx->wt, ldt, ctx->stats);
+    // W^T serves the second side of a phase (unassigned columns that still carry a price), which a
+    // square, fully matched problem may never enter: it is made when first needed, unless the
+    // transposed problem is the one being solved
+    bool have_transpose = false;
+    auto make_transpose = [&]() {
+        hipLaunchKernelGGL(transpose_kernel, dim3((m + 63) / 64, (n + 63) / 64), dim3(256), 0, ctx->stream,
+                           d_W, n, m, ldw, ctx->wt, ldt, ctx->stats);
+        have_transpose = true;
+    };
+    if (flip) make_transpose();
+    else {
+        const int chunks = (m + 4095) / 4096 < 4 ? (m + 4095) / 4096 : 4;
+        hipLaunchKernelGGL(max_weight_kernel, dim3(chunks, n < 1024 ? n : 1024), dim3(256), 0, ctx->stream, d_W, n, m,
+                           ldw, ctx->stats);
+    }
     MF_HIP(hipGetLastError());
     MF_HIP(hipEventRecord(ctx->ev[4], ctx->stream));
     MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
@@ -1466,6 +1498,7 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         MF_HIP(hipStreamSynchronize(ctx->stream));
         const int rev_count = ctx->h_stats->cnt[0];
         if (rev_count > 0) {
+            if (!have_transpose) make_transpose();
             rc = run_side(ctx, rev, rev_count, false);
             if (rc != MF_OK) return rc;
             hipLaunchKernelGGL(reverse_done_cols_kernel, dim3((rm + 255) / 256), dim3(256), 0, ctx->stream, rm,
