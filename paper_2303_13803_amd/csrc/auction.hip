@@ -64,7 +64,14 @@ struct SideArgs {
     double *other_dual;                 // opposite duals as doubles, raised with atomicMax on the bits
     unsigned long long *otherword;      // opposite packed (dual, holder): the authoritative copy
     double eps, Kd;
+    const int *line_len;                // optional: every entry of line b at or beyond line_len[b] is infeasible
 };
+
+// How much of line b a scan has to read.
+__device__ __forceinline__ int line_length(const SideArgs &s, int b)
+{
+    return s.line_len ? min(s.line_len[b], s.len) : s.len;
+}
 
 // Loads that must observe values other wavefronts produced during this kernel:
 // they bypass the caches that atomics performed at the memory side do not update.
@@ -338,19 +345,23 @@ __global__ __launch_bounds__(NT) void round_kernel(SideArgs s, const int *__rest
         if (count > 0) {
             stats->rounds += 1ull;
             stats->bids += (unsigned long long)count;
-            stats->bytes += (unsigned long long)count * (unsigned long long)s.len * 4ull;
         }
     }
+    unsigned long long entries = 0;                         // scanned by this workgroup (thread 0 keeps count)
     for (int item = blockIdx.x * RB; item < count; item += gridDim.x * RB) {
         int salt[RB];
         const int32_t *rows[RB];
+        int len = 0;                                        // the group scans as far as its longest line
 #pragma unroll
         for (int r = 0; r < RB; ++r) {
             const int b = list[min(item + r, count - 1)];   // a short last group repeats its last line
             rows[r] = s.A + (size_t)b * s.pitch;
             salt[r] = tie_salt(b);
+            const int lb = line_length(s, b);
+            len = max(len, lb);
+            if (item + r < count) entries += (unsigned long long)lb;
         }
-        block_scan_rows<NT, RB>(rows, salt, s.other_dual, s.len, s.Kd, red);
+        block_scan_rows<NT, RB>(rows, salt, s.other_dual, len, s.Kd, red);
         if (threadIdx.x < 64) {                                      // first wavefront: one lane bids per line
             int again = -1;
             if (threadIdx.x < RB && item + (int)threadIdx.x < count) {
@@ -369,6 +380,7 @@ __global__ __launch_bounds__(NT) void round_kernel(SideArgs s, const int *__rest
             }
         }
     }
+    if (threadIdx.x == 0 && entries) atomicAdd(&stats->bytes, entries * 4ull);
 }
 
 // The tail of a run.  When few bidders are left, rounds are bound by launch
@@ -390,7 +402,7 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const 
     __shared__ int s_next, s_active;
     if (threadIdx.x == 0) s_active = 0x7fffffff;
     const int count = stats->cnt[ring & 3];
-    unsigned long long steps = 0, retries = 0;
+    unsigned long long steps = 0, retries = 0, scanned = 0;
     for (;;) {
         __syncthreads();
         if (threadIdx.x == 0) s_next = atomicAdd(&stats->head, 1);
@@ -411,7 +423,9 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const 
                 break;
             }
             ++steps;
-            Top2 t = block_scan<CHAIN_THREADS>(s.A + (size_t)b * s.pitch, s.other_dual, s.len, s.Kd, fresh, red,
+            const int len = line_length(s, b);
+            scanned += (unsigned long long)len;
+            Top2 t = block_scan<CHAIN_THREADS>(s.A + (size_t)b * s.pitch, s.other_dual, len, s.Kd, fresh, red,
                                                0, tie_salt(b));
             t.idx ^= tie_salt(b);
             if (threadIdx.x == 0) s_next = decide_and_bid(s, b, t);
@@ -427,7 +441,7 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const 
         if (steps) {
             atomicAdd(&stats->bids, steps);
             atomicAdd(&stats->chain_bids, steps);
-            atomicAdd(&stats->bytes, steps * (unsigned long long)s.len * 4ull);
+            atomicAdd(&stats->bytes, scanned * 4ull);
             atomicMax(&stats->launch_max, steps);
             if (retries) atomicAdd(&stats->chain_retries, retries);
         }
@@ -507,10 +521,14 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
     __shared__ long long s_word;
     TeamCtl *ctl = ctl_all + blockIdx.x / TEAM_SIZE;
     const int member = blockIdx.x % TEAM_SIZE;
-    const int slice = (((s.len + TEAM_SIZE - 1) / TEAM_SIZE) + 3) & ~3;
-    const int off = member * slice;
-    const int my_len = max(0, min(slice, s.len - off));
     const int count = stats->cnt[ring & 3];
+    // the members share a line in equal slices of what has to be read of it
+    auto slice_of = [&](int b, int &off) {
+        const int len = line_length(s, b);
+        const int slice = (((len + TEAM_SIZE - 1) / TEAM_SIZE) + 3) & ~3;
+        off = member * slice;
+        return max(0, min(slice, len - off));
+    };
 
     if (member != 0) {
         // ---- member: wait for the leader's next command, scan, post ----
@@ -535,6 +553,8 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
             if (b < 0) break;                                   // stop (or abort)
             // a slice is small enough to stay in this compute unit's cache from step to step, so the
             // duals are always read past the caches here
+            int off;
+            const int my_len = slice_of(b, off);
             const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch + off, s.other_dual + off, my_len, s.Kd,
                                           true, red, off, tie_salt(b));
             if (threadIdx.x == 0) {
@@ -551,7 +571,7 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
 
     // ---- leader: follow chains, one command per step ----
     unsigned seq = 0;
-    unsigned long long steps = 0, retries = 0;
+    unsigned long long steps = 0, retries = 0, scanned = 0;
     bool dead = false;
     while (!dead) {
         __syncthreads();
@@ -572,6 +592,9 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
             if (threadIdx.x == 0)
                 store_through(&ctl->cmd, ((unsigned long long)seq << 32) | (fresh ? 0x80000000ull : 0ull) |
                                              (unsigned long long)(b + 1));
+            int off;
+            const int my_len = slice_of(b, off);                       // member 0: off == 0
+            scanned += (unsigned long long)line_length(s, b);
             const Top2 t = block_scan<NT>(s.A + (size_t)b * s.pitch, s.other_dual, my_len, s.Kd, true, red, 0,
                                           tie_salt(b));
             if (threadIdx.x < 64) {                         // first wavefront: one lane per member
@@ -623,7 +646,7 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
             atomicAdd(&stats->bids, steps);
             atomicAdd(&stats->chain_bids, steps);
             atomicAdd(&stats->team_bids, steps);
-            atomicAdd(&stats->bytes, steps * (unsigned long long)s.len * 4ull);
+            atomicAdd(&stats->bytes, scanned * 4ull);
             atomicMax(&stats->launch_max, steps);
             if (retries) atomicAdd(&stats->chain_retries, retries);
         }
@@ -673,7 +696,7 @@ struct alignas(128) PathCtl {
     // slower workgroup has yet to read this one
     unsigned long long first_value[2];
     unsigned int arrive, generation, abort, pad;
-    unsigned long long steps, scans;
+    unsigned long long steps, scans, entries;
     struct alignas(128) { unsigned int arrive; } group[PATH_MAX_GROUPS];
     // Frontier lengths: one counter per segment (a segment collects the pushes of sixteen
     // workgroups, so no counter is hit by more than sixteen atomics per step), in three slots:
@@ -728,7 +751,7 @@ __device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned 
 
 __global__ void path_begin_kernel(mf_device_stats *stats, PathCtl *ctl, int ring)
 {
-    ctl->arrive = 0u; ctl->generation = 0u; ctl->abort = 0u; ctl->steps = 0ull; ctl->scans = 0ull;
+    ctl->arrive = 0u; ctl->generation = 0u; ctl->abort = 0u; ctl->steps = 0ull; ctl->scans = 0ull; ctl->entries = 0ull;
     for (int g = 0; g < PATH_MAX_GROUPS; ++g) ctl->group[g].arrive = 0u;
     stats->cnt[(ring + 1) & 3] = 0;
     stats->cnt[(ring + 2) & 3] = 0;
@@ -768,8 +791,8 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
             __hip_atomic_store(&buf.stamp[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (wg == 0) {
-            const Top2 t = block_scan<PATH_THREADS>(s.A + (size_t)r0 * s.pitch, s.other_dual, s.len, s.Kd, true,
-                                                    red, 0, 0);
+            const Top2 t = block_scan<PATH_THREADS>(s.A + (size_t)r0 * s.pitch, s.other_dual, line_length(s, r0),
+                                                    s.Kd, true, red, 0, 0);
             if (tid < 3 * PATH_SEGMENTS)
                 __hip_atomic_store(&ctl->seg[tid / PATH_SEGMENTS][tid % PATH_SEGMENTS].count, 0u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
@@ -805,7 +828,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         // that rows are not scanned long before their label is final (every workgroup derives the
         // same width from the same counters).
         double width = 4.0 * s.eps;
-        unsigned long long my_steps = 0, my_scans = 0;
+        unsigned long long my_steps = 0, my_scans = 0, my_entries = 0;
         const int segment = wg / PATH_GROUP % PATH_SEGMENTS;
         unsigned step = 0;
         bool swept = false;                      // the previous step was a pass over all columns
@@ -890,7 +913,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                     }
                     const int32_t *row = s.A + (size_t)i * s.pitch;
                     const double base = dist + profit + s.eps;
-                    const int from = sl * span, to = min(s.len, from + span);
+                    const int from = sl * span, to = min(line_length(s, i), from + span);
 #pragma unroll 2
                     for (int k = from + lane * 4; k < to; k += 256) {
                         const int4 w4 = *(const int4 *)(row + k);
@@ -916,7 +939,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                             }
                         }
                     }
-                    if (sl == 0 && lane == 0) ++my_scans;
+                    if (sl == 0 && lane == 0) { ++my_scans; my_entries += (unsigned long long)line_length(s, i); }
                 }
             } else {
                 // ---- nothing on the frontier: look at every column ----
@@ -988,7 +1011,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                 atomicAdd(&ctl->steps, my_steps);
             }
         }
-        if ((tid & 63) == 0 && my_scans) atomicAdd(&ctl->scans, my_scans);
+        if ((tid & 63) == 0 && my_scans) { atomicAdd(&ctl->scans, my_scans); atomicAdd(&ctl->entries, my_entries); }
         if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; ++item; break; }   // r0 is placed
     }
     if (gtid == 0) {
@@ -1001,7 +1024,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         stats->chain_bids += scans;
         stats->path_steps += steps;
         stats->path_scans += scans;
-        stats->bytes += scans * (unsigned long long)s.len * 4ull;
+        stats->bytes += load_fresh_u64(&ctl->entries) * 4ull;
     }
 }
 
@@ -1293,6 +1316,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
     long long team_steps = 0;
     while (count > 0) {
         bool timed = false, counted_teams = false;
+        const unsigned long long bytes_before = ctx->h_stats->bytes;
         const bool paths_ok = ctx->path_max > 0 && !ctx->path_off && ctx->n_cus > 0;
         const bool teams_ok = ctx->team_max > 0 && !ctx->team_off;
         const int cus = ctx->n_cus > 0 ? ctx->n_cus : 256;
@@ -1305,7 +1329,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
         const long long left = ctx->max_rounds - (long long)ctx->h_stats->bids;
         if (left <= 0) return MF_ERR_NOT_CONVERGED;
         if (count > ctx->tail_max) {
-            const int batch = count > 4096 ? 1 : 3;
+            const int batch = (count > 4096 || time_first) ? 1 : 3;     // the timed round stands alone
             for (int r = 0; r < batch; ++r) {
                 if (time_first && r == 0) { MF_HIP(hipEventRecord(ctx->ev[6], ctx->stream)); timed = true; }
                 launch_round(ctx, s, count, ring);
@@ -1378,7 +1402,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
             MF_HIP(hipEventElapsedTime(&ms, ctx->ev[6], ctx->ev[7]));
             ctx->timings[T_BID_BULK] += ms;
             ctx->timings[T_BID_BULK_LAUNCHES] += 1.0f;
-            ctx->timings[T_BID_BULK_BYTES] += (float)((double)count * s.len * 4.0);
+            ctx->timings[T_BID_BULK_BYTES] += (float)((double)(ctx->h_stats->bytes - bytes_before));
         }
         time_first = false;
         count = ctx->h_stats->cnt[ring & 3];
