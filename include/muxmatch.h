@@ -122,8 +122,9 @@ typedef struct {
  * Creates a context bound to HIP device `device` and to `hip_stream` (a
  * hipStream_t passed as void*, NULL = the default stream).  Allocates all
  * scratch for problems up to max_n x max_m (each at most 2^20 - 2):
- * layer-1 projections, a transposed copy of the weight matrix
- * (4*max_n*max_m bytes) and O(max_n + max_m) solver state.
+ * layer-1 projections, a transposed copy of the weight matrix and a copy with
+ * rows and columns in order of memory fraction (4*max_n*max_m bytes each) and
+ * O(max_n + max_m) solver state.
  * Fails with MF_ERR_HIP when no such device exists or memory runs out.
  */
 int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m);
@@ -242,7 +243,9 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
  * "warm_eps_units" (0, the default: mf_schedule_round_update matches from scratch; > 0: from
  * the previous prices at that epsilon, in weight units), "warm_reset_cols", "fit_order" (1,
  * the default: scoring skips pairs that cannot fit in memory; 0: every pair goes through the
- * MLP). */
+ * MLP), "fit_prefix_below" (percent, default 50: when fewer of the pairs just scored can share
+ * GPU memory, mf_schedule_round matches on the context's memory-ordered copy of the matrix, where
+ * those pairs are a prefix of every row and column, and reads only the prefixes; 0: never). */
 int mf_set_option(mf_ctx *ctx, const char *name, int64_t value);
 
 /*

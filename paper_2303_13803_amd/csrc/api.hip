@@ -104,6 +104,8 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->team_regroup = 128;
     ctx->team_threads = 1024;
     ctx->fit_order = true;
+    ctx->fit_prefix = true;
+    ctx->fit_prefix_below = 50;
     ctx->path_max = 8;
     ctx->path_width = 1024;
     ctx->path_after = 256;
@@ -125,14 +127,18 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->order_on, (size_t)max_n));
     TRY(dev_alloc(&ctx->order_off, (size_t)max_m));
     TRY(dev_alloc(&ctx->rank_off, (size_t)max_m));
+    TRY(dev_alloc(&ctx->rank_on, (size_t)max_n));
+    TRY(dev_alloc(&ctx->mem_on_sorted, (size_t)max_n));
+    TRY(dev_alloc(&ctx->mem_off_sorted, (size_t)max_m + 4));
+    TRY(dev_alloc(&ctx->fit_len_on, (size_t)max_n));
+    TRY(dev_alloc(&ctx->fit_len_off, (size_t)max_m));
+    TRY(dev_alloc(&ctx->staged, (size_t)max_n * ((((size_t)max_m + 3) & ~(size_t)3))));
     TRY(dev_alloc(&ctx->type_segment, (size_t)MF_MAX_TYPES + 1));
     TRY(dev_alloc(&ctx->pairs_evaluated, 1));
+    TRY(dev_alloc(&ctx->feasible_pairs, 1));
+    TRY(hipHostMalloc((void **)&ctx->h_feasible_pairs, sizeof(unsigned long long)));
     TRY(hipHostMalloc((void **)&ctx->h_pairs_evaluated, sizeof(unsigned long long)));
-    {   // holds W^T for the solver ([m][n padded]) and, while scoring, W with its columns in memory order ([n][m padded])
-        const size_t ldo = ((size_t)max_m + 3) & ~(size_t)3;
-        const size_t a = (size_t)max_m * ldt, b = (size_t)max_n * ldo;
-        TRY(dev_alloc(&ctx->wt, a > b ? a : b));
-    }
+    TRY(dev_alloc(&ctx->wt, (size_t)max_m * ldt));
     TRY(dev_alloc(&ctx->price, nm + 8));
     TRY(dev_alloc(&ctx->profit, nm + 8));
     TRY(dev_alloc(&ctx->colword, nm));
@@ -171,13 +177,14 @@ int mf_destroy(mf_ctx *ctx)
     if (!ctx) return MF_ERR_ARG;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->rank_off, ctx->type_segment, ctx->pairs_evaluated, ctx->wt, ctx->price,
+    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->rank_off, ctx->rank_on, ctx->mem_on_sorted, ctx->mem_off_sorted, ctx->fit_len_on, ctx->fit_len_off, ctx->staged, ctx->type_segment, ctx->pairs_evaluated, ctx->feasible_pairs, ctx->wt, ctx->price,
                    ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_frontier[0], ctx->path_frontier[1], ctx->path_stamp, ctx->path_held, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (ctx->h_stats) (void)hipHostFree(ctx->h_stats);
     if (ctx->h_cert) (void)hipHostFree(ctx->h_cert);
     if (ctx->h_pairs_evaluated) (void)hipHostFree(ctx->h_pairs_evaluated);
+    if (ctx->h_feasible_pairs) (void)hipHostFree(ctx->h_feasible_pairs);
     for (int i = 0; i < 10; ++i) if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
     delete ctx;
     return MF_OK;
@@ -204,7 +211,7 @@ int mf_solve_assignment(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t l
     MF_HIP(hipSetDevice(ctx->device));
     clear_timings(ctx);
     memset(h_res, 0, sizeof(*h_res));
-    rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, false, nullptr, 0);
+    rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, false, nullptr, 0, false);
     h_res->status = rc;
     return rc;
 }
@@ -244,7 +251,7 @@ int mf_schedule_round(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, 
     clear_timings(ctx);
     memset(h_res, 0, sizeof(*h_res));
     rc = mf_launch_score(ctx, pred, 1, nullptr, d_on, n, d_off, m, d_W, ldw, nullptr);
-    if (rc == MF_OK) rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, false, nullptr, 0);
+    if (rc == MF_OK) rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, false, nullptr, 0, true);
     if (rc == MF_OK || rc == MF_ERR_CERT) {
         int rt = finish_score_timing(ctx);
         if (rt != MF_OK) rc = rt;
@@ -279,7 +286,7 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
     clear_timings(ctx);
     memset(h_res, 0, sizeof(*h_res));
     rc = mf_launch_score(ctx, preds, n_types, d_type_on, d_on, n, d_off, m, d_W, ldw, nullptr);
-    if (rc == MF_OK) rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, false, nullptr, 0);
+    if (rc == MF_OK) rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, false, nullptr, 0, true);
     if (rc == MF_OK || rc == MF_ERR_CERT) {
         int rt = finish_score_timing(ctx);
         if (rt != MF_OK) rc = rt;
@@ -309,7 +316,7 @@ int mf_schedule_round_update(mf_ctx *ctx, const mf_predictor *pred, const float 
                            d_changed_off, n_changed_off);
     if (rc == MF_OK)
         rc = mf_run_solver(ctx, d_W, n, m, ldw, d_row2col, d_u, d_v, h_res, ctx->warm_eps_units > 0, d_changed_off,
-                           ctx->warm_reset_cols ? n_changed_off : 0);
+                           ctx->warm_reset_cols ? n_changed_off : 0, false);
     if (rc == MF_OK || rc == MF_ERR_CERT) {
         int rt = finish_score_timing(ctx);
         if (rt != MF_OK) rc = rt;
@@ -336,6 +343,8 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "path_spin_limit")) { if (value < 0 || value > (1ll << 30)) return MF_ERR_ARG; ctx->path_spin_limit = (unsigned)value; ctx->path_off = false; return MF_OK; }
     if (!strcmp(name, "path_after")) { if (value < 0) return MF_ERR_ARG; ctx->path_after = value; return MF_OK; }
     if (!strcmp(name, "path_width")) { if (value < 1 || value > (1 << 30)) return MF_ERR_ARG; ctx->path_width = (int)value; return MF_OK; }
+    if (!strcmp(name, "fit_prefix_below")) { if (value < 0 || value > 101) return MF_ERR_ARG; ctx->fit_prefix_below = (int)value; return MF_OK; }
+    if (!strcmp(name, "fit_prefix")) { ctx->fit_prefix = value != 0; return MF_OK; }
     if (!strcmp(name, "fit_order")) { ctx->fit_order = value != 0; return MF_OK; }
     if (!strcmp(name, "max_rounds")) { if (value < 1) return MF_ERR_ARG; ctx->max_rounds = value; return MF_OK; }
     return MF_ERR_ARG;

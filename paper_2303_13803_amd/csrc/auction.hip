@@ -1167,11 +1167,12 @@ __global__ __launch_bounds__(256) void max_weight_kernel(const int32_t *__restri
 __global__ __launch_bounds__(BID_THREADS) void duals_kernel(
     const int32_t *__restrict__ W, int64_t ldw, int n, int m, const double *__restrict__ price,
     const int *__restrict__ row2col, double Kd, int32_t *__restrict__ out_row2col,
-    int64_t *__restrict__ u, int64_t *__restrict__ v)
+    int64_t *__restrict__ u, int64_t *__restrict__ v, const int *__restrict__ line_len)
 {
     __shared__ Top2 red[BID_THREADS / 64];
     for (int i = blockIdx.x; i < n; i += gridDim.x) {
-        const Top2 t = block_scan<BID_THREADS>(W + (size_t)i * ldw, price, m, Kd, false, red, 0, 0);
+        const int len = line_len ? min(line_len[i], m) : m;
+        const Top2 t = block_scan<BID_THREADS>(W + (size_t)i * ldw, price, len, Kd, false, red, 0, 0);
         if (threadIdx.x == 0) {
             u[i] = (int64_t)fmax(t.b1, 0.0);
             out_row2col[i] = row2col[i];
@@ -1255,11 +1256,27 @@ __global__ void fill_int_kernel(int *p, int count, int value)
     if (i < count) p[i] = value;
 }
 
-// to[from[i]] = i for every i with a partner; `to` was filled with -1 before.
-__global__ void invert_map_kernel(const int32_t *__restrict__ from, int count, int32_t *to)
+// Results of a solve that ran in other coordinates (rows and columns in memory order, and/or
+// the transposed problem) handed to the caller: internal row k is the caller's row_ids[k]
+// (k itself without a map), likewise columns; with `flipped` the internal rows are the caller's
+// columns.  d_row2col was filled with -1 before.
+__global__ void map_back_kernel(int rn, int rm, const int32_t *__restrict__ r2c, const int64_t *__restrict__ u,
+                                const int64_t *__restrict__ v, const int32_t *__restrict__ row_ids,
+                                const int32_t *__restrict__ col_ids, int flipped, int32_t *d_row2col,
+                                int64_t *d_u, int64_t *d_v)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count && from[i] >= 0) to[from[i]] = i;
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < rn) {
+        const int rid = row_ids ? row_ids[k] : k;
+        const int c = r2c[k];
+        const int cid = c < 0 ? -1 : (col_ids ? col_ids[c] : c);
+        if (!flipped) { d_row2col[rid] = cid; d_u[rid] = u[k]; }
+        else { d_v[rid] = u[k]; if (cid >= 0) d_row2col[cid] = rid; }
+    }
+    if (k < rm) {
+        const int cid = col_ids ? col_ids[k] : k;
+        if (!flipped) d_v[cid] = v[k]; else d_u[cid] = v[k];
+    }
 }
 
 __global__ void init_cert_kernel(mf_cert_out *out)
@@ -1445,27 +1462,49 @@ int mf_run_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ld
 // only how much work the phases have to do.
 int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
                   int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res,
-                  bool warm, const int32_t *d_reset_cols, int n_reset_cols)
+                  bool warm, const int32_t *d_reset_cols, int n_reset_cols, bool may_use_staged)
 {
-    // The side with fewer lines bids first ("rows" below); with more online than
-    // offline workloads the roles of the matrix and its transposed copy swap and
-    // the results are mapped back at the end.
+    // When the matrix was just scored here, the context still holds it with rows and columns in
+    // order of memory fraction, where the pairs that can share are a prefix of every row and of
+    // every column: the auction then runs on that copy and reads only the prefixes; the
+    // certificate below is still evaluated on the caller's matrix, in the caller's coordinates.
+    const bool candidate = may_use_staged && ctx->fit_prefix && ctx->staged_n == n && ctx->staged_m == m;
     const bool flip = n > m;
-    warm = warm && !flip && ctx->warm_n == n && ctx->warm_m == m;
+    warm = warm && !flip && !candidate && ctx->warm_n == n && ctx->warm_m == m;
     ctx->warm_n = ctx->warm_m = 0;
     const int64_t ldt = ((int64_t)n + 3) & ~3ll;
     const int rn = flip ? m : n, rm = flip ? n : m;
-    const int32_t *A = flip ? ctx->wt : d_W;
-    const int64_t lda = flip ? ldt : ldw;
-    const int32_t *At = flip ? d_W : ctx->wt;
-    const int64_t ldat = flip ? ldw : ldt;
     const long long K = (long long)rn + 1;
     const double Kd = (double)K;
     const int nm = rm;
 
     MF_HIP(hipEventRecord(ctx->ev[3], ctx->stream));
-    hipLaunchKernelGGL(init_solver_kernel, dim3((nm + 4 + 255) / 256), dim3(256), 0, ctx->stream, rn, rm,
-                       ctx->price, ctx->profit, ctx->stats, warm ? 1 : 0);
+    {
+        // the largest weight sets the first epsilon
+        const int chunks = (m + 4095) / 4096 < 4 ? (m + 4095) / 4096 : 4;
+        hipLaunchKernelGGL(init_solver_kernel, dim3((nm + 4 + 255) / 256), dim3(256), 0, ctx->stream, rn, rm,
+                           ctx->price, ctx->profit, ctx->stats, warm ? 1 : 0);
+        hipLaunchKernelGGL(max_weight_kernel, dim3(chunks, n < 1024 ? n : 1024), dim3(256), 0, ctx->stream, d_W, n, m,
+                           ldw, ctx->stats);
+        MF_HIP(hipGetLastError());
+    }
+    *ctx->h_feasible_pairs = ~0ull;
+    if (candidate)
+        MF_HIP(hipMemcpyAsync(ctx->h_feasible_pairs, ctx->feasible_pairs, sizeof(unsigned long long),
+                              hipMemcpyDeviceToHost, ctx->stream));
+    MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
+    MF_HIP(hipStreamSynchronize(ctx->stream));
+    const long long cmax = K * (long long)ctx->h_stats->max_weight;
+    if (cmax >= MF_MAX_DUAL) return MF_ERR_RANGE;
+    // ... worth it when most of the matrix can be left unread
+    const bool staged = candidate && (double)*ctx->h_feasible_pairs * 100.0 < (double)ctx->fit_prefix_below * (double)n * (double)m;
+    const int32_t *M = staged ? ctx->staged : d_W;
+    const int64_t ldm = staged ? (((int64_t)m + 3) & ~3ll) : ldw;
+    const int *len_rows = staged ? ctx->fit_len_on : nullptr, *len_cols = staged ? ctx->fit_len_off : nullptr;
+    const int32_t *A = flip ? ctx->wt : M;
+    const int64_t lda = flip ? ldt : ldm;
+    const int32_t *At = flip ? M : ctx->wt;
+    const int64_t ldat = flip ? ldm : ldt;
     if (warm && n_reset_cols > 0)
         hipLaunchKernelGGL(zero_listed_kernel, dim3((n_reset_cols + 255) / 256), dim3(256), 0, ctx->stream,
                            ctx->price, d_reset_cols, n_reset_cols, m);
@@ -1475,29 +1514,21 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     bool have_transpose = false;
     auto make_transpose = [&]() {
         hipLaunchKernelGGL(transpose_kernel, dim3((m + 63) / 64, (n + 63) / 64), dim3(256), 0, ctx->stream,
-                           d_W, n, m, ldw, ctx->wt, ldt, ctx->stats);
+                           M, n, m, ldm, ctx->wt, ldt, ctx->stats);
         have_transpose = true;
     };
     if (flip) make_transpose();
-    else {
-        const int chunks = (m + 4095) / 4096 < 4 ? (m + 4095) / 4096 : 4;
-        hipLaunchKernelGGL(max_weight_kernel, dim3(chunks, n < 1024 ? n : 1024), dim3(256), 0, ctx->stream, d_W, n, m,
-                           ldw, ctx->stats);
-    }
     MF_HIP(hipGetLastError());
     MF_HIP(hipEventRecord(ctx->ev[4], ctx->stream));
-    MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
     MF_HIP(hipStreamSynchronize(ctx->stream));
     {
         float ms = 0.0f;
         MF_HIP(hipEventElapsedTime(&ms, ctx->ev[3], ctx->ev[4]));
         ctx->timings[T_TRANSPOSE] = ms;
     }
-    const long long cmax = K * (long long)ctx->h_stats->max_weight;
-    if (cmax >= MF_MAX_DUAL) return MF_ERR_RANGE;
 
-    SideArgs fwd{A, (long long)lda, rm, ctx->price, ctx->colword, 0.0, Kd};
-    SideArgs rev{At, (long long)ldat, rn, ctx->profit, ctx->roword, 0.0, Kd};
+    SideArgs fwd{A, (long long)lda, rm, ctx->price, ctx->colword, 0.0, Kd, flip ? len_cols : len_rows};
+    SideArgs rev{At, (long long)ldat, rn, ctx->profit, ctx->roword, 0.0, Kd, flip ? len_rows : len_cols};
 
     long long eps = cmax / ctx->theta;
     if (warm && ctx->warm_eps_units * K < eps) eps = ctx->warm_eps_units * K;
@@ -1538,17 +1569,20 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     MF_HIP(hipEventRecord(ctx->ev[4], ctx->stream));
     {
         const int grid = rn < MAX_GRID ? rn : MAX_GRID;
-        if (!flip) {
+        if (!flip && !staged) {
             hipLaunchKernelGGL(duals_kernel, dim3(grid), dim3(BID_THREADS), 0, ctx->stream, A, lda, rn, rm,
-                               ctx->price, ctx->row2col, Kd, d_row2col, d_u, d_v);
+                               ctx->price, ctx->row2col, Kd, d_row2col, d_u, d_v, fwd.line_len);
         } else {
-            // bidders were the offline workloads: their duals are v, and list[0] takes
-            // their partners until the map is inverted into the caller's row2col
+            // the solve ran in other coordinates: results go through scratch (the searches' label
+            // arrays are idle now) and are mapped to the caller's rows and columns
+            int64_t *u_int = (int64_t *)ctx->path_label, *v_int = (int64_t *)ctx->path_expanded;
             hipLaunchKernelGGL(duals_kernel, dim3(grid), dim3(BID_THREADS), 0, ctx->stream, A, lda, rn, rm,
-                               ctx->price, ctx->row2col, Kd, ctx->list[0], d_v, d_u);
+                               ctx->price, ctx->row2col, Kd, ctx->list[0], u_int, v_int, fwd.line_len);
             hipLaunchKernelGGL(fill_int_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, d_row2col, n, -1);
-            hipLaunchKernelGGL(invert_map_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream,
-                               ctx->list[0], m, d_row2col);
+            const int32_t *row_ids = staged ? (flip ? ctx->order_off : ctx->order_on) : nullptr;
+            const int32_t *col_ids = staged ? (flip ? ctx->order_on : ctx->order_off) : nullptr;
+            hipLaunchKernelGGL(map_back_kernel, dim3((nm + 255) / 256), dim3(256), 0, ctx->stream, rn, rm, ctx->list[0],
+                               u_int, v_int, row_ids, col_ids, flip ? 1 : 0, d_row2col, d_u, d_v);
         }
         MF_HIP(hipGetLastError());
     }
@@ -1577,6 +1611,6 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     h_res->phases = phases;
     h_res->ms_solve = ms_solve;
     h_res->ms_certify = ms_duals + ms_cert;
-    if (h_res->cert_ok) { ctx->warm_n = n; ctx->warm_m = m; }      // these prices may seed the next solve
+    if (h_res->cert_ok && !staged) { ctx->warm_n = n; ctx->warm_m = m; }      // these prices may seed the next solve
     return h_res->cert_ok ? MF_OK : MF_ERR_CERT;
 }

@@ -61,10 +61,17 @@ struct mf_ctx {
     float *mem_on, *mem_off;        // [max_n], [max_m]
     float *sm_on, *sm_off;          // SM activity / SM demand features (pair-dependent SM input)
     int32_t *order_on, *order_off;  // workloads by ascending memory fraction (online: by type first)
-    int32_t *rank_off;              // position of each offline workload in order_off
+    int32_t *rank_on, *rank_off;    // position of each workload in its order
+    float *mem_on_sorted, *mem_off_sorted;
+    int32_t *staged;                // [max_n][pad4(max_m)] the last scored matrix with rows and columns in memory order
+    int32_t *fit_len_on, *fit_len_off;   // per staged row / column: how many entries from the start can share
+    unsigned long long *feasible_pairs, *h_feasible_pairs;    // how many pairs of the staged matrix can share (device, pinned)
+    int fit_prefix_below;           // percent of pairs that can share below which the solve uses the staged matrix
+    int staged_n, staged_m;         // shape of the staged matrix the solver may use (0: none)
     int32_t *type_segment;          // [MF_MAX_TYPES + 1] first position of each type in order_on
     unsigned long long *pairs_evaluated, *h_pairs_evaluated;   // pairs the last scoring pass ran the MLP on (device, pinned)
     double pairs_total;             // ... out of this many
+    bool fit_prefix;                // solve on the staged matrix, reading only the prefixes that can share
     bool fit_order;                 // score in memory order and skip pairs that cannot fit
     // solver scratch
     int32_t *wt;                    // transposed weights [max_m][ldt]
@@ -119,7 +126,7 @@ int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, 
 // auction.hip
 int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
                   int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res,
-                  bool warm, const int32_t *d_reset_cols, int n_reset_cols);
+                  bool warm, const int32_t *d_reset_cols, int n_reset_cols, bool may_use_staged);
 int mf_run_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
                        const int32_t *d_row2col, const int64_t *d_u, const int64_t *d_v,
                        int64_t K, mf_result *h_res);

@@ -98,28 +98,73 @@ __global__ void order_from_rank_kernel(const int32_t *__restrict__ rank, int cou
     if (i < count) order[rank[i]] = i;
 }
 
-// The memory-ordered pass leaves row i of the scores in `sorted` with its columns in memory
-// order (whole-line stores; entries of pairs it skipped were never written).  This puts them in
-// place: W[i][j] = sorted[i][rank[j]], or MF_INFEASIBLE where the memory rule (paper: Section
-// "Implementation", the memory quota) says the pair cannot share - the rule alone decides, so
-// unwritten entries are never used.  A row of `sorted` is read back in scattered 4-byte pieces,
-// but every piece of it is used by the same workgroup while it sits in the caches.
-__global__ __launch_bounds__(256) void place_columns_kernel(const int32_t *__restrict__ sorted, int64_t lds,
-                                                            const int32_t *__restrict__ rank,
-                                                            const float *__restrict__ mem_on,
-                                                            const float *__restrict__ mem_off, int n, int m,
-                                                            float mem_limit, int32_t *__restrict__ W, int64_t ldw,
-                                                            int wide_stores)
+// The staged matrix: rows and columns of the weight matrix in order of memory fraction.  Before
+// the pair kernel runs it is filled, in whole lines, with MF_INFEASIBLE where the memory rule
+// (paper: Section "Implementation", the memory quota; one float32 addition) says the pair cannot
+// share and 0 elsewhere, so that what the kernel skips is already marked.
+__global__ __launch_bounds__(256) void stage_marks_kernel(const float *__restrict__ mem_on_sorted,
+                                                          const float *__restrict__ mem_off_sorted, int n, int m,
+                                                          float mem_limit, int32_t *__restrict__ S, int64_t lds)
 {
     const int i = blockIdx.x;
-    const float mon = mem_on[i];
-    const int32_t *src = sorted + (size_t)i * lds;
+    const float mon = mem_on_sorted[i];
+    int32_t *row = S + (size_t)i * lds;                    // lds is a multiple of four, S 16-byte aligned
+    for (int j = (blockIdx.y * 256 + threadIdx.x) * 4; j < m; j += gridDim.y * 1024) {
+        int32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (j + e < m && mon + mem_off_sorted[j + e] > mem_limit) ? MF_INFEASIBLE : 0;
+        *(int4 *)(row + j) = make_int4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// *total += sum of len[0..count): how many pairs can share at all.
+__global__ void sum_lengths_kernel(const int32_t *__restrict__ len, int count, unsigned long long *total)
+{
+    unsigned long long t = 0;
+    for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < count; k += gridDim.x * blockDim.x) t += (unsigned)len[k];
+    for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off);
+    if ((threadIdx.x & 63) == 0 && t) atomicAdd(total, t);
+}
+
+__global__ void gather_by_order_kernel(const float *__restrict__ value, const int32_t *__restrict__ order, int count,
+                                       float *__restrict__ out)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < count) out[k] = value[order[k]];
+}
+
+// In memory order the pairs that can share form, in every row, a prefix of the columns (and in
+// every column a prefix of the rows): len[k] = how many entries of `other` (ascending) fit next
+// to mine[k].  A binary search on the same float32 rule the marks were written with.
+__global__ void fit_prefix_kernel(const float *__restrict__ mine, int count, const float *__restrict__ other,
+                                  int other_count, float mem_limit, int32_t *__restrict__ len)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= count) return;
+    const float a = mine[k];
+    int lo = 0, hi = other_count;                          // first position that does not fit
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a + other[mid] > mem_limit) hi = mid; else lo = mid + 1;
+    }
+    len[k] = lo;
+}
+
+// Puts the staged scores in place: W[i][j] = S[rank_on[i]][rank_off[j]].  General form: a row of
+// S is read back in scattered 4-byte pieces, every piece of it by the same workgroup while it
+// sits in the caches.
+__global__ __launch_bounds__(256) void place_kernel(const int32_t *__restrict__ S, int64_t lds,
+                                                    const int32_t *__restrict__ rank_on,
+                                                    const int32_t *__restrict__ rank_off, int n, int m,
+                                                    int32_t *__restrict__ W, int64_t ldw, int wide_stores)
+{
+    const int i = blockIdx.x;
+    const int32_t *src = S + (size_t)rank_on[i] * lds;
     int32_t *row = W + (size_t)i * ldw;
     for (int j = (blockIdx.y * 256 + threadIdx.x) * 4; j < m; j += gridDim.y * 1024) {
         int32_t w[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            w[e] = j + e < m ? ((mon + mem_off[j + e] > mem_limit) ? MF_INFEASIBLE : src[rank[j + e]]) : 0;
+        for (int e = 0; e < 4; ++e) w[e] = j + e < m ? src[rank_off[j + e]] : 0;
         if (wide_stores && j + 3 < m) {
             *(int4 *)(row + j) = make_int4(w[0], w[1], w[2], w[3]);
         } else {
@@ -130,49 +175,30 @@ __global__ __launch_bounds__(256) void place_columns_kernel(const int32_t *__res
     }
 }
 
-// The same through LDS, for rows of up to PLACE_MAX_COLS entries (one chunk; measured faster than
-// the kernel above there, slower beyond): a workgroup per row loads the row's memory-ordered
-// scores in whole lines, picks each output's entry out of LDS, and stores the row in whole lines
-// - no scattered access reaches the caches.
-constexpr int PLACE_THREADS = 1024, PLACE_CHUNK = 32768, PLACE_GROUPS = 8;
+// The same through LDS, for rows of up to PLACE_MAX_COLS entries (measured faster than the
+// kernel above there, slower beyond): a workgroup per row loads the staged row in whole lines,
+// picks each output's entry out of LDS, and stores the row in whole lines - no scattered access
+// reaches the caches.
+constexpr int PLACE_THREADS = 1024, PLACE_GROUPS = 8;
 constexpr int PLACE_MAX_COLS = PLACE_THREADS * PLACE_GROUPS * 4;
 
-__global__ __launch_bounds__(PLACE_THREADS) void place_columns_lds_kernel(
-    const int32_t *__restrict__ sorted, int64_t lds, const int32_t *__restrict__ rank,
-    const float *__restrict__ mem_on, const float *__restrict__ mem_off, int n, int m, float mem_limit,
-    int32_t *__restrict__ W, int64_t ldw, int wide_stores)
+__global__ __launch_bounds__(PLACE_THREADS) void place_lds_kernel(
+    const int32_t *__restrict__ S, int64_t lds, const int32_t *__restrict__ rank_on,
+    const int32_t *__restrict__ rank_off, int n, int m, int32_t *__restrict__ W, int64_t ldw, int wide_stores)
 {
     extern __shared__ int32_t staged[];
     const int i = blockIdx.x, tid = threadIdx.x;
-    const float mon = mem_on[i];
-    const int32_t *src = sorted + (size_t)i * lds;       // lds is a multiple of four, the buffer 16-byte aligned
+    const int32_t *src = S + (size_t)rank_on[i] * lds;
     int32_t *row = W + (size_t)i * ldw;
-    int32_t val[PLACE_GROUPS][4];
-    for (int c0 = 0; c0 < m; c0 += PLACE_CHUNK) {
-        const int cn = min(PLACE_CHUNK, m - c0);
-        __syncthreads();
-        for (int t = tid * 4; t < cn; t += PLACE_THREADS * 4) *(int4 *)(staged + t) = *(const int4 *)(src + c0 + t);
-        __syncthreads();
-#pragma unroll
-        for (int g = 0; g < PLACE_GROUPS; ++g) {
-            const int j = (g * PLACE_THREADS + tid) * 4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (j + e < m) {
-                    const int at = rank[j + e] - c0;
-                    if (at >= 0 && at < cn) val[g][e] = staged[at];
-                }
-            }
-        }
-    }
+    for (int t = tid * 4; t < m; t += PLACE_THREADS * 4) *(int4 *)(staged + t) = *(const int4 *)(src + t);
+    __syncthreads();
 #pragma unroll
     for (int g = 0; g < PLACE_GROUPS; ++g) {
         const int j = (g * PLACE_THREADS + tid) * 4;
         if (j >= m) break;
         int32_t w[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            w[e] = (j + e < m && mon + mem_off[j + e] > mem_limit) ? MF_INFEASIBLE : val[g][e];
+        for (int e = 0; e < 4; ++e) w[e] = j + e < m ? staged[rank_off[j + e]] : 0;
         if (wide_stores && j + 3 < m) {
             *(int4 *)(row + j) = make_int4(w[0], w[1], w[2], w[3]);
         } else {
@@ -239,8 +265,10 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hh = lane >> 5, nn = lane & 31;
+    int staged_row0 = 0;                    // where the row map's entry 0 sits in the staged matrix
     if (segment) {                          // only entries [segment[0], segment[1]) of the row map
         row_map += segment[0];
+        staged_row0 = segment[0];
         n = segment[1] - segment[0];
     }
     // consecutive workgroups (which the hardware deals out to the eight XCDs in turn) share one
@@ -387,13 +415,12 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
                 float qv = rintf(sg * scale);
                 qv = fminf(fmaxf(qv, 0.0f), scale);
                 int32_t w = (int32_t)qv;
+                const float memsum = mon_lds[r + x] + moff;
+                if (memsum > mem_limit) w = MF_INFEASIBLE;
                 if (by_memory) {
-                    // row i of the staging matrix, columns in memory order: one whole line per wave;
-                    // the memory rule is applied when the columns are put back in place
-                    W[(size_t)i * ldw + j] = w;
+                    // the staged matrix: rows and columns both in memory order, one whole line per wave
+                    W[(size_t)(staged_row0 + row0 + r + x) * ldw + j] = w;
                 } else {
-                    const float memsum = mon_lds[r + x] + moff;
-                    if (memsum > mem_limit) w = MF_INFEASIBLE;
                     W[(size_t)i * ldw + jc] = w;
                     if (sigma) sigma[(size_t)i * m + jc] = sg;
                 }
@@ -410,7 +437,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
         if (pair_of_rows) { score_rows(std::integral_constant<int, 2>{}, r); r += 2; }
         else { score_rows(std::integral_constant<int, 1>{}, r); r += 1; }
     }
-    // rows the loop left early get their "cannot fit" marks when the columns are put back in place
+    // rows the loop left early keep the "cannot fit" marks the staged matrix was filled with
     if (evaluated && lane == 0 && r > 0) atomicAdd(evaluated, (unsigned long long)r * (unsigned)min(32, m - j0));
 }
 
@@ -532,14 +559,37 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
     // corner of the tile grid and the kernel leaves them out.  Results land at the same places.
     const bool by_memory = ctx->fit_order && !d_sigma;
     hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->pairs_evaluated);
-    if (by_memory || typed) order_by_memory(ctx, ctx->mem_on, d_type, n, ctx->order_on, ctx->list[0]);
-    if (by_memory) order_by_memory(ctx, ctx->mem_off, nullptr, m, ctx->order_off, ctx->rank_off);
+    if (by_memory || typed) order_by_memory(ctx, ctx->mem_on, d_type, n, ctx->order_on, ctx->rank_on);
+    const int64_t lds = ((int64_t)m + 3) & ~3ll;
+    ctx->staged_n = ctx->staged_m = 0;
+    if (by_memory) {
+        order_by_memory(ctx, ctx->mem_off, nullptr, m, ctx->order_off, ctx->rank_off);
+        hipLaunchKernelGGL(gather_by_order_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, ctx->mem_on,
+                           ctx->order_on, n, ctx->mem_on_sorted);
+        hipLaunchKernelGGL(gather_by_order_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, ctx->mem_off,
+                           ctx->order_off, m, ctx->mem_off_sorted);
+        const int chunks = (m + 4095) / 4096 < 16 ? (m + 4095) / 4096 : 16;
+        hipLaunchKernelGGL(stage_marks_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->mem_on_sorted,
+                           ctx->mem_off_sorted, n, m, p0->mem_limit, ctx->staged, lds);
+        if (!typed) {
+            // one predictor: rows are in memory order too, so feasibility is a prefix both ways
+            hipLaunchKernelGGL(fit_prefix_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, ctx->mem_on_sorted,
+                               n, ctx->mem_off_sorted, m, p0->mem_limit, ctx->fit_len_on);
+            hipLaunchKernelGGL(fit_prefix_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, ctx->mem_off_sorted,
+                               m, ctx->mem_on_sorted, n, p0->mem_limit, ctx->fit_len_off);
+            hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->feasible_pairs);
+            hipLaunchKernelGGL(sum_lengths_kernel, dim3(64), dim3(256), 0, ctx->stream, ctx->fit_len_on, n,
+                               ctx->feasible_pairs);
+            ctx->staged_n = n;
+            ctx->staged_m = m;
+        }
+    }
     MF_HIP(hipGetLastError());
     ctx->pairs_total = (double)n * (double)m;
     const int32_t *rmap = (by_memory || typed) ? ctx->order_on : nullptr, *cmap = by_memory ? ctx->order_off : nullptr;
-    // in memory order the scores go to a staging matrix (the solver's transposed-copy buffer, idle now)
-    int32_t *out = by_memory ? ctx->wt : d_W;
-    const int64_t ldo = by_memory ? (((int64_t)m + 3) & ~3ll) : ldw;
+    // in memory order the scores go to the staged matrix
+    int32_t *out = by_memory ? ctx->staged : d_W;
+    const int64_t ldo = by_memory ? lds : ldw;
     for (int t = 0; t < n_types; ++t) {
         const mf_predictor *p = &preds[t];
         const int H = p->H;
@@ -562,18 +612,16 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
         const int wide = ((uintptr_t)d_W & 15u) == 0 && (ldw & 3) == 0;
         if (m <= PLACE_MAX_COLS) {
             static bool configured = false;
-            const size_t bytes = sizeof(int32_t) * (size_t)(m < PLACE_CHUNK ? ((m + 3) & ~3) : PLACE_CHUNK);
             if (!configured) {
-                MF_HIP(hipFuncSetAttribute((const void *)place_columns_lds_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)(sizeof(int32_t) * PLACE_CHUNK)));
+                MF_HIP(hipFuncSetAttribute((const void *)place_lds_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)(sizeof(int32_t) * PLACE_MAX_COLS)));
                 configured = true;
             }
-            hipLaunchKernelGGL(place_columns_lds_kernel, dim3(n), dim3(PLACE_THREADS), bytes, ctx->stream, ctx->wt, ldo,
-                               ctx->rank_off, ctx->mem_on, ctx->mem_off, n, m, p0->mem_limit, d_W, ldw, wide);
+            hipLaunchKernelGGL(place_lds_kernel, dim3(n), dim3(PLACE_THREADS), sizeof(int32_t) * (size_t)lds, ctx->stream,
+                               ctx->staged, lds, ctx->rank_on, ctx->rank_off, n, m, d_W, ldw, wide);
         } else {
-            hipLaunchKernelGGL(place_columns_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->wt, ldo,
-                               ctx->rank_off, ctx->mem_on, ctx->mem_off, n, m, p0->mem_limit, d_W, ldw, wide);
+            hipLaunchKernelGGL(place_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->staged, lds,
+                               ctx->rank_on, ctx->rank_off, n, m, d_W, ldw, wide);
         }
         MF_HIP(hipGetLastError());
     }
@@ -601,6 +649,7 @@ int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int
                       const int32_t *d_cols, int n_cols)
 {
     const int H = p->H, F = p->F;
+    ctx->staged_n = ctx->staged_m = 0;       // the staged copy no longer matches the matrix
     // the lists index device arrays: refuse anything out of range before a kernel trusts it
     hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->colmark);
     if (n_rows > 0)

@@ -228,12 +228,18 @@ def test_argument_errors(mm):
     ctx.close()
 
 
+@pytest.mark.parametrize("prefix_below", [50, 101, 0])
 @pytest.mark.parametrize("cfg,n,m,exact", [("C1", None, None, True), ("C2", None, None, True),
-                                           ("C3", 512, 1024, True), ("C5", 400, 800, True)])
-def test_schedule_round(mm, orc, cfg, n, m, exact):
+                                           ("C3", 512, 1024, True), ("C5", 400, 800, True),
+                                           ("C5", 900, 350, True), ("C4", 300, 301, True)])
+def test_schedule_round(mm, orc, cfg, n, m, exact, prefix_below):
+    """prefix_below: share of pairs that can share GPU memory below which the matching runs on the
+    context's memory-ordered copy of the matrix and reads only the feasible prefix of each line
+    (101: always, 0: never, 50: the default); results come back in the caller's coordinates."""
     r = synth.scheduling_round(cfg, 1, n=n, m=m)
     n, m, S = r["n"], r["m"], r["cfg"].scale
     ctx = mm.Context(n, m)
+    ctx.set_option("fit_prefix_below", prefix_below)
     pred = ctx.predictor(dev_params(r["params"]), S)
     W = empty_matrix(n, m)
     r2c = torch.empty(n, dtype=torch.int32, device="cuda")
@@ -246,6 +252,6 @@ def test_schedule_round(mm, orc, cfg, n, m, exact):
     ok = Wc != INF
     assert np.abs(Wg[ok].astype(np.int64) - Wc[ok]).max() <= weight_tolerance(S)
     # the matching is optimal for the matrix the GPU scored: bit-exact total, host-verified duals
-    exact_total = orc.max_weight_matching(Wg)[0] if exact else None
+    exact_total = orc.max_weight_matching(Wg if n <= m else np.ascontiguousarray(Wg.T))[0] if exact else None
     _verify(orc, Wg, res, r2c.cpu().numpy(), u.cpu().numpy(), v.cpu().numpy(), exact_total)
     ctx.close()
