@@ -1389,26 +1389,14 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
             hipLaunchKernelGGL(team_begin_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->stats,
                                (TeamCtl *)ctx->team_ctl, ring);
             const dim3 grid(teams * size);
-            if (ctx->team_threads == 64)
-                hipLaunchKernelGGL(team_kernel<64>, grid, dim3(64), 0, ctx->stream, s, ctx->list[ring & 1],
-                                   ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   team_cap, size);
-            else if (ctx->team_threads == 128)
-                hipLaunchKernelGGL(team_kernel<128>, grid, dim3(128), 0, ctx->stream, s, ctx->list[ring & 1],
-                                   ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   team_cap, size);
-            else if (ctx->team_threads == 256)
-                hipLaunchKernelGGL(team_kernel<256>, grid, dim3(256), 0, ctx->stream, s, ctx->list[ring & 1],
-                                   ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   team_cap, size);
-            else if (ctx->team_threads == 512)
-                hipLaunchKernelGGL(team_kernel<512>, grid, dim3(512), 0, ctx->stream, s, ctx->list[ring & 1],
-                                   ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   team_cap, size);
-            else
-                hipLaunchKernelGGL(team_kernel<1024>, grid, dim3(1024), 0, ctx->stream, s, ctx->list[ring & 1],
-                                   ctx->list[(ring + 1) & 1], ctx->stats, (TeamCtl *)ctx->team_ctl, ring,
-                                   team_cap, size);
+            using TeamKernel = void (*)(SideArgs, const int *, int *, mf_device_stats *, TeamCtl *, int, long long, int);
+            const int threads = ctx->team_threads;
+            const TeamKernel kernel = threads == 64 ? team_kernel<64> : threads == 128 ? team_kernel<128>
+                                    : threads == 256 ? team_kernel<256> : threads == 512 ? team_kernel<512>
+                                                                                         : team_kernel<1024>;
+            hipLaunchKernelGGL(kernel, grid, dim3(threads == 64 || threads == 128 || threads == 256 || threads == 512 ? threads : 1024),
+                               0, ctx->stream, s, ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats,
+                               (TeamCtl *)ctx->team_ctl, ring, team_cap, size);
             ++ring;
         }
         MF_HIP(hipGetLastError());
