@@ -213,6 +213,12 @@ __global__ void clear_counter_kernel(unsigned long long *c) { *c = 0ull; }
 
 __global__ void fill_flag_kernel(int *flag) { *flag = 0; }
 
+__global__ void fill_value_kernel(int32_t *p, int count, int value)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = value;
+}
+
 __global__ void fill_zero_kernel(int32_t *p, int count)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -571,18 +577,21 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
         const int chunks = (m + 4095) / 4096 < 16 ? (m + 4095) / 4096 : 16;
         hipLaunchKernelGGL(stage_marks_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->mem_on_sorted,
                            ctx->mem_off_sorted, n, m, p0->mem_limit, ctx->staged, lds);
-        if (!typed) {
-            // one predictor: rows are in memory order too, so feasibility is a prefix both ways
-            hipLaunchKernelGGL(fit_prefix_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, ctx->mem_on_sorted,
-                               n, ctx->mem_off_sorted, m, p0->mem_limit, ctx->fit_len_on);
+        // feasibility is a prefix of every staged row (columns are in memory order) and, when the
+        // rows are in memory order too - one predictor - of every staged column; with several
+        // predictors the rows are ordered by type first and columns are read whole
+        hipLaunchKernelGGL(fit_prefix_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, ctx->mem_on_sorted,
+                           n, ctx->mem_off_sorted, m, p0->mem_limit, ctx->fit_len_on);
+        if (!typed)
             hipLaunchKernelGGL(fit_prefix_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, ctx->mem_off_sorted,
                                m, ctx->mem_on_sorted, n, p0->mem_limit, ctx->fit_len_off);
-            hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->feasible_pairs);
-            hipLaunchKernelGGL(sum_lengths_kernel, dim3(64), dim3(256), 0, ctx->stream, ctx->fit_len_on, n,
-                               ctx->feasible_pairs);
-            ctx->staged_n = n;
-            ctx->staged_m = m;
-        }
+        else
+            hipLaunchKernelGGL(fill_value_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, ctx->fit_len_off, m, n);
+        hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->feasible_pairs);
+        hipLaunchKernelGGL(sum_lengths_kernel, dim3(64), dim3(256), 0, ctx->stream, ctx->fit_len_on, n,
+                           ctx->feasible_pairs);
+        ctx->staged_n = n;
+        ctx->staged_m = m;
     }
     MF_HIP(hipGetLastError());
     ctx->pairs_total = (double)n * (double)m;

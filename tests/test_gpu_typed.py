@@ -95,3 +95,27 @@ def test_typed_round_and_errors(mm, orc):
         ctx.score_pairs_typed([preds[0], other], dev(np.zeros(n, np.int32)), dev(r["x_on"]), dev(r["x_off"]), W)
     assert e.value.code == mm.ERR_ARG
     ctx.close()
+
+
+@pytest.mark.parametrize("prefix_below", [101, 0])
+@pytest.mark.parametrize("cfg,n,m", [("C3", 400, 900), ("C5", 700, 300), ("C5", 1500, 2100)])
+def test_typed_round_on_either_copy_of_the_matrix(mm, orc, cfg, n, m, prefix_below):
+    """The matching may be computed on the memory-ordered copy (rows ordered by type, then memory):
+    whichever copy is used, the optimum, the caller's matrix and the certificate are the same."""
+    r = _case(cfg, 11, n, m, [128, 64, 128])
+    S = r["cfg"].scale
+    ctx = mm.Context(n, m)
+    ctx.set_option("fit_prefix_below", prefix_below)
+    preds = [ctx.predictor(dev_params(p), S) for p in r["plist"]]
+    W = empty_matrix(n, m)
+    r2c = torch.empty(n, dtype=torch.int32, device="cuda")
+    u = torch.empty(n, dtype=torch.int64, device="cuda"); v = torch.empty(m, dtype=torch.int64, device="cuda")
+    res = ctx.schedule_round_typed(preds, dev(r["types"]), dev(r["x_on"]), dev(r["x_off"]), W, r2c, u, v)
+    Wg = W.cpu().numpy()[:, :m]
+    _, Wc = orc.score_pairs_typed(r["x_on"], r["x_off"], r["plist"], r["types"], S)
+    assert ((Wg == INF) == (Wc == INF)).all()
+    assert res.cert_ok == 1
+    assert res.primal == orc.max_weight_matching(Wg if n <= m else np.ascontiguousarray(Wg.T))[0]
+    code, P, D = orc.check_certificate(Wg, r2c.cpu().numpy(), u.cpu().numpy(), v.cpu().numpy(), res.K)
+    assert code == 0 and (P, D) == (res.primal, res.dual)
+    ctx.close()
