@@ -833,7 +833,9 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         unsigned step = 0;
         bool swept = false;                      // the previous step was a pass over all columns
         for (;;) {
-            ++step;
+            // far more steps than a search over sound duals can take: give the bidder back to the
+            // chains (every workgroup counts the same steps, so all leave here together)
+            if (++step > 4u * (unsigned)s.len + 4096u) { alive = false; break; }
             const unsigned c = step % 3u, p = (step + 1u) % 3u, z = (step + 2u) % 3u;
             // frontier of this step: its segments' lengths (the very first holds just the bidder)
             if (tid < 64) {
@@ -1066,6 +1068,29 @@ __global__ void forward_done_cols_kernel(int m, const int32_t *__restrict__ W, i
         roword[r] = pack_word(pi, j + 1);
     } else if (price[j] > 0.0) {
         list[atomicAdd(&stats->cnt[0], 1)] = j;    // an unassigned column that still carries a price must bid
+    }
+}
+
+// A forward side that was stopped early leaves rows that still wanted to bid.  Before the other
+// side runs, each gets the profit that covers all of its pairs at the current prices (its best
+// value, or 0), held by nobody: then pi_i + p_j >= K W_ij - eps holds on every feasible pair
+// again, which the bids and searches of the other side rely on.
+__global__ __launch_bounds__(BID_THREADS) void settle_unplaced_kernel(
+    const int32_t *__restrict__ W, int64_t ldw, int n, int m, const double *__restrict__ price,
+    const int *__restrict__ row2col, double Kd, double *__restrict__ profit, unsigned long long *roword,
+    const int *__restrict__ line_len)
+{
+    __shared__ Top2 red[BID_THREADS / 64];
+    for (int i = blockIdx.x; i < n; i += gridDim.x) {
+        if (row2col[i] >= 0) continue;                               // block-uniform
+        const int len = line_len ? min(line_len[i], m) : m;
+        const Top2 t = block_scan<BID_THREADS>(W + (size_t)i * ldw, price, len, Kd, false, red, 0, 0);
+        if (threadIdx.x == 0) {
+            const double pi = fmax(t.b1, 0.0);
+            profit[i] = pi;
+            roword[i] = pack_word(pi, 0);
+        }
+        __syncthreads();
     }
 }
 
@@ -1323,15 +1348,17 @@ void launch_round(mf_ctx *ctx, const SideArgs &s, int count, int ring)
     }
 }
 
-// Runs one side until nobody is left to bid.  list[0] / cnt[0] hold the first
-// bidders (`count` of them).  Returns MF_OK or an error.
-int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
+// Runs one side until at most `stop_at` bidders are left (0: until nobody is left to bid).
+// list[0] / cnt[0] hold the first bidders (`count` of them).  Returns MF_OK or an error;
+// *left_over is the number of bidders still unplaced.
+int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int stop_at, int *left_over)
 {
     int ring = 0;
     // Short chains are cheapest followed step by step; a chain that is still going after
     // `path_after` steps is ended by shortest-path searches instead.
     long long team_steps = 0;
-    while (count > 0) {
+    *left_over = count;
+    while (count > stop_at) {
         bool timed = false, counted_teams = false;
         const unsigned long long bytes_before = ctx->h_stats->bytes;
         const bool paths_ok = ctx->path_max > 0 && !ctx->path_off && ctx->n_cus > 0;
@@ -1414,6 +1441,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first)
         if (counted_teams) team_steps += (long long)ctx->h_stats->launch_max;     // the longest any leader went
         if (ctx->h_stats->team_abort == 1) ctx->team_off = true;   // a bounded wait ran out: one workgroup per chain from now on
         if (ctx->h_stats->team_abort == 2) ctx->path_off = true;   // ... or no more shortest-path searches
+        *left_over = count;
     }
     return MF_OK;
 }
@@ -1527,8 +1555,23 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         fwd.eps = rev.eps = (double)eps;
         hipLaunchKernelGGL(reset_kernel, dim3((nm + 255) / 256), dim3(256), 0, ctx->stream, rn, rm, ctx->price,
                            ctx->colword, ctx->row2col, ctx->col2row, ctx->list[0], ctx->stats);
-        int rc = run_side(ctx, fwd, rn, true);
+        // A phase at a coarse epsilon only prepares prices for the later ones (each drops the
+        // assignment anyway), so it may end while a few bidders are still unplaced: their long
+        // chains of dependent bids, and the searches that would end them, are then never run at
+        // that epsilon.  The last phase_keep phases run to the end: the first of them settles what
+        // was left open, the last one is what makes the result exact.  (With more columns than
+        // rows the second side still runs: it is what takes the price off unused columns.)
+        int left_over = 0, phases_after = 0;
+        for (long long e = eps; e > 1; ++phases_after) { e /= ctx->theta; if (e < 1) e = 1; }
+        // (never more than one bidder in 64: small problems complete every phase)
+        const int stop_at = phases_after >= ctx->phase_keep ? (ctx->phase_stop < rn / 64 ? ctx->phase_stop : rn / 64) : 0;
+        int rc = run_side(ctx, fwd, rn, true, stop_at, &left_over);
         if (rc != MF_OK) return rc;
+        if (left_over > 0 && rm == rn) {
+            eps /= ctx->theta;
+            if (eps < 1) eps = 1;
+            continue;
+        }
         // who holds what after the forward rounds; unassigned priced columns go to list[0]
         hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats);
         hipLaunchKernelGGL(forward_done_rows_kernel, dim3((rn + 255) / 256), dim3(256), 0, ctx->stream, rn,
@@ -1536,13 +1579,17 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         hipLaunchKernelGGL(forward_done_cols_kernel, dim3((rm + 255) / 256), dim3(256), 0, ctx->stream, rm,
                            A, lda, Kd, ctx->colword, ctx->price, ctx->profit, ctx->roword, ctx->row2col,
                            ctx->col2row, ctx->list[0], ctx->stats);
+        if (left_over > 0)
+            hipLaunchKernelGGL(settle_unplaced_kernel, dim3(rn < MAX_GRID ? rn : MAX_GRID), dim3(BID_THREADS), 0,
+                               ctx->stream, A, lda, rn, rm, ctx->price, ctx->row2col, Kd, ctx->profit, ctx->roword,
+                               fwd.line_len);
         MF_HIP(hipGetLastError());
         MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
         MF_HIP(hipStreamSynchronize(ctx->stream));
         const int rev_count = ctx->h_stats->cnt[0];
         if (rev_count > 0) {
             if (!have_transpose) make_transpose();
-            rc = run_side(ctx, rev, rev_count, false);
+            rc = run_side(ctx, rev, rev_count, false, 0, &left_over);
             if (rc != MF_OK) return rc;
             hipLaunchKernelGGL(reverse_done_cols_kernel, dim3((rm + 255) / 256), dim3(256), 0, ctx->stream, rm,
                                ctx->price, ctx->col2row);

@@ -95,3 +95,22 @@ def test_a_search_that_gives_up_hands_back_to_the_chains(mm, orc, polls):
     res = _solve_and_verify(ctx, orc, W, expect)
     assert res.path_steps > 0
     ctx.close()
+
+
+@pytest.mark.parametrize("options", [{"phase_stop": 0}, {"phase_stop": 8, "phase_keep": 1},
+                                     {"phase_stop": 64, "phase_keep": 2, "path_after": 0},
+                                     {"phase_stop": 1 << 20, "phase_keep": 1},
+                                     {"phase_stop": 3, "phase_keep": 64}])
+def test_phases_that_end_early_leave_the_optimum_alone(mm, orc, options):
+    """Phases at a coarse epsilon may stop with bidders unplaced (they only prepare prices); with
+    more columns than rows the other side then runs from profits that cover the unplaced rows.
+    Whatever the setting - every phase completed, only the last one, as many bidders left over as
+    the library allows - the last phase makes the result exactly optimal."""
+    cases = list(_cases()) + [("one more column than rows", synth.uniform_matrix(48, 300, 301, 2 ** 24, 0.2)),
+                              ("one more row than columns", synth.uniform_matrix(49, 301, 300, 2 ** 24, 0.2))]
+    for name, W in cases:
+        ctx = mm.Context(*W.shape)
+        for k, val in options.items():
+            ctx.set_option(k, val)
+        _solve_and_verify(ctx, orc, W, _optimum(orc, W))
+        ctx.close()
