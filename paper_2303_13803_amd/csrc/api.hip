@@ -96,6 +96,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->tail_max = 1024;
     ctx->phase_stop = 8;
     ctx->phase_keep = 4;
+    ctx->phase_growth = 3;
     ctx->warm_eps_units = 0;
     ctx->warm_reset_cols = true;
     ctx->chain_grid = 256;
@@ -332,6 +333,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!ctx || !name) return MF_ERR_ARG;
     if (!strcmp(name, "theta")) { if (value < 2 || value > 1024) return MF_ERR_ARG; ctx->theta = value; return MF_OK; }
     if (!strcmp(name, "phase_keep")) { if (value < 1 || value > 64) return MF_ERR_ARG; ctx->phase_keep = (int)value; return MF_OK; }
+    if (!strcmp(name, "phase_growth")) { if (value < 1 || value > 64) return MF_ERR_ARG; ctx->phase_growth = (int)value; return MF_OK; }
     if (!strcmp(name, "phase_stop")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->phase_stop = (int)value; return MF_OK; }
     if (!strcmp(name, "tail_max")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->tail_max = (int)value; return MF_OK; }
     if (!strcmp(name, "bulk_shape")) { if (value < 0 || value > 4) return MF_ERR_ARG; ctx->bulk_shape = (int)value; return MF_OK; }

@@ -1563,8 +1563,18 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         // rows the second side still runs: it is what takes the price off unused columns.)
         int left_over = 0, phases_after = 0;
         for (long long e = eps; e > 1; ++phases_after) { e /= ctx->theta; if (e < 1) e = 1; }
-        // (never more than one bidder in 64: small problems complete every phase)
-        const int stop_at = phases_after >= ctx->phase_keep ? (ctx->phase_stop < rn / 64 ? ctx->phase_stop : rn / 64) : 0;
+        // The coarser the phase, the more may be left (phase_growth times more per phase), but
+        // never more than one bidder in 64: small problems complete every phase.
+        long long stop_ll = 0;
+        if (phases_after >= ctx->phase_keep) {
+            stop_ll = ctx->phase_stop;
+            for (int k = ctx->phase_keep; k < phases_after && stop_ll < rn; ++k) stop_ll *= ctx->phase_growth;
+            // the searches are for the phases that have to finish: a coarse one ends at the latest
+            // where they would take over
+            if (ctx->path_max > 0 && !ctx->path_off && stop_ll > 0 && stop_ll < ctx->path_max) stop_ll = ctx->path_max;
+            if (stop_ll > rn / 64) stop_ll = rn / 64;
+        }
+        const int stop_at = (int)stop_ll;
         int rc = run_side(ctx, fwd, rn, true, stop_at, &left_over);
         if (rc != MF_OK) return rc;
         if (left_over > 0 && rm == rn) {

@@ -82,6 +82,7 @@ struct mf_ctx {
     bool warm_reset_cols;           // start replaced columns at price 0 instead of their predecessor's price
     int64_t warm_eps_units;         // first epsilon of a warm-started solve, in weight units
     int phase_stop;                 // unplaced bidders at or below which a phase that only prepares prices ends
+    int phase_growth;               // ... times this for every phase further from the ones that run to the end
     int phase_keep;                 // the last so many phases always run to the end
     int tail_max;                   // bidder count at or below which chains are followed in one kernel
     int bulk_shape;                 // workgroup shape of rounds with many bidders (see launch_round)
