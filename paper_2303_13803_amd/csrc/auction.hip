@@ -65,6 +65,7 @@ struct SideArgs {
     unsigned long long *otherword;      // opposite packed (dual, holder): the authoritative copy
     double eps, Kd;
     const int *line_len;                // optional: every entry of line b at or beyond line_len[b] is infeasible
+    int typical_len;                    // what a scan reads on average (host-side choice of kernels only)
 };
 
 // How much of line b a scan has to read.
@@ -1367,7 +1368,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
         // chains at or below which teams take over from one workgroup per chain
         // (lines short enough for one compute unit to read in a couple of microseconds gain nothing
         // from being split: there the teams wait for the last few chains)
-        int team_from = (ctx->team_wide > ctx->team_max && s.len >= TEAM_WIDE_MIN_LINE) ? ctx->team_wide : ctx->team_max;
+        int team_from = (ctx->team_wide > ctx->team_max && s.typical_len >= TEAM_WIDE_MIN_LINE) ? ctx->team_wide : ctx->team_max;
         if (team_from > TEAM_MAX) team_from = TEAM_MAX;
         if (team_from * 2 > cus) team_from = cus / 2;
         const long long left = ctx->max_rounds - (long long)ctx->h_stats->bids;
@@ -1543,8 +1544,12 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         ctx->timings[T_TRANSPOSE] = ms;
     }
 
-    SideArgs fwd{A, (long long)lda, rm, ctx->price, ctx->colword, 0.0, Kd, flip ? len_cols : len_rows};
-    SideArgs rev{At, (long long)ldat, rn, ctx->profit, ctx->roword, 0.0, Kd, flip ? len_rows : len_cols};
+    // with per-line lengths a scan reads, on average, the pairs that can share divided by the lines
+    const double feasible = staged ? (double)*ctx->h_feasible_pairs : (double)n * (double)m;
+    SideArgs fwd{A, (long long)lda, rm, ctx->price, ctx->colword, 0.0, Kd, flip ? len_cols : len_rows,
+                 (int)(feasible / (double)rn)};
+    SideArgs rev{At, (long long)ldat, rn, ctx->profit, ctx->roword, 0.0, Kd, flip ? len_rows : len_cols,
+                 (int)(feasible / (double)rm)};
 
     long long eps = cmax / ctx->theta;
     if (warm && ctx->warm_eps_units * K < eps) eps = ctx->warm_eps_units * K;
