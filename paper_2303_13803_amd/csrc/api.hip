@@ -111,6 +111,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->fit_prefix_below = 50;
     ctx->path_max = 8;
     ctx->path_width = 1024;
+    ctx->path_grid = 0;
     ctx->path_after = 256;
     ctx->path_spin_limit = 1u << 22;
     {
@@ -348,6 +349,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "path_max")) { if (value < 0 || value > 4096) return MF_ERR_ARG; ctx->path_max = (int)value; return MF_OK; }
     if (!strcmp(name, "path_spin_limit")) { if (value < 0 || value > (1ll << 30)) return MF_ERR_ARG; ctx->path_spin_limit = (unsigned)value; ctx->path_off = false; return MF_OK; }
     if (!strcmp(name, "path_after")) { if (value < 0) return MF_ERR_ARG; ctx->path_after = value; return MF_OK; }
+    if (!strcmp(name, "path_grid")) { if (value < 0 || value > 1024) return MF_ERR_ARG; ctx->path_grid = (int)value; return MF_OK; }
     if (!strcmp(name, "path_width")) { if (value < 1 || value > (1 << 30)) return MF_ERR_ARG; ctx->path_width = (int)value; return MF_OK; }
     if (!strcmp(name, "fit_prefix_below")) { if (value < 0 || value > 101) return MF_ERR_ARG; ctx->fit_prefix_below = (int)value; return MF_OK; }
     if (!strcmp(name, "fit_prefix")) { ctx->fit_prefix = value != 0; return MF_OK; }

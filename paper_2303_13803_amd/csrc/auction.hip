@@ -1388,7 +1388,8 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
                             {ctx->path_frontier[0], ctx->path_frontier[1]}, ctx->path_held};
             hipLaunchKernelGGL(path_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats,
                                (PathCtl *)ctx->path_ctl, ring);
-            hipLaunchKernelGGL(path_kernel, dim3(ctx->n_cus), dim3(PATH_THREADS), 0, ctx->stream, s,
+            const int path_wgs = ctx->path_grid > 0 && ctx->path_grid < ctx->n_cus ? ctx->path_grid : ctx->n_cus;
+            hipLaunchKernelGGL(path_kernel, dim3(path_wgs), dim3(PATH_THREADS), 0, ctx->stream, s,
                                ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, (PathCtl *)ctx->path_ctl,
                                buf, ring, ctx->max_n > ctx->max_m ? ctx->max_n : ctx->max_m,
                                (double)ctx->path_width * s.eps, ctx->path_spin_limit);

@@ -99,6 +99,7 @@ struct mf_ctx {
     int *path_held;
     int path_max;                   // bidders at or below which shortest-path searches place them (0: never)
     long long path_after;           // chain steps per run after which the searches take over
+    int path_grid;                  // workgroups of a search (0: one per compute unit)
     int path_width;                 // label window of one super-step, in epsilons
     unsigned path_spin_limit;       // polls a workgroup waits at a barrier of the search before it gives up
     bool path_off;                  // set after a wait of the search ran out
