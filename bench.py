@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--update-rounds", type=int, default=3,
                     help="also time this many follow-up rounds with --churn of the workloads replaced")
     ap.add_argument("--churn", type=float, default=0.02)
-    ap.add_argument("--other-seeds", default="2,3",
+    ap.add_argument("--other-seeds", default="2,3,4,5,6,7,8",
                     help="also run one warm-up and two rounds on these input seeds and report the median "
                          "round time over all seeds ('' to skip)")
     ap.add_argument("--types", type=int, default=3,
@@ -201,7 +201,8 @@ def main():
         out["seeds"] = {"round_ms": per_seed, "median_round_ms": float(np.median(list(per_seed.values())))}
     if args.update_rounds > 0:
         # follow-up rounds: a share of the online and offline workloads is replaced by fresh draws,
-        # only their rows/columns are re-scored and the matching starts from the previous prices
+        # only their rows/columns are re-scored, then the matching is solved again (from zero prices
+        # unless the warm-start option is set)
         xo, xf = r["x_on"].copy(), r["x_off"].copy()
         times, last = [], None
         for k in range(args.update_rounds):

@@ -226,11 +226,11 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
                             int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
 
 /* Solver knobs: "theta" (epsilon divisor per phase, default 24), "phase_stop" / "phase_keep" /
- * "phase_growth" (a phase that only prepares prices for later ones ends once at most phase_stop
- * bidders are unplaced, default 8; phase_growth times as many, default 3, for every phase
- * before that one; never more than one bidder in 64, and at least "path_max" so that such a
- * phase runs no searches; the last phase_keep phases, default 4 and at least 1, always run until
- * nobody is left to bid, so the result stays exactly optimal; phase_stop 0 completes every
+ * "phase_growth" (either side of a phase that only prepares prices for later ones ends once at
+ * most phase_stop bidders are unplaced, default 8; phase_growth times as many, default 1, for
+ * every phase before that one; never more than one bidder in 64, and at least "path_max" so that
+ * such a phase runs no searches; the last phase_keep phases, default 4 and at least 1, always run
+ * until nobody is left to bid, so the result stays exactly optimal; phase_stop 0 completes every
  * phase), "max_rounds" (limit on
  * evaluated bids, default 4,000,000,000), "tail_max" (bidder count at or below which one
  * kernel follows the remaining eviction chains, default 1024), "chain_grid" (workgroups of

@@ -96,7 +96,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->tail_max = 1024;
     ctx->phase_stop = 8;
     ctx->phase_keep = 4;
-    ctx->phase_growth = 3;
+    ctx->phase_growth = 1;
     ctx->warm_eps_units = 0;
     ctx->warm_reset_cols = true;
     ctx->chain_grid = 256;

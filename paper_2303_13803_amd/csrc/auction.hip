@@ -1562,11 +1562,12 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         hipLaunchKernelGGL(reset_kernel, dim3((nm + 255) / 256), dim3(256), 0, ctx->stream, rn, rm, ctx->price,
                            ctx->colword, ctx->row2col, ctx->col2row, ctx->list[0], ctx->stats);
         // A phase at a coarse epsilon only prepares prices for the later ones (each drops the
-        // assignment anyway), so it may end while a few bidders are still unplaced: their long
-        // chains of dependent bids, and the searches that would end them, are then never run at
-        // that epsilon.  The last phase_keep phases run to the end: the first of them settles what
-        // was left open, the last one is what makes the result exact.  (With more columns than
-        // rows the second side still runs: it is what takes the price off unused columns.)
+        // assignment anyway), so either of its sides may end while a few bidders are still
+        // unplaced: their long chains of dependent bids, and the searches that would end them, are
+        // then never run at that epsilon.  The last phase_keep phases run to the end: the first of
+        // them settles what was left open, the last one is what makes the result exact.  The
+        // second side runs whenever more columns than that are unused and still priced - skipping
+        // it would carry their prices into ever finer phases, where taking them off costs far more.
         int left_over = 0, phases_after = 0;
         for (long long e = eps; e > 1; ++phases_after) { e /= ctx->theta; if (e < 1) e = 1; }
         // The coarser the phase, the more may be left (phase_growth times more per phase), but
@@ -1583,11 +1584,6 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         const int stop_at = (int)stop_ll;
         int rc = run_side(ctx, fwd, rn, true, stop_at, &left_over);
         if (rc != MF_OK) return rc;
-        if (left_over > 0 && rm == rn) {
-            eps /= ctx->theta;
-            if (eps < 1) eps = 1;
-            continue;
-        }
         // who holds what after the forward rounds; unassigned priced columns go to list[0]
         hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats);
         hipLaunchKernelGGL(forward_done_rows_kernel, dim3((rn + 255) / 256), dim3(256), 0, ctx->stream, rn,
@@ -1603,9 +1599,9 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
         MF_HIP(hipStreamSynchronize(ctx->stream));
         const int rev_count = ctx->h_stats->cnt[0];
-        if (rev_count > 0) {
+        if (rev_count > stop_at) {
             if (!have_transpose) make_transpose();
-            rc = run_side(ctx, rev, rev_count, false, 0, &left_over);
+            rc = run_side(ctx, rev, rev_count, false, stop_at, &left_over);
             if (rc != MF_OK) return rc;
             hipLaunchKernelGGL(reverse_done_cols_kernel, dim3((rm + 255) / 256), dim3(256), 0, ctx->stream, rm,
                                ctx->price, ctx->col2row);
