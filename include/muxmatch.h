@@ -227,7 +227,7 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
 
 /* Solver knobs: "theta" (epsilon divisor per phase, default 24), "phase_stop" / "phase_keep" /
  * "phase_growth" (either side of a phase that only prepares prices for later ones ends once at
- * most phase_stop bidders are unplaced, default 8; phase_growth times as many, default 1, for
+ * most phase_stop bidders are unplaced, default 16; phase_growth times as many, default 1, for
  * every phase before that one; never more than one bidder in 64, and at least "path_max" so that
  * such a phase runs no searches; the last phase_keep phases, default 4 and at least 1, always run
  * until nobody is left to bid, so the result stays exactly optimal; phase_stop 0 completes every
@@ -241,7 +241,7 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
  * "path_after" starts to count, default 8), "team_size" / "team_threads" (most workgroups per
  * chain and threads per workgroup there, default 16 / 1024), "path_max" (bidders at or below which each is placed by
  * a device-wide shortest-augmenting-path search once the chains have gone on for "path_after"
- * steps, defaults 8 and 256; path_max 0 turns the searches off), "path_grid" (workgroups of a search, default 0 = one per compute unit), "path_width" (widest label
+ * steps, defaults 16 and 256; path_max 0 turns the searches off), "path_grid" (workgroups of a search, default 0 = one per compute unit), "path_width" (widest label
  * window of a search step, in epsilons, default 1024), "path_spin_limit" (polls a workgroup of a
  * search waits for the others before all give up and the chains take over again, default 2^22;
  * setting it also re-arms the searches after such a fallback), "bulk_shape" (0..4: threads x lines

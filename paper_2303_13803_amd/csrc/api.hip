@@ -94,7 +94,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->theta = 24;
     ctx->max_rounds = 4000000000ll;
     ctx->tail_max = 1024;
-    ctx->phase_stop = 8;
+    ctx->phase_stop = 16;
     ctx->phase_keep = 4;
     ctx->phase_growth = 1;
     ctx->warm_eps_units = 0;
@@ -109,7 +109,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->fit_order = true;
     ctx->fit_prefix = true;
     ctx->fit_prefix_below = 50;
-    ctx->path_max = 8;
+    ctx->path_max = 16;
     ctx->path_width = 1024;
     ctx->path_grid = 0;
     ctx->path_after = 256;
