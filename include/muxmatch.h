@@ -237,8 +237,9 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
  * that kernel, default 256), "team_wide" (chains at or below which teams of workgroups take the
  * chains over, as many workgroups per chain as the device has per chain, default 64; 0: only at
  * "team_max"), "team_regroup" (steps after which such teams stop so that the chains still going
- * get larger teams, default 128), "team_max" (chains at or below which the chains' step budget
- * "path_after" starts to count, default 8), "team_size" / "team_threads" (most workgroups per
+ * get larger teams, default 128), "team_max" (chains at or below which teams take the chains over
+ * when lines are too short for "team_wide" to pay, and below which such a launch is no longer cut
+ * short for regrouping, default 8), "team_size" / "team_threads" (most workgroups per
  * chain and threads per workgroup there, default 16 / 1024), "path_max" (bidders at or below which each is placed by
  * a device-wide shortest-augmenting-path search once the chains have gone on for "path_after"
  * steps, defaults 16 and 256; path_max 0 turns the searches off), "path_grid" (workgroups of a search, default 0 = one per compute unit), "path_width" (widest label
