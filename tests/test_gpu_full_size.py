@@ -87,3 +87,13 @@ def test_cluster_scale_round(mm, orc, cfg, target):
     _check_certificate(orc, Wg, res, r2c, u, v)
     if cfg == "C5":
         assert set(np.unique(Wg[Wg != INF]).tolist()) <= set(range(256))   # few-level weights
+
+
+def test_cluster_scale_round_with_unmatched_workloads(mm, orc):
+    """Seed 7 of the C4 recipe leaves online workloads without a partner at the optimum (too few
+    offline workloads fit beside them): rows rest, columns stay unused but priced, and the second
+    side of the auction runs in every phase, also in those that end early.  Same contract: the
+    host re-checks the proof of optimality."""
+    r, res, Wg, r2c, u, v = _round(mm, "C4", 7)
+    _check_certificate(orc, Wg, res, r2c, u, v)
+    assert res.matched < r["n"], "the instance no longer exercises the second side"

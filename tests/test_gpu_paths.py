@@ -44,6 +44,10 @@ def _cases():
     yield "constant", np.full((200, 300), 77, np.int32)
     yield "single row", synth.uniform_matrix(47, 1, 50, 1000, 0.0)
     yield "nothing feasible", np.full((60, 70), INF, np.int32)
+    W = synth.uniform_matrix(50, 1400, 1400, 2 ** 24, 0.1)          # rows that rest while epsilon is coarse
+    faint = W[:120] != INF
+    W[:120][faint] = W[:120][faint] >> 12
+    yield "square with faint rows", W
 
 
 def _optimum(orc, W):
