@@ -1211,26 +1211,49 @@ __global__ __launch_bounds__(BID_THREADS) void duals_kernel(
 // The proof of optimality, evaluated for arbitrary caller-supplied integers:
 // matching valid, duals non-negative, every feasible pair covered
 // (min reduced cost), primal and dual totals.
+// K32: K fits a signed 32-bit integer, so K*w is one 32 x 32 -> 64-bit multiply-add.
+template <bool K32>
 __global__ __launch_bounds__(BID_THREADS) void certificate_kernel(
     const int32_t *__restrict__ W, int64_t ldw, int n, int m, const int32_t *__restrict__ row2col,
     const int64_t *__restrict__ u, const int64_t *__restrict__ v, long long K, int *colmark,
     mf_cert_out *out)
 {
     __shared__ long long red[BID_THREADS / 64];
+    constexpr int UN = 4;               // independent 16-byte loads in flight per thread
     long long dual_part = 0, primal_part = 0;
     int flags = 0, matched = 0;
     long long min_rc = INT64_MAX;
+    const int k32 = (int)K;
     for (int i = blockIdx.x; i < n; i += gridDim.x) {
         const long long ui = u[i];
         const int32_t *row = W + (size_t)i * ldw;
-        for (int j = threadIdx.x * 4; j < m; j += BID_THREADS * 4) {
-            const int4 w4 = *(const int4 *)(row + j);
-            const int32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
+        for (int j0 = threadIdx.x * 4; j0 < m; j0 += BID_THREADS * 4 * UN) {
+            int4 w4[UN];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (j + e < m && w[e] != MF_INFEASIBLE) {
-                    const long long rc = ui + v[j + e] - K * (long long)w[e];
-                    min_rc = rc < min_rc ? rc : min_rc;
+            for (int q = 0; q < UN; ++q) {
+                const int j = j0 + q * BID_THREADS * 4;
+                w4[q] = j < m ? *(const int4 *)(row + j)
+                              : make_int4(MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE);
+            }
+            // the column duals are loaded whatever the weights turn out to be (index clamped into
+            // the array), so that no load waits for a comparison
+            long long vj[UN][4];
+#pragma unroll
+            for (int q = 0; q < UN; ++q) {
+                const int j = j0 + q * BID_THREADS * 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) vj[q][e] = v[min(j + e, m - 1)];
+            }
+#pragma unroll
+            for (int q = 0; q < UN; ++q) {
+                const int j = j0 + q * BID_THREADS * 4;
+                const int32_t w[4] = {w4[q].x, w4[q].y, w4[q].z, w4[q].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const long long cover = ui + vj[q][e];
+                    const long long rc = K32 ? cover - (long long)w[e] * (long long)k32 : cover - K * (long long)w[e];
+                    const bool counts = j + e < m && w[e] != MF_INFEASIBLE;
+                    min_rc = counts && rc < min_rc ? rc : min_rc;
                 }
             }
         }
@@ -1457,7 +1480,8 @@ int mf_run_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ld
     hipLaunchKernelGGL(init_cert_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->cert);
     hipLaunchKernelGGL(fill_int_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, ctx->colmark, m, 0);
     const int grid = n < MAX_GRID ? n : MAX_GRID;
-    hipLaunchKernelGGL(certificate_kernel, dim3(grid), dim3(BID_THREADS), 0, ctx->stream, d_W, ldw, n, m,
+    hipLaunchKernelGGL(K >= INT32_MIN && K <= INT32_MAX ? certificate_kernel<true> : certificate_kernel<false>,
+                       dim3(grid), dim3(BID_THREADS), 0, ctx->stream, d_W, ldw, n, m,
                        d_row2col, d_u, d_v, (long long)K, ctx->colmark, ctx->cert);
     MF_HIP(hipGetLastError());
     MF_HIP(hipMemcpyAsync(ctx->h_cert, ctx->cert, sizeof(mf_cert_out), hipMemcpyDeviceToHost, ctx->stream));

@@ -210,6 +210,20 @@ def test_certificate_entry_point(mm, orc):
     neg = v.copy(); neg[0] = -1
     assert ctx.check_certificate(Wd, 120, 200, dev(r2c), dev(u), dev(neg), 1).cert_ok == 0
     ctx.close()
+    # a ragged, several-loads-wide matrix; duals scaled by factors within and beyond 32 bits
+    W = synth.uniform_matrix(32, 77, 4131, 2 ** 20, 0.4)
+    total, r2c, u, v = orc.max_weight_matching(W)
+    ctx = mm.Context(77, 4131)
+    Wd = padded_matrix(W)
+    for K in (1, 78, 2 ** 31 - 1, 2 ** 31, 2 ** 33 + 1):
+        got = ctx.check_certificate(Wd, 77, 4131, dev(r2c), dev(u * K), dev(v * K), K)
+        code, P, D = orc.check_certificate(W, r2c, u * K, v * K, K)
+        assert code == 0 and got.cert_ok == 1 and (got.primal, got.dual) == (P, D) == (total, K * total)
+        assert got.min_reduced_cost == 0
+        short = u * K; short[int(np.argmax(u))] -= 3
+        got = ctx.check_certificate(Wd, 77, 4131, dev(r2c), dev(short), dev(v * K), K)
+        assert got.cert_ok == 0 and got.min_reduced_cost == -3
+    ctx.close()
 
 
 def test_argument_errors(mm):
