@@ -159,6 +159,9 @@ def main():
         "score_pairs_per_s": n * m / ((pair_ms + avg["projections_ms"]) * 1e-3),
         "stage_ms": {k: avg[k] for k in ("projections_ms", "pair_scoring_ms", "prepare_ms", "auction_ms",
                                          "duals_ms", "certificate_ms")},
+        # the two whole-matrix passes after the auction, against the 4 n m bytes each has to read
+        "scan_gbps": {"duals": 4.0 * n * m / (avg["duals_ms"] * 1e-3) / 1e9 if avg["duals_ms"] > 0 else None,
+                      "certificate": 4.0 * n * m / (avg["certificate_ms"] * 1e-3) / 1e9 if avg["certificate_ms"] > 0 else None},
         "auction": {"phases": res.phases, "rounds": res.rounds, "bids": res.bids,
                     "bytes_scanned": res.bytes_scanned, "chain_bids": res.chain_bids, "chain_depth": res.chain_depth, "chain_retries": res.chain_retries, "team_bids": res.team_bids, "path_steps": res.path_steps, "path_scans": res.path_scans, "matched": res.matched,
                     "primal": res.primal, "cert_ok": res.cert_ok},
@@ -169,7 +172,9 @@ def main():
         "roofline_bid_scan": {"bound": "hbm", "kernel": "round_kernel (first round of each phase: every row bids)",
                               "achieved": bulk_bytes / (bulk_ms * 1e-3) / 1e9, "peak": HBM_PEAK / 1e9,
                               "unit": "GB/s", "frac": bulk_bytes / (bulk_ms * 1e-3) / HBM_PEAK,
-                              "traffic": MEASURED_TRAFFIC.get((cfg.name, "round_kernel"))},
+                              "traffic": MEASURED_TRAFFIC.get((cfg.name, "round_kernel")),
+                              # every weight byte any scan of the solve read, over the whole auction's time
+                              "whole_solve_gbps": res.bytes_scanned / (avg["auction_ms"] * 1e-3) / 1e9},
         # the chain-following kernels take most of the auction's time but are bound by the latency of
         # dependent steps, not by bandwidth: reported as steps and microseconds per step
         "auction_tail": {"kernels": "chain_kernel + team_kernel (dependent bids), path_kernel (search super-steps)",

@@ -36,7 +36,10 @@ class Predictor(C.Structure):
 
 class Result(C.Structure):
     _fields_ = [("primal", C.c_int64), ("dual", C.c_int64), ("K", C.c_int64),
-                ("min_reduced_cost", C.c_int64), ("rounds", C.c_int64), ("bids", C.c_int64),                 ("bytes_scanned", C.c_int64), ("chain_bids", C.c_int64), ("chain_depth", C.c_int64), ("chain_retries", C.c_int64), ("team_bids", C.c_int64), ("path_steps", C.c_int64), ("path_scans", C.c_int64),
+                ("min_reduced_cost", C.c_int64), ("rounds", C.c_int64), ("bids", C.c_int64),
+                ("bytes_scanned", C.c_int64), ("chain_bids", C.c_int64), ("chain_depth", C.c_int64),
+                ("chain_retries", C.c_int64), ("team_bids", C.c_int64), ("path_steps", C.c_int64),
+                ("path_scans", C.c_int64),
                 ("matched", C.c_int32), ("phases", C.c_int32),
                 ("cert_ok", C.c_int32), ("status", C.c_int32), ("ms_solve", C.c_float),
                 ("ms_certify", C.c_float)]
