@@ -450,7 +450,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
 template <int H, bool PAIR_SM>
 int launch_pair_variant(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
                         float *d_sigma, const int32_t *row_map, const int32_t *col_map, bool by_memory,
-                        const int32_t *segment)
+                        const int32_t *segment, int grid_rows)
 {
     using S = PairShape<H>;
     static bool configured = false;
@@ -459,8 +459,9 @@ int launch_pair_variant(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS_BYTES));
         configured = true;
     }
-    // x padded to a multiple of 8: every XCD then meets the same row tiles for each column tile
-    dim3 grid((((n + S::ROWS - 1) / S::ROWS) + 7) & ~7, (m + PAIR_COLS - 1) / PAIR_COLS);
+    // x covers the rows this launch scores (a segment of the row map, or all n), padded to a
+    // multiple of 8: every XCD then meets the same row tiles for each column tile
+    dim3 grid((((grid_rows + S::ROWS - 1) / S::ROWS) + 7) & ~7, (m + PAIR_COLS - 1) / PAIR_COLS);
     hipLaunchKernelGGL((pair_mlp_kernel<H, PAIR_SM>), grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
                        ctx->proj_on, ctx->proj_off, p->d_W2, p->d_b2, p->d_W3, p->d_b3,
                        ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma, row_map, col_map,
@@ -472,10 +473,11 @@ int launch_pair_variant(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_
 template <int H>
 int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
                 float *d_sigma, const int32_t *row_map, const int32_t *col_map, bool by_memory,
-                const int32_t *segment = nullptr)
+                const int32_t *segment = nullptr, int segment_rows = -1)
 {
-    return p->d_W1sm ? launch_pair_variant<H, true>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment)
-                     : launch_pair_variant<H, false>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment);
+    const int grid_rows = segment_rows >= 0 ? segment_rows : n;
+    return p->d_W1sm ? launch_pair_variant<H, true>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows)
+                     : launch_pair_variant<H, false>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows);
 }
 
 // order[k] = the workload with the k-th smallest (group, key); rank[i] = its position k
@@ -539,6 +541,7 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
     const mf_predictor *p0 = &preds[0];
     const int F = p0->F;
     const bool typed = d_type != nullptr;
+    int32_t type_first[MF_MAX_TYPES + 1] = {0};
     if (typed) {
         hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->colmark);
         hipLaunchKernelGGL(type_segments_kernel, dim3(1), dim3(1024), 0, ctx->stream, d_type, n, n_types,
@@ -546,6 +549,9 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
         MF_HIP(hipGetLastError());
         int bad = 0;
         MF_HIP(hipMemcpyAsync(&bad, ctx->colmark, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+        // the host sizes each type's launch by its number of rows
+        MF_HIP(hipMemcpyAsync(type_first, ctx->type_segment, sizeof(int32_t) * (size_t)(n_types + 1),
+                              hipMemcpyDeviceToHost, ctx->stream));
         MF_HIP(hipStreamSynchronize(ctx->stream));
         if (bad) return MF_ERR_ARG;
     }
@@ -611,8 +617,10 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
         MF_HIP(hipGetLastError());
         if (t == 0) MF_HIP(hipEventRecord(ctx->ev[1], ctx->stream));      // later types' projections count as scoring
         const int32_t *segment = typed ? ctx->type_segment + t : nullptr;
-        int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, out, ldo, d_sigma, rmap, cmap, by_memory, segment)
-                           : launch_pair<128>(ctx, p, n, m, out, ldo, d_sigma, rmap, cmap, by_memory, segment);
+        const int segment_rows = typed ? type_first[t + 1] - type_first[t] : -1;
+        if (segment_rows == 0) continue;                                   // no workload of this type
+        int rc = (H == 64) ? launch_pair<64>(ctx, p, n, m, out, ldo, d_sigma, rmap, cmap, by_memory, segment, segment_rows)
+                           : launch_pair<128>(ctx, p, n, m, out, ldo, d_sigma, rmap, cmap, by_memory, segment, segment_rows);
         if (rc != MF_OK) return rc;
     }
     MF_HIP(hipEventRecord(ctx->ev[2], ctx->stream));
