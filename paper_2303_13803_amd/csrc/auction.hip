@@ -696,7 +696,7 @@ struct alignas(128) PathCtl {
     // when a bidder rests, workgroup 0 may already be writing the next bidder's value while a
     // slower workgroup has yet to read this one
     unsigned long long first_value[2];
-    unsigned int arrive, generation, abort, pad;
+    unsigned int arrive, pad[3];    // whole groups that have arrived at barriers so far | PATH_GAVE_UP
     unsigned long long steps, scans, entries;
     struct alignas(128) { unsigned int arrive; } group[PATH_MAX_GROUPS];
     // Frontier lengths: one counter per segment (a segment collects the pushes of sixteen
@@ -715,10 +715,13 @@ struct PathBuffers {
 };
 
 // Grid-wide barrier in two levels: workgroups arrive at their group's counter, the last of a
-// group at the top counter, the last of all opens the barrier by advancing `generation`.
-// (Hundreds of atomics on one address take turns; sixteen groups of sixteen do not.)  Counters
-// only ever grow: a level is complete whenever its count is a multiple of its size.
+// group at the top counter, and everybody waits until the top counter shows that all groups have
+// arrived for the so-many-th time.  (Hundreds of atomics on one address take turns; sixteen
+// groups of sixteen do not.)  Counters only ever grow.  The top bit of the top counter says that
+// somebody's wait ran out: whoever sees it leaves, so one load tells a waiting workgroup both.
 // Returns false when the wait ran out or another workgroup gave up.
+constexpr unsigned PATH_GAVE_UP = 0x80000000u;
+
 __device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned &generation, unsigned spin_limit)
 {
     __shared__ int s_ok;
@@ -727,23 +730,18 @@ __device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
-        int ok = 1;
         const unsigned groups = (workgroups + PATH_GROUP - 1) / PATH_GROUP;
         const unsigned g = blockIdx.x / PATH_GROUP;
         const unsigned size = min((unsigned)PATH_GROUP, workgroups - g * PATH_GROUP);
-        bool opened = false;
-        if ((atomicAdd(&ctl->group[g].arrive, 1u) + 1u) % size == 0u)
-            if ((atomicAdd(&ctl->arrive, 1u) + 1u) % groups == 0u) { atomicAdd(&ctl->generation, 1u); opened = true; }
-        if (!opened) {
-            unsigned spins = 0;
-            while (load_fresh_u32(&ctl->generation) == generation) {
-                ++spins;
-                if (spins > spin_limit || ((spins & 255u) == 0u && load_fresh_u32(&ctl->abort))) { ok = 0; break; }
-            }
+        const unsigned target = (generation + 1u) * groups;      // whole groups arrived once this barrier is complete
+        unsigned seen = 0u;
+        if ((atomicAdd(&ctl->group[g].arrive, 1u) + 1u) % size == 0u) seen = atomicAdd(&ctl->arrive, 1u) + 1u;
+        unsigned spins = 0;
+        while (!(seen & PATH_GAVE_UP) && seen < target) {
+            if (++spins > spin_limit) { seen = atomicOr(&ctl->arrive, PATH_GAVE_UP) | PATH_GAVE_UP; break; }
+            seen = load_fresh_u32(&ctl->arrive);
         }
-        if (!ok) atomicExch(&ctl->abort, 1u);
-        else if (load_fresh_u32(&ctl->abort)) ok = 0;
-        s_ok = ok;
+        s_ok = (seen & PATH_GAVE_UP) ? 0 : 1;
     }
     ++generation;
     __syncthreads();
@@ -752,7 +750,7 @@ __device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned 
 
 __global__ void path_begin_kernel(mf_device_stats *stats, PathCtl *ctl, int ring)
 {
-    ctl->arrive = 0u; ctl->generation = 0u; ctl->abort = 0u; ctl->steps = 0ull; ctl->scans = 0ull; ctl->entries = 0ull;
+    ctl->arrive = 0u; ctl->steps = 0ull; ctl->scans = 0ull; ctl->entries = 0ull;
     for (int g = 0; g < PATH_MAX_GROUPS; ++g) ctl->group[g].arrive = 0u;
     stats->cnt[(ring + 1) & 3] = 0;
     stats->cnt[(ring + 2) & 3] = 0;
