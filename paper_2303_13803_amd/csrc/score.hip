@@ -104,12 +104,16 @@ __global__ void order_from_rank_kernel(const int32_t *__restrict__ rank, int cou
 // share and 0 elsewhere, so that what the kernel skips is already marked.
 __global__ __launch_bounds__(256) void stage_marks_kernel(const float *__restrict__ mem_on_sorted,
                                                           const float *__restrict__ mem_off_sorted, int n, int m,
-                                                          float mem_limit, int32_t *__restrict__ S, int64_t lds)
+                                                          float mem_limit, int32_t *__restrict__ S, int64_t lds,
+                                                          const int32_t *__restrict__ fit_len)
 {
     const int i = blockIdx.x;
     const float mon = mem_on_sorted[i];
     int32_t *row = S + (size_t)i * lds;                    // lds is a multiple of four, S 16-byte aligned
-    for (int j = (blockIdx.y * 256 + threadIdx.x) * 4; j < m; j += gridDim.y * 1024) {
+    // the pairs before fit_len[i] can share and are all written by the scoring kernel: only the
+    // rest of the line needs marks (from the group of four the boundary falls in)
+    const int first = fit_len[i] & ~3;
+    for (int j = first + (blockIdx.y * 256 + threadIdx.x) * 4; j < m; j += gridDim.y * 1024) {
         int32_t w[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) w[e] = (j + e < m && mon + mem_off_sorted[j + e] > mem_limit) ? MF_INFEASIBLE : 0;
@@ -581,13 +585,13 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
         hipLaunchKernelGGL(gather_by_order_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, ctx->mem_off,
                            ctx->order_off, m, ctx->mem_off_sorted);
         const int chunks = (m + 4095) / 4096 < 16 ? (m + 4095) / 4096 : 16;
-        hipLaunchKernelGGL(stage_marks_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->mem_on_sorted,
-                           ctx->mem_off_sorted, n, m, p0->mem_limit, ctx->staged, lds);
         // feasibility is a prefix of every staged row (columns are in memory order) and, when the
         // rows are in memory order too - one predictor - of every staged column; with several
         // predictors the rows are ordered by type first and columns are read whole
         hipLaunchKernelGGL(fit_prefix_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, ctx->mem_on_sorted,
                            n, ctx->mem_off_sorted, m, p0->mem_limit, ctx->fit_len_on);
+        hipLaunchKernelGGL(stage_marks_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->mem_on_sorted,
+                           ctx->mem_off_sorted, n, m, p0->mem_limit, ctx->staged, lds, ctx->fit_len_on);
         if (!typed)
             hipLaunchKernelGGL(fit_prefix_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, ctx->mem_off_sorted,
                                m, ctx->mem_on_sorted, n, p0->mem_limit, ctx->fit_len_off);
