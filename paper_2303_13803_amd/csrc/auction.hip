@@ -1188,17 +1188,30 @@ __global__ __launch_bounds__(256) void max_weight_kernel(const int32_t *__restri
 
 // Duals handed to the caller: v_j = p_j and the tightest row dual the prices
 // allow, u_i = max(0, max_j (K W_ij - p_j)).
-__global__ __launch_bounds__(BID_THREADS) void duals_kernel(
+// RB rows per workgroup share every load of the prices (8 bytes per entry against 4 for a
+// weight), as in the bulk bidding rounds.
+template <int NT, int RB>
+__global__ __launch_bounds__(NT) void duals_kernel(
     const int32_t *__restrict__ W, int64_t ldw, int n, int m, const double *__restrict__ price,
     const int *__restrict__ row2col, double Kd, int32_t *__restrict__ out_row2col,
     int64_t *__restrict__ u, int64_t *__restrict__ v, const int *__restrict__ line_len)
 {
-    __shared__ Top2 red[BID_THREADS / 64];
-    for (int i = blockIdx.x; i < n; i += gridDim.x) {
-        const int len = line_len ? min(line_len[i], m) : m;
-        const Top2 t = block_scan<BID_THREADS>(W + (size_t)i * ldw, price, len, Kd, false, red, 0, 0);
-        if (threadIdx.x == 0) {
-            u[i] = (int64_t)fmax(t.b1, 0.0);
+    __shared__ Top2 red[RB + RB * (NT / 64)];
+    for (int i0 = blockIdx.x * RB; i0 < n; i0 += gridDim.x * RB) {
+        const int32_t *rows[RB];
+        int salt[RB];
+        int len = 0;                                        // the group scans as far as its longest row
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            const int i = min(i0 + r, n - 1);               // a short last group repeats its last row
+            rows[r] = W + (size_t)i * ldw;
+            salt[r] = 0;
+            len = max(len, line_len ? min(line_len[i], m) : m);
+        }
+        block_scan_rows<NT, RB>(rows, salt, price, len, Kd, red);
+        if (threadIdx.x < RB && i0 + (int)threadIdx.x < n) {
+            const int i = i0 + threadIdx.x;
+            u[i] = (int64_t)fmax(red[threadIdx.x].b1, 0.0);
             out_row2col[i] = row2col[i];
         }
     }
@@ -1210,6 +1223,10 @@ __global__ __launch_bounds__(BID_THREADS) void duals_kernel(
 // matching valid, duals non-negative, every feasible pair covered
 // (min reduced cost), primal and dual totals.
 // K32: K fits a signed 32-bit integer, so K*w is one 32 x 32 -> 64-bit multiply-add.
+// A workgroup takes CERT_ROWS rows at a time: each column dual (8 bytes, against 4 for a weight)
+// is loaded once for all of them.
+constexpr int CERT_ROWS = 4;
+
 template <bool K32>
 __global__ __launch_bounds__(BID_THREADS) void certificate_kernel(
     const int32_t *__restrict__ W, int64_t ldw, int n, int m, const int32_t *__restrict__ row2col,
@@ -1217,53 +1234,62 @@ __global__ __launch_bounds__(BID_THREADS) void certificate_kernel(
     mf_cert_out *out)
 {
     __shared__ long long red[BID_THREADS / 64];
-    constexpr int UN = 4;               // independent 16-byte loads in flight per thread
+    constexpr int UN = 2;               // column groups of four in flight per thread
     long long dual_part = 0, primal_part = 0;
     int flags = 0, matched = 0;
     long long min_rc = INT64_MAX;
     const int k32 = (int)K;
-    for (int i = blockIdx.x; i < n; i += gridDim.x) {
-        const long long ui = u[i];
-        const int32_t *row = W + (size_t)i * ldw;
-        for (int j0 = threadIdx.x * 4; j0 < m; j0 += BID_THREADS * 4 * UN) {
-            int4 w4[UN];
+    for (int i0 = blockIdx.x * CERT_ROWS; i0 < n; i0 += gridDim.x * CERT_ROWS) {
+        long long ui[CERT_ROWS];
+        const int32_t *rows[CERT_ROWS];
 #pragma unroll
-            for (int q = 0; q < UN; ++q) {
-                const int j = j0 + q * BID_THREADS * 4;
-                w4[q] = j < m ? *(const int4 *)(row + j)
-                              : make_int4(MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE);
-            }
-            // the column duals are loaded whatever the weights turn out to be (index clamped into
-            // the array), so that no load waits for a comparison
+        for (int r = 0; r < CERT_ROWS; ++r) {
+            const int i = min(i0 + r, n - 1);               // a short last group repeats its last row
+            ui[r] = u[i];
+            rows[r] = W + (size_t)i * ldw;
+        }
+        for (int j0 = threadIdx.x * 4; j0 < m; j0 += BID_THREADS * 4 * UN) {
+            // every load is issued before any comparison: the column duals whatever the weights
+            // turn out to be (index clamped into the array), the weights of all the rows
             long long vj[UN][4];
+            int4 w4[UN][CERT_ROWS];
 #pragma unroll
             for (int q = 0; q < UN; ++q) {
                 const int j = j0 + q * BID_THREADS * 4;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) vj[q][e] = v[min(j + e, m - 1)];
+#pragma unroll
+                for (int r = 0; r < CERT_ROWS; ++r)
+                    w4[q][r] = j < m ? *(const int4 *)(rows[r] + j)
+                                     : make_int4(MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE);
             }
 #pragma unroll
             for (int q = 0; q < UN; ++q) {
                 const int j = j0 + q * BID_THREADS * 4;
-                const int32_t w[4] = {w4[q].x, w4[q].y, w4[q].z, w4[q].w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const long long cover = ui + vj[q][e];
-                    const long long rc = K32 ? cover - (long long)w[e] * (long long)k32 : cover - K * (long long)w[e];
-                    const bool counts = j + e < m && w[e] != MF_INFEASIBLE;
-                    min_rc = counts && rc < min_rc ? rc : min_rc;
+                for (int r = 0; r < CERT_ROWS; ++r) {
+                    const int32_t w[4] = {w4[q][r].x, w4[q][r].y, w4[q][r].z, w4[q][r].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const long long cover = ui[r] + vj[q][e];
+                        const long long rc = K32 ? cover - (long long)w[e] * (long long)k32 : cover - K * (long long)w[e];
+                        const bool counts = j + e < m && w[e] != MF_INFEASIBLE;
+                        min_rc = counts && rc < min_rc ? rc : min_rc;
+                    }
                 }
             }
         }
-        if (threadIdx.x == 0) {
-            if (ui < 0) flags |= 4;
-            dual_part += ui;
+        if (threadIdx.x < CERT_ROWS && i0 + (int)threadIdx.x < n) {          // one thread per row of the group
+            const int i = i0 + threadIdx.x;
+            const long long mine = u[i];
+            if (mine < 0) flags |= 4;
+            dual_part += mine;
             const int j = row2col[i];
             if (j != -1) {
                 if (j < 0 || j >= m) flags |= 1;
                 else {
                     if (atomicAdd(&colmark[j], 1) != 0) flags |= 1;
-                    const int32_t w = row[j];
+                    const int32_t w = W[(size_t)i * ldw + j];
                     if (w == MF_INFEASIBLE || w < 0) flags |= 2;
                     else { primal_part += w; matched += 1; }
                 }
@@ -1280,6 +1306,8 @@ __global__ __launch_bounds__(BID_THREADS) void certificate_kernel(
         const long long o = __shfl_xor(min_rc, off);
         min_rc = o < min_rc ? o : min_rc;
         dual_part += __shfl_xor(dual_part, off);
+        primal_part += __shfl_xor(primal_part, off);
+        matched += __shfl_xor(matched, off);
         flags |= __shfl_xor(flags, off);
     }
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1477,7 +1505,7 @@ int mf_run_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ld
 {
     hipLaunchKernelGGL(init_cert_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->cert);
     hipLaunchKernelGGL(fill_int_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, ctx->colmark, m, 0);
-    const int grid = n < MAX_GRID ? n : MAX_GRID;
+    const int groups = (n + CERT_ROWS - 1) / CERT_ROWS, grid = groups < MAX_GRID ? groups : MAX_GRID;
     hipLaunchKernelGGL(K >= INT32_MIN && K <= INT32_MAX ? certificate_kernel<true> : certificate_kernel<false>,
                        dim3(grid), dim3(BID_THREADS), 0, ctx->stream, d_W, ldw, n, m,
                        d_row2col, d_u, d_v, (long long)K, ctx->colmark, ctx->cert);
@@ -1637,15 +1665,15 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     }
     MF_HIP(hipEventRecord(ctx->ev[4], ctx->stream));
     {
-        const int grid = rn < MAX_GRID ? rn : MAX_GRID;
+        const int groups = (rn + 3) / 4, grid = groups < MAX_GRID ? groups : MAX_GRID;
         if (!flip && !staged) {
-            hipLaunchKernelGGL(duals_kernel, dim3(grid), dim3(BID_THREADS), 0, ctx->stream, A, lda, rn, rm,
+            hipLaunchKernelGGL((duals_kernel<64, 4>), dim3(grid), dim3(64), 0, ctx->stream, A, lda, rn, rm,
                                ctx->price, ctx->row2col, Kd, d_row2col, d_u, d_v, fwd.line_len);
         } else {
             // the solve ran in other coordinates: results go through scratch (the searches' label
             // arrays are idle now) and are mapped to the caller's rows and columns
             int64_t *u_int = (int64_t *)ctx->path_label, *v_int = (int64_t *)ctx->path_expanded;
-            hipLaunchKernelGGL(duals_kernel, dim3(grid), dim3(BID_THREADS), 0, ctx->stream, A, lda, rn, rm,
+            hipLaunchKernelGGL((duals_kernel<64, 4>), dim3(grid), dim3(64), 0, ctx->stream, A, lda, rn, rm,
                                ctx->price, ctx->row2col, Kd, ctx->list[0], u_int, v_int, fwd.line_len);
             hipLaunchKernelGGL(fill_int_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, d_row2col, n, -1);
             const int32_t *row_ids = staged ? (flip ? ctx->order_off : ctx->order_on) : nullptr;
