@@ -97,3 +97,65 @@ def test_cluster_scale_round_with_unmatched_workloads(mm, orc):
     r, res, Wg, r2c, u, v = _round(mm, "C4", 7)
     _check_certificate(orc, Wg, res, r2c, u, v)
     assert res.matched < r["n"], "the instance no longer exercises the second side"
+
+
+def _mask_bits_agree(r, Wg):
+    a, b = r["x_on"][:, 0], r["x_off"][:, 0]
+    for i0 in range(0, r["n"], 2048):
+        masked = (a[i0:i0 + 2048, None] + b[None, :]) > np.float32(1.0)
+        assert ((Wg[i0:i0 + 2048] == INF) == masked).all()
+
+
+def test_cluster_scale_scoring_with_one_predictor_per_gpu_type(mm, orc):
+    """The typed scoring pass bench.py times (C4, three GPU types): sampled rows and columns against
+    the checker's per-row choice of predictor, every mask bit against the rule itself."""
+    r = synth.scheduling_round("C4", 1)
+    n, m, S = r["n"], r["m"], r["cfg"].scale
+    plist = synth.typed_predictors(1 + 7, r["cfg"].F, [r["cfg"].H] * 3)
+    types = synth.gpu_types(1, n, 3)
+    ctx = mm.Context(n, m)
+    preds = [ctx.predictor(dev_params(p), S) for p in plist]
+    W = torch.empty((n, (m + 3) // 4 * 4), dtype=torch.int32, device="cuda")
+    ctx.score_pairs_typed(preds, dev(types), dev(r["x_on"]), dev(r["x_off"]), W)
+    torch.cuda.synchronize()
+    Wg = W.cpu().numpy()[:, :m]
+    ctx.close()
+    _mask_bits_agree(r, Wg)
+    tol = weight_tolerance(S)
+    rows = np.sort(synth.permutation(17, n)[:48])
+    assert len(set(types[rows].tolist())) == 3, "the sample misses a GPU type"
+    _, Wr = orc.score_pairs_typed(r["x_on"][rows], r["x_off"], plist, types[rows], S)
+    ok = Wr != INF
+    assert np.abs(Wg[rows][ok].astype(np.int64) - Wr[ok]).max() <= tol
+    cols = np.sort(synth.permutation(18, m)[:32])
+    _, Wc = orc.score_pairs_typed(r["x_on"], r["x_off"][cols], plist, types, S)
+    ok = Wc != INF
+    assert np.abs(Wg[:, cols][ok].astype(np.int64) - Wc[ok]).max() <= tol
+
+
+def test_cluster_scale_scoring_with_the_pair_dependent_sm_input(mm, orc):
+    """The scoring pass with the third predictor input that bench.py times (C4): sampled rows and
+    columns against the checker, every mask bit against the rule itself."""
+    sm = (2, 3)                                   # as in bench.py: online SM activity, offline SM share
+    r = synth.scheduling_round("C4", 1)
+    n, m, S = r["n"], r["m"], r["cfg"].scale
+    full = synth.with_sm_input(r["params"], 1 + 3)
+    p = {k: dev(v) for k, v in full.items() if k != "W1"}
+    p["W1"] = dev(full["W1"][:, :-1]); p["W1sm"] = dev(full["W1"][:, -1])
+    ctx = mm.Context(n, m)
+    pred = ctx.predictor(p, S, sm=sm)
+    W = torch.empty((n, (m + 3) // 4 * 4), dtype=torch.int32, device="cuda")
+    ctx.score_pairs(pred, dev(r["x_on"]), dev(r["x_off"]), W)
+    torch.cuda.synchronize()
+    Wg = W.cpu().numpy()[:, :m]
+    ctx.close()
+    _mask_bits_agree(r, Wg)
+    tol = weight_tolerance(S)
+    rows = np.sort(synth.permutation(19, n)[:48])
+    _, Wr = orc.score_pairs(r["x_on"][rows], r["x_off"], full, S, sm=sm)
+    ok = Wr != INF
+    assert np.abs(Wg[rows][ok].astype(np.int64) - Wr[ok]).max() <= tol
+    cols = np.sort(synth.permutation(20, m)[:32])
+    _, Wc = orc.score_pairs(r["x_on"], r["x_off"][cols], full, S, sm=sm)
+    ok = Wc != INF
+    assert np.abs(Wg[:, cols][ok].astype(np.int64) - Wc[ok]).max() <= tol
