@@ -26,306 +26,9 @@
 // All dual values are integers below 2^43; the scans evaluate K*w - dual in
 // double precision, where such integers and their differences are exact, so
 // that they run at the full rate of the FP64 vector units.
-#include "internal.h"
-#include <math.h>
+#include "scan.h"
 
 namespace {
-
-constexpr int BID_THREADS = 256;
-constexpr int MAX_GRID = 8192;
-constexpr double NEG_HUGE = -1.0e300;
-
-__device__ inline unsigned long long pack_word(double dual, int id_plus_one)
-{
-    return ((unsigned long long)(long long)dual << MF_ID_BITS) | (unsigned long long)id_plus_one;
-}
-__device__ inline double word_dual(unsigned long long w) { return (double)(long long)(w >> MF_ID_BITS); }
-__device__ inline int word_id(unsigned long long w) { return (int)(w & MF_ID_MASK) - 1; }
-
-struct Top2 {
-    double b1, b2;      // best and second-best value
-    int idx, w;         // position and weight of the best
-};
-
-__device__ inline void top2_merge(Top2 &t, const Top2 &o)
-{
-    const double nb2 = fmax(fmax(t.b2, o.b2), fmin(t.b1, o.b1));
-    const bool take = (o.b1 > t.b1) || (o.b1 == t.b1 && o.idx < t.idx);
-    t.idx = take ? o.idx : t.idx;
-    t.w = take ? o.w : t.w;
-    t.b1 = fmax(t.b1, o.b1);
-    t.b2 = nb2;
-}
-
-struct SideArgs {
-    const int32_t *A;                   // the bidding side's lines (W for rows, W^T for columns)
-    long long pitch;
-    int len;
-    double *other_dual;                 // opposite duals as doubles, raised with atomicMax on the bits
-    unsigned long long *otherword;      // opposite packed (dual, holder): the authoritative copy
-    double eps, Kd;
-    const int *line_len;                // optional: every entry of line b at or beyond line_len[b] is infeasible
-    int typical_len;                    // what a scan reads on average (host-side choice of kernels only)
-};
-
-// How much of line b a scan has to read.
-__device__ __forceinline__ int line_length(const SideArgs &s, int b)
-{
-    return s.line_len ? min(s.line_len[b], s.len) : s.len;
-}
-
-// Loads that must observe values other wavefronts produced during this kernel:
-// they bypass the caches that atomics performed at the memory side do not update.
-__device__ inline unsigned long long load_fresh_u64(const unsigned long long *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline unsigned load_fresh_u32(const unsigned *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline void store_through(unsigned long long *p, unsigned long long v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline double load_fresh(const double *p)
-{
-    return __longlong_as_double((long long)__hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED,
-                                                             __HIP_MEMORY_SCOPE_AGENT));
-}
-
-// Folds four consecutive entries (values v0..v3 at index j) into a running
-// top-2: a min/max network finds the group's best two, and only a group that
-// beats the running best pays for locating the entry.
-//
-// Ties.  Any entry attaining the best value is a correct choice, and "the
-// smallest index" sends every one of a set of identical bidders to the same
-// entry, where all but one lose.  Indices are therefore compared through a
-// per-bidder key, index ^ salt (salt below 2^20, so keys stay below 2^20 too):
-// identical bidders spread over tied entries.  Scans return the key; callers
-// undo it with the same xor.
-__device__ __forceinline__ int tie_salt(int bidder)
-{
-    return (int)(((unsigned)bidder * 2654435761u) >> 12) & 0xfffff;
-}
-
-__device__ __forceinline__ void top2_push4(double &b1, double &b2, int &idx, int &wbest, double v0,
-                                           double v1, double v2, double v3, int j, const int4 &w, int salt)
-{
-    const double hi0 = fmax(v0, v1), lo0 = fmin(v0, v1);
-    const double hi1 = fmax(v2, v3), lo1 = fmin(v2, v3);
-    const double g1 = fmax(hi0, hi1);
-    const double g2 = fmax(fmin(hi0, hi1), fmax(lo0, lo1));
-    if (g1 > b1) {                                      // smallest index attaining the group's best
-        const bool a0 = v0 == g1, a1 = v1 == g1, a2 = v2 == g1;
-        idx = (j + (a0 ? 0 : a1 ? 1 : a2 ? 2 : 3)) ^ salt;
-        wbest = a0 ? w.x : a1 ? w.y : a2 ? w.z : w.w;
-    }
-    b2 = fmax(fmax(b2, g2), fmin(b1, g1));
-    b1 = fmax(b1, g1);
-}
-
-// Wavefront-wide reductions by data-parallel-primitive moves (row shifts
-// within each row of 16 lanes, then row broadcasts), which cost a few cycles
-// per step where a cross-lane permute through LDS costs a hundred.  Lanes a
-// step has no source for keep their own value; maximum and minimum do not mind
-// seeing a value twice.  The total lands in lane 63 and is read from there.
-template <int CTRL>
-__device__ __forceinline__ int dpp_move(int v)
-{
-    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
-}
-template <int CTRL>
-__device__ __forceinline__ double dpp_move(double v)
-{
-    return __hiloint2double(dpp_move<CTRL>(__double2hiint(v)), dpp_move<CTRL>(__double2loint(v)));
-}
-constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118,
-              DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
-
-__device__ __forceinline__ double wave_max(double v)
-{
-    v = fmax(v, dpp_move<DPP_ROW_SHR1>(v));
-    v = fmax(v, dpp_move<DPP_ROW_SHR2>(v));
-    v = fmax(v, dpp_move<DPP_ROW_SHR4>(v));
-    v = fmax(v, dpp_move<DPP_ROW_SHR8>(v));
-    v = fmax(v, dpp_move<DPP_ROW_BCAST15>(v));
-    v = fmax(v, dpp_move<DPP_ROW_BCAST31>(v));
-    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63),
-                            __builtin_amdgcn_readlane(__double2loint(v), 63));
-}
-
-__device__ __forceinline__ int wave_min(int v)
-{
-    v = min(v, dpp_move<DPP_ROW_SHR1>(v));
-    v = min(v, dpp_move<DPP_ROW_SHR2>(v));
-    v = min(v, dpp_move<DPP_ROW_SHR4>(v));
-    v = min(v, dpp_move<DPP_ROW_SHR8>(v));
-    v = min(v, dpp_move<DPP_ROW_BCAST15>(v));
-    v = min(v, dpp_move<DPP_ROW_BCAST31>(v));
-    return __builtin_amdgcn_readlane(v, 63);
-}
-
-// Wavefront-wide top-2 of per-lane top-2s, as two plain maximum reductions: the
-// best value, the first lane holding it (its index and weight are then read
-// from that lane), and the best of everything else.
-__device__ __forceinline__ Top2 wave_top2(const Top2 &t)
-{
-    Top2 r;
-    r.b1 = wave_max(t.b1);
-    // among lanes attaining the best, the smallest index wins (ties between lanes are rare)
-    const bool hit = t.b1 == r.b1;
-    const int idx = wave_min(hit ? t.idx : 0x7fffffff);
-    r.idx = idx;
-    const bool owner = hit && t.idx == idx;
-    const unsigned long long own = __ballot(owner);
-    const int src = own ? (int)__ffsll((long long)own) - 1 : 0;
-    r.w = __builtin_amdgcn_readlane(t.w, src);
-    r.b2 = wave_max(owner ? t.b2 : t.b1);
-    return r;
-}
-
-// Scans line A[0..len) against dual[0..len): best and second-best value of
-// K*w - dual, the entry attaining the best (as the key (index_base + position)
-// ^ salt, smallest key among ties) and its weight.  Every thread of the
-// NT-thread block must call it; the result is valid in thread 0.
-// A is 16-byte aligned and padded to a multiple of four entries, dual
-// likewise.  `fresh` re-reads the duals past the caches (block-uniform).
-template <int NT>
-__device__ inline Top2 block_scan(const int32_t *__restrict__ A, const double *__restrict__ dual,
-                                  int len, double Kd, bool fresh, Top2 *red, int index_base, int salt)
-{
-    constexpr int UN = 4;               // independent load batches in flight per thread
-    Top2 t{NEG_HUGE, NEG_HUGE, 0x7fffffff, 0};
-    const int full = len & ~3;          // whole groups of four
-    for (int j0 = threadIdx.x * 4; j0 < full; j0 += NT * 4 * UN) {
-        int4 w[UN];
-        double p[UN][4];
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int j = j0 + u * NT * 4;
-            if (j < full) {
-                w[u] = *(const int4 *)(A + j);
-                if (fresh) {
-                    p[u][0] = load_fresh(dual + j); p[u][1] = load_fresh(dual + j + 1);
-                    p[u][2] = load_fresh(dual + j + 2); p[u][3] = load_fresh(dual + j + 3);
-                } else {
-                    const double2 p01 = *(const double2 *)(dual + j);
-                    const double2 p23 = *(const double2 *)(dual + j + 2);
-                    p[u][0] = p01.x; p[u][1] = p01.y; p[u][2] = p23.x; p[u][3] = p23.y;
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int j = j0 + u * NT * 4;
-            if (j < full)
-                top2_push4(t.b1, t.b2, t.idx, t.w, fma(Kd, (double)w[u].x, -p[u][0]),
-                           fma(Kd, (double)w[u].y, -p[u][1]), fma(Kd, (double)w[u].z, -p[u][2]),
-                           fma(Kd, (double)w[u].w, -p[u][3]), j + index_base, w[u], salt);
-        }
-    }
-    if (full < len && (int)threadIdx.x == (full / 4) % NT) {   // the last, partial group
-        const int4 w = *(const int4 *)(A + full);
-        double p[3];
-        for (int e = 0; e < 3; ++e) p[e] = fresh ? load_fresh(dual + full + e) : dual[full + e];
-        top2_push4(t.b1, t.b2, t.idx, t.w, fma(Kd, (double)w.x, -p[0]),
-                   full + 1 < len ? fma(Kd, (double)w.y, -p[1]) : NEG_HUGE,
-                   full + 2 < len ? fma(Kd, (double)w.z, -p[2]) : NEG_HUGE, NEG_HUGE, full + index_base, w, salt);
-    }
-    // waves that saw no entry skip the reduction (they share SIMDs with the busy ones)
-    const bool busy = (int)(threadIdx.x & ~63u) * 4 < len;
-    if (busy) t = wave_top2(t);
-    if (NT == 64) return t;
-    __syncthreads();                       // protect `red` from its previous use
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
-    __syncthreads();
-    if (threadIdx.x < 64) {
-        t = threadIdx.x < NT / 64 ? red[threadIdx.x] : Top2{NEG_HUGE, NEG_HUGE, 0x7fffffff, 0};
-        t = wave_top2(t);
-    }
-    return t;
-}
-
-// Whole-line scan of RB lines at once: the opposite duals are loaded once per
-// four entries and applied to all RB lines, which cuts the on-chip traffic per
-// entry (duals are 8 bytes, weights 4) and keeps RB + 2 loads in flight per
-// thread.  On return red[r] holds line r's result (a barrier has been passed).
-template <int NT, int RB>
-__device__ __forceinline__ void block_scan_rows(const int32_t *const (&rows)[RB], const int (&salt)[RB],
-                                                const double *__restrict__ dual, int len, double Kd,
-                                                Top2 *red)
-{
-    double b1[RB], b2[RB];
-    int idx[RB], wb[RB];
-#pragma unroll
-    for (int r = 0; r < RB; ++r) { b1[r] = NEG_HUGE; b2[r] = NEG_HUGE; idx[r] = 0x7fffffff; wb[r] = 0; }
-    const int full = len & ~3;                          // whole groups of four
-#pragma unroll 2
-    for (int j = threadIdx.x * 4; j < full; j += NT * 4) {
-        int4 w[RB];
-#pragma unroll
-        for (int r = 0; r < RB; ++r) w[r] = *(const int4 *)(rows[r] + j);
-        const double2 p01 = *(const double2 *)(dual + j);
-        const double2 p23 = *(const double2 *)(dual + j + 2);
-#pragma unroll
-        for (int r = 0; r < RB; ++r)
-            top2_push4(b1[r], b2[r], idx[r], wb[r], fma(Kd, (double)w[r].x, -p01.x),
-                       fma(Kd, (double)w[r].y, -p01.y), fma(Kd, (double)w[r].z, -p23.x),
-                       fma(Kd, (double)w[r].w, -p23.y), j, w[r], salt[r]);
-    }
-    if (full < len && (int)threadIdx.x == (full / 4) % NT) {   // the last, partial group
-        const double2 p01 = *(const double2 *)(dual + full);
-        const double2 p23 = *(const double2 *)(dual + full + 2);
-#pragma unroll
-        for (int r = 0; r < RB; ++r) {
-            const int4 w = *(const int4 *)(rows[r] + full);
-            top2_push4(b1[r], b2[r], idx[r], wb[r], fma(Kd, (double)w.x, -p01.x),
-                       full + 1 < len ? fma(Kd, (double)w.y, -p01.y) : NEG_HUGE,
-                       full + 2 < len ? fma(Kd, (double)w.z, -p23.x) : NEG_HUGE, NEG_HUGE, full, w, salt[r]);
-        }
-    }
-    __syncthreads();                       // protect `red` from its previous use
-#pragma unroll
-    for (int r = 0; r < RB; ++r) {
-        const Top2 t = wave_top2(Top2{b1[r], b2[r], idx[r], wb[r]});
-        if ((threadIdx.x & 63) == 0) red[RB + r * (NT / 64) + (threadIdx.x >> 6)] = t;
-    }
-    __syncthreads();
-    if (threadIdx.x < RB) {                // thread r folds the per-wave results of line r
-        Top2 t = red[RB + threadIdx.x * (NT / 64)];
-        for (int wv = 1; wv < NT / 64; ++wv) top2_merge(t, red[RB + threadIdx.x * (NT / 64) + wv]);
-        red[threadIdx.x] = t;
-    }
-    __syncthreads();
-}
-
-// One thread: bidder b has seen best value t.b1 at column/row t.idx and
-// second-best t.b2.  A bidder whose best value is at most eps rests with dual
-// 0.  (A bidder's own dual is implied by what it holds - K*w minus the dual it
-// offered, or 0 when it holds nothing - and is written out once the run is
-// over; nothing reads it while bids are flying.)  Otherwise it offers the opposite workload the highest dual at which that
-// workload is still within eps of the bidder's best alternative; the offer is
-// an atomicMax on the packed (dual, holder) word, so the highest offer wins
-// whatever the order.  The offer is formed from the weight itself, not from the
-// dual the scan happened to read, which may have moved since.
-// Returns the workload that has to bid next because of this bid (the bidder
-// itself if it was outbid in the meantime, the previous holder if it won), or -1.
-__device__ inline int decide_and_bid(const SideArgs &s, int b, const Top2 &t)
-{
-    if (t.b1 <= s.eps) return -1;
-    const double keep = fmax(t.b2 - s.eps, 0.0);
-    const double offer = s.Kd * (double)t.w - keep;
-    const unsigned long long mine = pack_word(offer, b + 1);
-    const unsigned long long old = atomicMax(&s.otherword[t.idx], mine);
-    unsigned long long *dual_bits = (unsigned long long *)&s.other_dual[t.idx];
-    if (old < mine) {
-        atomicMax(dual_bits, (unsigned long long)__double_as_longlong(offer));
-        return word_id(old);
-    }
-    atomicMax(dual_bits, (unsigned long long)__double_as_longlong(word_dual(old)));
-    return b;
-}
 
 // One round for many bidders: a workgroup per bidder, bids taking effect at
 // once.  Later bidders of the same round may already see them (or a slightly
@@ -654,381 +357,6 @@ __global__ __launch_bounds__(NT) void team_kernel(SideArgs s, const int *__restr
     }
 }
 
-// The last bidders of a run, placed by shortest augmenting paths.
-//
-// A chain of bids is a greedy walk: every evicted holder moves to its own best
-// alternative, and with one or two bidders left such a walk takes thousands of
-// dependent steps to reach a free line.  The shortest way to make room is far
-// shorter in hops, and finding it is a breadth-type search whose every step is
-// wide.  For a bidder r, in the notation of the header of this file with
-// "rows" the bidding side, let rc(i,k) = pi_i + p_k - K W_ik + eps >= 0 (I1)
-// for every assigned row i and for r (pi_r = best value of r - eps); assigned
-// pairs have rc = eps.  A path r -> k1, holder(k1) -> k2, ... that ends in a
-// column nobody holds, or in a row giving up its column for profit 0 (at extra
-// length pi_i), frees a place for r; label(k) is the length sum(rc) of the
-// shortest such path to column k and d the length of the shortest complete
-// one.  Raising p_k by d - label(k) on every column with label(k) < d (their
-// holders' profits drop by as much) keeps I1 and I2 and makes the shortest
-// path tight; re-assigning along it, each row paying eps more for its new
-// column, keeps them too and leaves one bidder fewer.  Prices only rise, so
-// this mixes freely with bids.  (The successive-shortest-path step of the
-// Hungarian method, on costs relaxed by eps.)
-//
-// All compute units run the search together: labels are corrected in
-// super-steps - every row whose column's label dropped into the current
-// window [low, low + width) is scanned against all columns, in parallel, with
-// an atomic minimum per improved label - separated by grid-wide barriers.
-// Data shared between workgroups moves only through atomics and uncached
-// loads/stores.  Every wait is bounded; if one runs out all workgroups leave,
-// nothing half-done (the price update alone is a valid state), and the host
-// falls back to the chain kernels.
-constexpr int PATH_THREADS = 1024;
-constexpr int PATH_MAX_SLICES = 1024;
-constexpr int PATH_GROUP = 16, PATH_MAX_GROUPS = 64;      // up to 1024 workgroups
-constexpr int PATH_SEGMENTS = 16, PATH_PUSH_BUFFER = 4096;
-constexpr unsigned long long PATH_INF = ~0ull;
-constexpr int PATH_FRONTIER_LOW = 128, PATH_FRONTIER_HIGH = 1024;
-
-struct alignas(128) PathCtl {
-    unsigned long long sink;        // shortest complete path: length << 21 | kind << 20 | id (kind 1: row id gives up)
-    unsigned long long low[3];      // smallest label still to be expanded, per slot
-    // best value of the current bidder (bits of a double), by parity of its position in the list:
-    // when a bidder rests, workgroup 0 may already be writing the next bidder's value while a
-    // slower workgroup has yet to read this one
-    unsigned long long first_value[2];
-    unsigned int arrive, pad[3];    // whole groups that have arrived at barriers so far | PATH_GAVE_UP
-    unsigned long long steps, scans, entries;
-    struct alignas(128) { unsigned int arrive; } group[PATH_MAX_GROUPS];
-    // Frontier lengths: one counter per segment (a segment collects the pushes of sixteen
-    // workgroups, so no counter is hit by more than sixteen atomics per step), in three slots:
-    // step t reads slot t % 3, fills slot (t + 1) % 3 and clears slot (t + 2) % 3, which every
-    // workgroup finished reading before the barrier that ended step t - 1.
-    struct alignas(128) { unsigned int count; } seg[3][PATH_SEGMENTS];
-};
-
-struct PathBuffers {
-    unsigned long long *label;      // [len] length << 20 | predecessor row
-    unsigned long long *expanded;   // [len] label at which the column's holder was last scanned
-    unsigned int *stamp;            // [len] last step in which the column was put on a frontier
-    int *fr_col[2];                 // frontiers (by step parity): PATH_SEGMENTS segments of len columns each
-    int *held;                      // [rows] column a frontier row holds
-};
-
-// Grid-wide barrier in two levels: workgroups arrive at their group's counter, the last of a
-// group at the top counter, and everybody waits until the top counter shows that all groups have
-// arrived for the so-many-th time.  (Hundreds of atomics on one address take turns; sixteen
-// groups of sixteen do not.)  Counters only ever grow.  The top bit of the top counter says that
-// somebody's wait ran out: whoever sees it leaves, so one load tells a waiting workgroup both.
-// Returns false when the wait ran out or another workgroup gave up.
-constexpr unsigned PATH_GAVE_UP = 0x80000000u;
-
-__device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned &generation, unsigned spin_limit)
-{
-    __shared__ int s_ok;
-    // every thread's writes (uncached stores and atomics) are acknowledged by memory before its
-    // workgroup reports in
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned groups = (workgroups + PATH_GROUP - 1) / PATH_GROUP;
-        const unsigned g = blockIdx.x / PATH_GROUP;
-        const unsigned size = min((unsigned)PATH_GROUP, workgroups - g * PATH_GROUP);
-        const unsigned target = (generation + 1u) * groups;      // whole groups arrived once this barrier is complete
-        unsigned seen = 0u;
-        if ((atomicAdd(&ctl->group[g].arrive, 1u) + 1u) % size == 0u) seen = atomicAdd(&ctl->arrive, 1u) + 1u;
-        unsigned spins = 0;
-        while (!(seen & PATH_GAVE_UP) && seen < target) {
-            if (++spins > spin_limit) { seen = atomicOr(&ctl->arrive, PATH_GAVE_UP) | PATH_GAVE_UP; break; }
-            seen = load_fresh_u32(&ctl->arrive);
-        }
-        s_ok = (seen & PATH_GAVE_UP) ? 0 : 1;
-    }
-    ++generation;
-    __syncthreads();
-    return s_ok != 0;
-}
-
-__global__ void path_begin_kernel(mf_device_stats *stats, PathCtl *ctl, int ring)
-{
-    ctl->arrive = 0u; ctl->steps = 0ull; ctl->scans = 0ull; ctl->entries = 0ull;
-    for (int g = 0; g < PATH_MAX_GROUPS; ++g) ctl->group[g].arrive = 0u;
-    stats->cnt[(ring + 1) & 3] = 0;
-    stats->cnt[(ring + 2) & 3] = 0;
-    stats->rounds += 1ull;
-    stats->chain_depth += stats->launch_max;
-    stats->launch_max = 0;
-}
-
-__device__ inline void store_dual(const SideArgs &s, int k, double dual, int holder_plus_one)
-{
-    store_through(&s.otherword[k], pack_word(dual, holder_plus_one));
-    store_through((unsigned long long *)&s.other_dual[k], (unsigned long long)__double_as_longlong(dual));
-}
-
-__global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const int *__restrict__ list,
-                                                            int *__restrict__ out_list, mf_device_stats *stats,
-                                                            PathCtl *ctl, PathBuffers buf, int ring, int rows,
-                                                            double width_max, unsigned spin_limit)
-{
-    __shared__ Top2 red[PATH_THREADS / 64];
-    __shared__ unsigned s_pushes, s_base, s_first[PATH_SEGMENTS + 1];
-    __shared__ unsigned long long s_sink, s_low;
-    __shared__ int s_list[PATH_PUSH_BUFFER];
-    const unsigned G = gridDim.x;
-    const int wg = blockIdx.x, tid = threadIdx.x;
-    const int gtid = wg * PATH_THREADS + tid, gsize = (int)G * PATH_THREADS;
-    const int count = stats->cnt[ring & 3];
-    unsigned generation = 0;
-    int item = 0;
-    bool alive = true;
-    for (; item < count && alive; ++item) {
-        const int r0 = list[item];
-        // ---- clear the labels; workgroup 0 finds the bidder's best value ----
-        for (int k = gtid; k < s.len; k += gsize) {
-            store_through(&buf.label[k], PATH_INF);
-            store_through(&buf.expanded[k], PATH_INF);
-            __hip_atomic_store(&buf.stamp[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (wg == 0) {
-            const Top2 t = block_scan<PATH_THREADS>(s.A + (size_t)r0 * s.pitch, s.other_dual, line_length(s, r0),
-                                                    s.Kd, true, red, 0, 0);
-            if (tid < 3 * PATH_SEGMENTS)
-                __hip_atomic_store(&ctl->seg[tid / PATH_SEGMENTS][tid % PATH_SEGMENTS].count, 0u, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            if (tid == 0) {
-                const double v1 = t.b1;
-                store_through(&ctl->first_value[item & 1], (unsigned long long)__double_as_longlong(v1));
-                store_through(&ctl->low[0], PATH_INF);
-                store_through(&ctl->low[1], PATH_INF);
-                store_through(&ctl->low[2], PATH_INF);
-                if (v1 > s.eps) {                                       // pi_r = v1 - eps: rc(r, best column) = 0
-                    store_through(&ctl->sink, ((unsigned long long)(long long)(v1 - s.eps) << 21) | (1ull << 20) |
-                                                  (unsigned long long)r0);
-                    __hip_atomic_store(&buf.held[r0], -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-        }
-        if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
-        // duals stand still during a search: drop what the caches hold of them from before the
-        // last re-assignment once, then read them through the caches
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        const double v1 = __longlong_as_double((long long)load_fresh_u64(&ctl->first_value[item & 1]));
-        if (v1 <= s.eps) continue;                                      // rests with dual 0: nothing to move
-        const double first_profit = v1 - s.eps;
-
-        // ---- label-correcting search, one grid barrier per super-step ----
-        // A step scans the rows on the current frontier; a label that falls inside the window
-        // puts its column on the next frontier at once (claimed through a per-step stamp, so once
-        // per step), whose holder is scanned in the next step from the label the column has by
-        // then.  Only when a frontier comes up empty does a pass over all columns pick up the
-        // labels that fell outside earlier windows, or move the window on.
-        double low = 0.0;
-        // The window adapts to what it yields: wide enough to keep the device busy, narrow enough
-        // that rows are not scanned long before their label is final (every workgroup derives the
-        // same width from the same counters).
-        double width = 4.0 * s.eps;
-        unsigned long long my_steps = 0, my_scans = 0, my_entries = 0;
-        const int segment = wg / PATH_GROUP % PATH_SEGMENTS;
-        unsigned step = 0;
-        bool swept = false;                      // the previous step was a pass over all columns
-        for (;;) {
-            // far more steps than a search over sound duals can take: give the bidder back to the
-            // chains (every workgroup counts the same steps, so all leave here together)
-            if (++step > 4u * (unsigned)s.len + 4096u) { alive = false; break; }
-            const unsigned c = step % 3u, p = (step + 1u) % 3u, z = (step + 2u) % 3u;
-            // frontier of this step: its segments' lengths (the very first holds just the bidder)
-            if (tid < 64) {
-                unsigned n_seg = 0;
-                if (tid < PATH_SEGMENTS && step > 1u) n_seg = load_fresh_u32(&ctl->seg[c][tid].count);
-                unsigned run = n_seg;                               // inclusive prefix sums over 16 lanes
-                for (int d = 1; d < PATH_SEGMENTS; d <<= 1) {
-                    const unsigned o = __shfl_up(run, d);
-                    if ((int)tid >= d) run += o;
-                }
-                if (tid < PATH_SEGMENTS) s_first[tid + 1] = run;
-                if (tid == 0) { s_first[0] = 0u; s_pushes = 0u; s_sink = PATH_INF; s_low = PATH_INF; }
-            }
-            __syncthreads();
-            const int nf = step == 1u ? 1 : (int)s_first[PATH_SEGMENTS];
-            const unsigned long long sink_word = load_fresh_u64(&ctl->sink);
-            const double bound = (double)(long long)(sink_word >> 21);
-            if (step > 1u && swept && nf == 0) {
-                const unsigned long long lo = load_fresh_u64(&ctl->low[c]);
-                if (lo == PATH_INF || lo >= (sink_word >> 21)) break;       // every label below the sink is final
-                low = (double)(long long)lo;                                // move the window to the next label
-            }
-            if (nf > PATH_FRONTIER_HIGH) width = fmax(s.eps, width * 0.5);
-            else if (nf < PATH_FRONTIER_LOW) width = fmin(width_max, width * 2.0);
-            const double limit = fmin(low + width, bound);
-            if (gtid < PATH_SEGMENTS)
-                __hip_atomic_store(&ctl->seg[z][gtid].count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (gtid == 0) store_through(&ctl->low[z], PATH_INF);
-            const int *frontier = buf.fr_col[step & 1u];
-            int *next_frontier = buf.fr_col[(step + 1u) & 1u];
-
-            // puts column k on the next frontier (through the workgroup's LDS list while it has room)
-            auto push = [&](int k) {
-                const unsigned slot = atomicAdd(&s_pushes, 1u);
-                if (slot < (unsigned)PATH_PUSH_BUFFER) s_list[slot] = k;
-                else {
-                    const unsigned pos = atomicAdd(&ctl->seg[p][segment].count, 1u);
-                    __hip_atomic_store(&next_frontier[(size_t)segment * s.len + pos], k, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-                }
-            };
-
-            if (nf > 0) {
-                swept = false;
-                // one wavefront per (row, slice of columns): enough independent loads in flight to
-                // stream the rows at memory speed whether the frontier holds one row or thousands
-                constexpr int WAVES = PATH_THREADS / 64;
-                const int total_waves = (int)G * WAVES, wave_id = wg * WAVES + (tid >> 6), lane = tid & 63;
-                int slices = total_waves / nf;
-                slices = slices < 1 ? 1 : (slices > PATH_MAX_SLICES ? PATH_MAX_SLICES : slices);
-                const int span = (((s.len + slices - 1) / slices) + 255) & ~255;
-                slices = (s.len + span - 1) / span;
-                const int items = nf * slices;
-                for (int it = wave_id; it < items; it += total_waves) {
-                    const int e = it / slices, sl = it - e * slices;
-                    int i, mine_col;
-                    double dist, profit;
-                    if (step == 1u) {
-                        i = r0; mine_col = -1; dist = 0.0; profit = first_profit;
-                    } else {
-                        int g = 0;
-                        while ((unsigned)e >= s_first[g + 1]) ++g;
-                        mine_col = __hip_atomic_load(&frontier[(size_t)g * s.len + (e - s_first[g])], __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-                        const unsigned long long lw = load_fresh_u64(&buf.label[mine_col]);
-                        i = word_id(load_fresh_u64(&s.otherword[mine_col]));
-                        dist = (double)(long long)(lw >> MF_ID_BITS);
-                        // the row's profit: what it holds minus that column's dual
-                        profit = s.Kd * (double)s.A[(size_t)i * s.pitch + mine_col] - s.other_dual[mine_col];
-                        if (sl == 0 && lane == 0) {
-                            store_through(&buf.expanded[mine_col], lw >> MF_ID_BITS);
-                            __hip_atomic_store(&buf.held[i], mine_col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            if (dist + profit < bound)                      // it may also give up and rest
-                                atomicMin(&ctl->sink, ((unsigned long long)(long long)(dist + profit) << 21) |
-                                                          (1ull << 20) | (unsigned long long)i);
-                        }
-                    }
-                    const int32_t *row = s.A + (size_t)i * s.pitch;
-                    const double base = dist + profit + s.eps;
-                    const int from = sl * span, to = min(line_length(s, i), from + span);
-#pragma unroll 2
-                    for (int k = from + lane * 4; k < to; k += 256) {
-                        const int4 w4 = *(const int4 *)(row + k);
-                        const double2 p01 = *(const double2 *)(s.other_dual + k);
-                        const double2 p23 = *(const double2 *)(s.other_dual + k + 2);
-                        const int32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
-                        const double pr[4] = {p01.x, p01.y, p23.x, p23.y};
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const double cand = base - fma(s.Kd, (double)w[q], -pr[q]);
-                            if (k + q < to && w[q] != MF_INFEASIBLE && cand < bound) {
-                                const unsigned long long mine = ((unsigned long long)(long long)cand << MF_ID_BITS) |
-                                                                (unsigned long long)i;
-                                // a cached label is never below the true one (labels only fall during a
-                                // search and the caches were emptied at its start): a safe first test
-                                if (mine < buf.label[k + q] && atomicMin(&buf.label[k + q], mine) > mine && cand < limit &&
-                                    atomicExch(&buf.stamp[k + q], step) != step) {
-                                    if (word_id(load_fresh_u64(&s.otherword[k + q])) < 0)    // a column nobody holds ends a path
-                                        atomicMin(&ctl->sink, (unsigned long long)(long long)cand << 21 |
-                                                                  (unsigned long long)(k + q));
-                                    else push(k + q);
-                                }
-                            }
-                        }
-                    }
-                    if (sl == 0 && lane == 0) { ++my_scans; my_entries += (unsigned long long)line_length(s, i); }
-                }
-            } else {
-                // ---- nothing on the frontier: look at every column ----
-                swept = true;
-                for (int first = 0; first < s.len; first += gsize) {
-                    const int k = first + gtid;
-                    if (k < s.len) {
-                        const unsigned long long lw = load_fresh_u64(&buf.label[k]);
-                        const unsigned long long ex = load_fresh_u64(&buf.expanded[k]);
-                        const unsigned long long d_int = lw >> MF_ID_BITS;
-                        const double d = (double)(long long)d_int;
-                        if (lw != PATH_INF && d < bound && d_int < ex) {
-                            if (d >= limit) atomicMin(&s_low, d_int);
-                            else if (word_id(load_fresh_u64(&s.otherword[k])) < 0)
-                                atomicMin(&s_sink, (d_int << 21) | (unsigned long long)k);
-                            else push(k);
-                        }
-                    }
-                }
-            }
-            // ---- hand the workgroup's pushes, sink and window candidates over ----
-            __syncthreads();
-            const unsigned pushed = min(s_pushes, (unsigned)PATH_PUSH_BUFFER);
-            if (tid == 0) {
-                s_base = pushed ? atomicAdd(&ctl->seg[p][segment].count, pushed) : 0u;
-                if (s_sink != PATH_INF) atomicMin(&ctl->sink, s_sink);
-                if (s_low != PATH_INF) atomicMin(&ctl->low[p], s_low);
-            }
-            __syncthreads();
-            for (unsigned t = tid; t < pushed; t += PATH_THREADS)
-                __hip_atomic_store(&next_frontier[(size_t)segment * s.len + s_base + t], s_list[t], __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            ++my_steps;
-            if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
-        }
-        if (!alive) break;
-
-        // ---- make the shortest path tight, then re-assign along it ----
-        // Workgroup 0 does both on its own, and only behind one more barrier: passing it proves
-        // that every workgroup finished its share of the search, so no wait that runs out can
-        // leave the duals half-updated or updated from incomplete labels.
-        if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }      // r0 not placed: handed back below
-        if (wg == 0) {
-            const unsigned long long sink = load_fresh_u64(&ctl->sink);
-            const unsigned long long d_star = sink >> 21;
-            for (int k = tid; k < s.len; k += PATH_THREADS) {
-                const unsigned long long lw = load_fresh_u64(&buf.label[k]);
-                if (lw == PATH_INF) continue;
-                const unsigned long long d_int = lw >> MF_ID_BITS;
-                if (d_int < d_star) {
-                    const unsigned long long cw = load_fresh_u64(&s.otherword[k]);
-                    store_dual(s, k, word_dual(cw) + (double)(long long)(d_star - d_int), (int)(cw & MF_ID_MASK));
-                }
-            }
-            __threadfence();
-            __syncthreads();
-            if (tid == 0) {
-                const int id = (int)(sink & 0xfffffull);
-                int k = ((sink >> 20) & 1ull) ? (id == r0 ? -1 : __hip_atomic_load(&buf.held[id], __ATOMIC_RELAXED,
-                                                                                     __HIP_MEMORY_SCOPE_AGENT))
-                                              : id;
-                int guard = 0;
-                while (k >= 0 && guard++ <= rows) {
-                    const int i = (int)(load_fresh_u64(&buf.label[k]) & MF_ID_MASK);
-                    const int before = __hip_atomic_load(&buf.held[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    store_dual(s, k, word_dual(load_fresh_u64(&s.otherword[k])) + s.eps, i + 1);
-                    k = (i == r0) ? -1 : before;
-                }
-                atomicAdd(&ctl->steps, my_steps);
-            }
-        }
-        if ((tid & 63) == 0 && my_scans) { atomicAdd(&ctl->scans, my_scans); atomicAdd(&ctl->entries, my_entries); }
-        if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; ++item; break; }   // r0 is placed
-    }
-    if (gtid == 0) {
-        for (int rest = item; rest < count; ++rest)                         // whoever was not served bids again
-            out_list[atomicAdd(&stats->cnt[(ring + 1) & 3], 1)] = list[rest];
-        if (!alive) atomicExch(&stats->team_abort, 2);
-        const unsigned long long steps = load_fresh_u64(&ctl->steps), scans = load_fresh_u64(&ctl->scans);
-        stats->launch_max = steps;
-        stats->bids += scans;
-        stats->chain_bids += scans;
-        stats->path_steps += steps;
-        stats->path_scans += scans;
-        stats->bytes += load_fresh_u64(&ctl->entries) * 4ull;
-    }
-}
-
 // Start of an epsilon phase: drop the assignment, keep the duals, all rows bid.
 __global__ void reset_kernel(int n, int m, const double *__restrict__ price,
                              unsigned long long *colword, int *row2col, int *col2row, int *list,
@@ -1186,179 +514,6 @@ __global__ __launch_bounds__(256) void max_weight_kernel(const int32_t *__restri
     if ((threadIdx.x & 63) == 0 && mx > stats->max_weight) atomicMax(&stats->max_weight, mx);
 }
 
-// Duals handed to the caller: v_j = p_j and the tightest row dual the prices
-// allow, u_i = max(0, max_j (K W_ij - p_j)).
-// RB rows per workgroup share every load of the prices (8 bytes per entry against 4 for a
-// weight), as in the bulk bidding rounds.
-template <int NT, int RB>
-__global__ __launch_bounds__(NT) void duals_kernel(
-    const int32_t *__restrict__ W, int64_t ldw, int n, int m, const double *__restrict__ price,
-    const int *__restrict__ row2col, double Kd, int32_t *__restrict__ out_row2col,
-    int64_t *__restrict__ u, int64_t *__restrict__ v, const int *__restrict__ line_len)
-{
-    __shared__ Top2 red[RB + RB * (NT / 64)];
-    for (int i0 = blockIdx.x * RB; i0 < n; i0 += gridDim.x * RB) {
-        const int32_t *rows[RB];
-        int salt[RB];
-        int len = 0;                                        // the group scans as far as its longest row
-#pragma unroll
-        for (int r = 0; r < RB; ++r) {
-            const int i = min(i0 + r, n - 1);               // a short last group repeats its last row
-            rows[r] = W + (size_t)i * ldw;
-            salt[r] = 0;
-            len = max(len, line_len ? min(line_len[i], m) : m);
-        }
-        block_scan_rows<NT, RB>(rows, salt, price, len, Kd, red);
-        if (threadIdx.x < RB && i0 + (int)threadIdx.x < n) {
-            const int i = i0 + threadIdx.x;
-            u[i] = (int64_t)fmax(red[threadIdx.x].b1, 0.0);
-            out_row2col[i] = row2col[i];
-        }
-    }
-    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < m; j += gridDim.x * blockDim.x)
-        v[j] = (int64_t)price[j];
-}
-
-// The proof of optimality, evaluated for arbitrary caller-supplied integers:
-// matching valid, duals non-negative, every feasible pair covered
-// (min reduced cost), primal and dual totals.
-// K32: K fits a signed 32-bit integer, so K*w is one 32 x 32 -> 64-bit multiply-add.
-// A workgroup takes CERT_ROWS rows at a time: each column dual (8 bytes, against 4 for a weight)
-// is loaded once for all of them.
-constexpr int CERT_ROWS = 4;
-
-template <bool K32>
-__global__ __launch_bounds__(BID_THREADS) void certificate_kernel(
-    const int32_t *__restrict__ W, int64_t ldw, int n, int m, const int32_t *__restrict__ row2col,
-    const int64_t *__restrict__ u, const int64_t *__restrict__ v, long long K, int *colmark,
-    mf_cert_out *out)
-{
-    __shared__ long long red[BID_THREADS / 64];
-    constexpr int UN = 2;               // column groups of four in flight per thread
-    long long dual_part = 0, primal_part = 0;
-    int flags = 0, matched = 0;
-    long long min_rc = INT64_MAX;
-    const int k32 = (int)K;
-    for (int i0 = blockIdx.x * CERT_ROWS; i0 < n; i0 += gridDim.x * CERT_ROWS) {
-        long long ui[CERT_ROWS];
-        const int32_t *rows[CERT_ROWS];
-#pragma unroll
-        for (int r = 0; r < CERT_ROWS; ++r) {
-            const int i = min(i0 + r, n - 1);               // a short last group repeats its last row
-            ui[r] = u[i];
-            rows[r] = W + (size_t)i * ldw;
-        }
-        for (int j0 = threadIdx.x * 4; j0 < m; j0 += BID_THREADS * 4 * UN) {
-            // every load is issued before any comparison: the column duals whatever the weights
-            // turn out to be (index clamped into the array), the weights of all the rows
-            long long vj[UN][4];
-            int4 w4[UN][CERT_ROWS];
-#pragma unroll
-            for (int q = 0; q < UN; ++q) {
-                const int j = j0 + q * BID_THREADS * 4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) vj[q][e] = v[min(j + e, m - 1)];
-#pragma unroll
-                for (int r = 0; r < CERT_ROWS; ++r)
-                    w4[q][r] = j < m ? *(const int4 *)(rows[r] + j)
-                                     : make_int4(MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE);
-            }
-#pragma unroll
-            for (int q = 0; q < UN; ++q) {
-                const int j = j0 + q * BID_THREADS * 4;
-#pragma unroll
-                for (int r = 0; r < CERT_ROWS; ++r) {
-                    const int32_t w[4] = {w4[q][r].x, w4[q][r].y, w4[q][r].z, w4[q][r].w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const long long cover = ui[r] + vj[q][e];
-                        const long long rc = K32 ? cover - (long long)w[e] * (long long)k32 : cover - K * (long long)w[e];
-                        const bool counts = j + e < m && w[e] != MF_INFEASIBLE;
-                        min_rc = counts && rc < min_rc ? rc : min_rc;
-                    }
-                }
-            }
-        }
-        if (threadIdx.x < CERT_ROWS && i0 + (int)threadIdx.x < n) {          // one thread per row of the group
-            const int i = i0 + threadIdx.x;
-            const long long mine = u[i];
-            if (mine < 0) flags |= 4;
-            dual_part += mine;
-            const int j = row2col[i];
-            if (j != -1) {
-                if (j < 0 || j >= m) flags |= 1;
-                else {
-                    if (atomicAdd(&colmark[j], 1) != 0) flags |= 1;
-                    const int32_t w = W[(size_t)i * ldw + j];
-                    if (w == MF_INFEASIBLE || w < 0) flags |= 2;
-                    else { primal_part += w; matched += 1; }
-                }
-            }
-        }
-    }
-    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < m; j += gridDim.x * blockDim.x) {
-        const long long vj = v[j];
-        if (vj < 0) flags |= 4;
-        dual_part += vj;
-    }
-    // block reductions
-    for (int off = 32; off >= 1; off >>= 1) {
-        const long long o = __shfl_xor(min_rc, off);
-        min_rc = o < min_rc ? o : min_rc;
-        dual_part += __shfl_xor(dual_part, off);
-        primal_part += __shfl_xor(primal_part, off);
-        matched += __shfl_xor(matched, off);
-        flags |= __shfl_xor(flags, off);
-    }
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (lane == 0) red[wave] = min_rc;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int wv = 1; wv < BID_THREADS / 64; ++wv) min_rc = red[wv] < min_rc ? red[wv] : min_rc;
-        atomicMin(&out->min_rc, min_rc);
-        if (primal_part) atomicAdd((unsigned long long *)&out->primal, (unsigned long long)primal_part);
-        if (matched) atomicAdd(&out->matched, matched);
-    }
-    if (lane == 0) {
-        if (dual_part) atomicAdd((unsigned long long *)&out->dual, (unsigned long long)dual_part);
-        if (flags) atomicOr(&out->flags, flags);
-    }
-}
-
-__global__ void fill_int_kernel(int *p, int count, int value)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) p[i] = value;
-}
-
-// Results of a solve that ran in other coordinates (rows and columns in memory order, and/or
-// the transposed problem) handed to the caller: internal row k is the caller's row_ids[k]
-// (k itself without a map), likewise columns; with `flipped` the internal rows are the caller's
-// columns.  d_row2col was filled with -1 before.
-__global__ void map_back_kernel(int rn, int rm, const int32_t *__restrict__ r2c, const int64_t *__restrict__ u,
-                                const int64_t *__restrict__ v, const int32_t *__restrict__ row_ids,
-                                const int32_t *__restrict__ col_ids, int flipped, int32_t *d_row2col,
-                                int64_t *d_u, int64_t *d_v)
-{
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k < rn) {
-        const int rid = row_ids ? row_ids[k] : k;
-        const int c = r2c[k];
-        const int cid = c < 0 ? -1 : (col_ids ? col_ids[c] : c);
-        if (!flipped) { d_row2col[rid] = cid; d_u[rid] = u[k]; }
-        else { d_v[rid] = u[k]; if (cid >= 0) d_row2col[cid] = rid; }
-    }
-    if (k < rm) {
-        const int cid = col_ids ? col_ids[k] : k;
-        if (!flipped) d_v[cid] = v[k]; else d_u[cid] = v[k];
-    }
-}
-
-__global__ void init_cert_kernel(mf_cert_out *out)
-{
-    out->primal = 0; out->dual = 0; out->min_rc = INT64_MAX; out->matched = 0; out->flags = 0;
-}
-
 __global__ void zero_listed_kernel(double *price, const int32_t *__restrict__ which, int count, int m)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1433,15 +588,8 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
         } else if (paths_ok && count <= ctx->path_max && (team_steps >= ctx->path_after || !teams_ok)) {
             // few enough bidders, and chains long enough, to place each bidder by a shortest-path
             // search over the whole device
-            PathBuffers buf{ctx->path_label, ctx->path_expanded, ctx->path_stamp,
-                            {ctx->path_frontier[0], ctx->path_frontier[1]}, ctx->path_held};
-            hipLaunchKernelGGL(path_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats,
-                               (PathCtl *)ctx->path_ctl, ring);
-            const int path_wgs = ctx->path_grid > 0 && ctx->path_grid < ctx->n_cus ? ctx->path_grid : ctx->n_cus;
-            hipLaunchKernelGGL(path_kernel, dim3(path_wgs), dim3(PATH_THREADS), 0, ctx->stream, s,
-                               ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, (PathCtl *)ctx->path_ctl,
-                               buf, ring, ctx->max_n > ctx->max_m ? ctx->max_n : ctx->max_m,
-                               (double)ctx->path_width * s.eps, ctx->path_spin_limit);
+            const int rc = mf_launch_path_search(ctx, s, ring);
+            if (rc != MF_OK) return rc;
             ++ring;
         } else if (!teams_ok || count > team_from) {
             const int grid = count < ctx->chain_grid ? count : ctx->chain_grid;
@@ -1498,30 +646,6 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
 }
 
 }  // namespace
-
-int mf_run_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
-                       const int32_t *d_row2col, const int64_t *d_u, const int64_t *d_v,
-                       int64_t K, mf_result *h_res)
-{
-    hipLaunchKernelGGL(init_cert_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->cert);
-    hipLaunchKernelGGL(fill_int_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, ctx->colmark, m, 0);
-    const int groups = (n + CERT_ROWS - 1) / CERT_ROWS, grid = groups < MAX_GRID ? groups : MAX_GRID;
-    hipLaunchKernelGGL(K >= INT32_MIN && K <= INT32_MAX ? certificate_kernel<true> : certificate_kernel<false>,
-                       dim3(grid), dim3(BID_THREADS), 0, ctx->stream, d_W, ldw, n, m,
-                       d_row2col, d_u, d_v, (long long)K, ctx->colmark, ctx->cert);
-    MF_HIP(hipGetLastError());
-    MF_HIP(hipMemcpyAsync(ctx->h_cert, ctx->cert, sizeof(mf_cert_out), hipMemcpyDeviceToHost, ctx->stream));
-    MF_HIP(hipStreamSynchronize(ctx->stream));
-    const mf_cert_out &c = *ctx->h_cert;
-    h_res->primal = c.primal;
-    h_res->dual = c.dual;
-    h_res->K = K;
-    h_res->min_reduced_cost = c.min_rc == INT64_MAX ? 0 : c.min_rc;
-    h_res->matched = c.matched;
-    const long long gap = c.dual - K * c.primal;
-    h_res->cert_ok = (c.flags == 0 && h_res->min_reduced_cost >= 0 && gap >= 0 && gap < K) ? 1 : 0;
-    return MF_OK;
-}
 
 // `warm`: start from the prices the previous solve of the same shape left in
 // the context (those of the columns listed in d_reset_cols set to 0) and from a
@@ -1665,23 +789,8 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     }
     MF_HIP(hipEventRecord(ctx->ev[4], ctx->stream));
     {
-        const int groups = (rn + 3) / 4, grid = groups < MAX_GRID ? groups : MAX_GRID;
-        if (!flip && !staged) {
-            hipLaunchKernelGGL((duals_kernel<64, 4>), dim3(grid), dim3(64), 0, ctx->stream, A, lda, rn, rm,
-                               ctx->price, ctx->row2col, Kd, d_row2col, d_u, d_v, fwd.line_len);
-        } else {
-            // the solve ran in other coordinates: results go through scratch (the searches' label
-            // arrays are idle now) and are mapped to the caller's rows and columns
-            int64_t *u_int = (int64_t *)ctx->path_label, *v_int = (int64_t *)ctx->path_expanded;
-            hipLaunchKernelGGL((duals_kernel<64, 4>), dim3(grid), dim3(64), 0, ctx->stream, A, lda, rn, rm,
-                               ctx->price, ctx->row2col, Kd, ctx->list[0], u_int, v_int, fwd.line_len);
-            hipLaunchKernelGGL(fill_int_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, d_row2col, n, -1);
-            const int32_t *row_ids = staged ? (flip ? ctx->order_off : ctx->order_on) : nullptr;
-            const int32_t *col_ids = staged ? (flip ? ctx->order_on : ctx->order_off) : nullptr;
-            hipLaunchKernelGGL(map_back_kernel, dim3((nm + 255) / 256), dim3(256), 0, ctx->stream, rn, rm, ctx->list[0],
-                               u_int, v_int, row_ids, col_ids, flip ? 1 : 0, d_row2col, d_u, d_v);
-        }
-        MF_HIP(hipGetLastError());
+        const int rc = mf_extract_duals(ctx, A, lda, rn, rm, Kd, fwd.line_len, n, flip, staged, d_row2col, d_u, d_v);
+        if (rc != MF_OK) return rc;
     }
     MF_HIP(hipEventRecord(ctx->ev[5], ctx->stream));
     MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));

@@ -120,6 +120,18 @@ struct mf_ctx {
     bool score_pending;             // score events recorded but not yet read
 };
 
+// One side of the auction as its kernels see it (rows bidding for columns, or the reverse).
+struct SideArgs {
+    const int32_t *A;                   // the bidding side's lines (W for rows, W^T for columns)
+    long long pitch;
+    int len;
+    double *other_dual;                 // opposite duals as doubles, raised with atomicMax on the bits
+    unsigned long long *otherword;      // opposite packed (dual, holder): the authoritative copy
+    double eps, Kd;
+    const int *line_len;                // optional: every entry of line b at or beyond line_len[b] is infeasible
+    int typical_len;                    // what a scan reads on average (host-side choice of kernels only)
+};
+
 // score.hip
 int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const int32_t *d_type,
                     const float *d_on, int n, const float *d_off, int m, int32_t *d_W, int64_t ldw,
@@ -131,6 +143,11 @@ int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, 
 int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
                   int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res,
                   bool warm, const int32_t *d_reset_cols, int n_reset_cols, bool may_use_staged);
+// paths.hip
+int mf_launch_path_search(mf_ctx *ctx, const SideArgs &s, int ring);
+// certificate.hip
+int mf_extract_duals(mf_ctx *ctx, const int32_t *A, int64_t lda, int rn, int rm, double Kd, const int *line_len,
+                     int n, bool flip, bool staged, int32_t *d_row2col, int64_t *d_u, int64_t *d_v);
 int mf_run_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
                        const int32_t *d_row2col, const int64_t *d_u, const int64_t *d_v,
                        int64_t K, mf_result *h_res);
