@@ -102,7 +102,7 @@ def test_a_search_that_gives_up_hands_back_to_the_chains(mm, orc, polls):
 
 
 @pytest.mark.parametrize("options", [{"phase_stop": 0}, {"phase_stop": 8, "phase_keep": 1},
-                                     {"phase_stop": 64, "phase_keep": 2, "path_after": 0},
+                                     {"phase_stop": 64, "phase_keep": 2, "phase_growth": 4, "path_after": 0},
                                      {"phase_stop": 1 << 20, "phase_keep": 1},
                                      {"phase_stop": 3, "phase_keep": 64}])
 def test_phases_that_end_early_leave_the_optimum_alone(mm, orc, options):
