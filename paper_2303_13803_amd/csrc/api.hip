@@ -140,6 +140,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->type_segment, (size_t)MF_MAX_TYPES + 1));
     TRY(dev_alloc(&ctx->pairs_evaluated, 1));
     TRY(dev_alloc(&ctx->feasible_pairs, 1));
+    TRY(dev_alloc(&ctx->largest_weight, 1));
     TRY(hipHostMalloc((void **)&ctx->h_feasible_pairs, sizeof(unsigned long long)));
     TRY(hipHostMalloc((void **)&ctx->h_pairs_evaluated, sizeof(unsigned long long)));
     TRY(dev_alloc(&ctx->wt, (size_t)max_m * ldt));
@@ -181,7 +182,7 @@ int mf_destroy(mf_ctx *ctx)
     if (!ctx) return MF_ERR_ARG;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->rank_off, ctx->rank_on, ctx->mem_on_sorted, ctx->mem_off_sorted, ctx->fit_len_on, ctx->fit_len_off, ctx->staged, ctx->type_segment, ctx->pairs_evaluated, ctx->feasible_pairs, ctx->wt, ctx->price,
+    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->rank_off, ctx->rank_on, ctx->mem_on_sorted, ctx->mem_off_sorted, ctx->fit_len_on, ctx->fit_len_off, ctx->staged, ctx->type_segment, ctx->pairs_evaluated, ctx->feasible_pairs, ctx->largest_weight, ctx->wt, ctx->price,
                    ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_frontier[0], ctx->path_frontier[1], ctx->path_stamp, ctx->path_held, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);

@@ -495,6 +495,8 @@ __global__ __launch_bounds__(256) void transpose_kernel(const int32_t *__restric
     if ((threadIdx.x & 63) == 0 && mx > stats->max_weight) atomicMax(&stats->max_weight, mx);
 }
 
+__global__ void known_weight_kernel(const int *largest, mf_device_stats *stats) { stats->max_weight = *largest; }
+
 // The largest weight alone (it sets the first epsilon), for solves that may never need W^T.
 __global__ __launch_bounds__(256) void max_weight_kernel(const int32_t *__restrict__ W, int n, int m, int64_t ldw,
                                                          mf_device_stats *stats)
@@ -676,8 +678,12 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         const int chunks = (m + 4095) / 4096 < 4 ? (m + 4095) / 4096 : 4;
         hipLaunchKernelGGL(init_solver_kernel, dim3((nm + 4 + 255) / 256), dim3(256), 0, ctx->stream, rn, rm,
                            ctx->price, ctx->profit, ctx->stats, warm ? 1 : 0);
-        hipLaunchKernelGGL(max_weight_kernel, dim3(chunks, n < 1024 ? n : 1024), dim3(256), 0, ctx->stream, d_W, n, m,
-                           ldw, ctx->stats);
+        // (when the matrix was scored here a moment ago its largest weight was noted on the way)
+        if (candidate && ctx->largest_weight_known)
+            hipLaunchKernelGGL(known_weight_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->largest_weight, ctx->stats);
+        else
+            hipLaunchKernelGGL(max_weight_kernel, dim3(chunks, n < 1024 ? n : 1024), dim3(256), 0, ctx->stream, d_W, n,
+                               m, ldw, ctx->stats);
         MF_HIP(hipGetLastError());
     }
     *ctx->h_feasible_pairs = ~0ull;

@@ -68,6 +68,8 @@ struct mf_ctx {
     unsigned long long *feasible_pairs, *h_feasible_pairs;    // how many pairs of the staged matrix can share (device, pinned)
     int fit_prefix_below;           // percent of pairs that can share below which the solve uses the staged matrix
     int staged_n, staged_m;         // shape of the staged matrix the solver may use (0: none)
+    int *largest_weight;            // largest weight of the matrix just scored (device), noted while it was put in place
+    bool largest_weight_known;      // ... and whether it is that of the matrix the staged copy belongs to
     int32_t *type_segment;          // [MF_MAX_TYPES + 1] first position of each type in order_on
     unsigned long long *pairs_evaluated, *h_pairs_evaluated;   // pairs the last scoring pass ran the MLP on (device, pinned)
     double pairs_total;             // ... out of this many

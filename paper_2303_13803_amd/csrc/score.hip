@@ -154,21 +154,40 @@ __global__ void fit_prefix_kernel(const float *__restrict__ mine, int count, con
     len[k] = lo;
 }
 
+// The placement kernels see every weight once more: they note the largest on the way (the
+// matching's first epsilon is set by it), at most one atomic per workgroup and only when it has
+// news.  Every thread of the NT-thread workgroup calls this.
+template <int NT>
+__device__ inline void note_largest(int mx, int *largest)
+{
+    __shared__ int wave_largest[NT / 64];
+    for (int off = 32; off >= 1; off >>= 1) mx = max(mx, __shfl_xor(mx, off));
+    if ((threadIdx.x & 63) == 0) wave_largest[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int wv = 1; wv < NT / 64; ++wv) mx = max(mx, wave_largest[wv]);
+        // the maximum only grows, so an outdated (smaller) cached value at worst costs a redundant atomic
+        if (mx > *largest) atomicMax(largest, mx);
+    }
+}
+
 // Puts the staged scores in place: W[i][j] = S[rank_on[i]][rank_off[j]].  General form: a row of
 // S is read back in scattered 4-byte pieces, every piece of it by the same workgroup while it
 // sits in the caches.
 __global__ __launch_bounds__(256) void place_kernel(const int32_t *__restrict__ S, int64_t lds,
                                                     const int32_t *__restrict__ rank_on,
                                                     const int32_t *__restrict__ rank_off, int n, int m,
-                                                    int32_t *__restrict__ W, int64_t ldw, int wide_stores)
+                                                    int32_t *__restrict__ W, int64_t ldw, int wide_stores,
+                                                    int *largest)
 {
     const int i = blockIdx.x;
     const int32_t *src = S + (size_t)rank_on[i] * lds;
     int32_t *row = W + (size_t)i * ldw;
+    int mx = 0;                                             // "cannot share" is the smallest integer
     for (int j = (blockIdx.y * 256 + threadIdx.x) * 4; j < m; j += gridDim.y * 1024) {
         int32_t w[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = j + e < m ? src[rank_off[j + e]] : 0;
+        for (int e = 0; e < 4; ++e) { w[e] = j + e < m ? src[rank_off[j + e]] : 0; mx = max(mx, w[e]); }
         if (wide_stores && j + 3 < m) {
             *(int4 *)(row + j) = make_int4(w[0], w[1], w[2], w[3]);
         } else {
@@ -177,6 +196,7 @@ __global__ __launch_bounds__(256) void place_kernel(const int32_t *__restrict__ 
                 if (j + e < m) row[j + e] = w[e];
         }
     }
+    note_largest<256>(mx, largest);
 }
 
 // The same through LDS, for rows of up to PLACE_MAX_COLS entries (measured faster than the
@@ -188,14 +208,20 @@ constexpr int PLACE_MAX_COLS = PLACE_THREADS * PLACE_GROUPS * 4;
 
 __global__ __launch_bounds__(PLACE_THREADS) void place_lds_kernel(
     const int32_t *__restrict__ S, int64_t lds, const int32_t *__restrict__ rank_on,
-    const int32_t *__restrict__ rank_off, int n, int m, int32_t *__restrict__ W, int64_t ldw, int wide_stores)
+    const int32_t *__restrict__ rank_off, int n, int m, int32_t *__restrict__ W, int64_t ldw, int wide_stores,
+    int *largest)
 {
     extern __shared__ int32_t staged[];
     const int i = blockIdx.x, tid = threadIdx.x;
     const int32_t *src = S + (size_t)rank_on[i] * lds;
     int32_t *row = W + (size_t)i * ldw;
-    for (int t = tid * 4; t < m; t += PLACE_THREADS * 4) *(int4 *)(staged + t) = *(const int4 *)(src + t);
-    __syncthreads();
+    int mx = 0;                                             // "cannot share" is the smallest integer
+    for (int t = tid * 4; t < m; t += PLACE_THREADS * 4) {
+        const int4 v = *(const int4 *)(src + t);            // entries beyond m in the last group are 0 or marks
+        *(int4 *)(staged + t) = v;
+        mx = max(max(mx, max(v.x, v.y)), max(v.z, v.w));
+    }
+    note_largest<PLACE_THREADS>(mx, largest);               // passes a barrier: the staged row is complete
 #pragma unroll
     for (int g = 0; g < PLACE_GROUPS; ++g) {
         const int j = (g * PLACE_THREADS + tid) * 4;
@@ -575,6 +601,8 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
     // corner of the tile grid and the kernel leaves them out.  Results land at the same places.
     const bool by_memory = ctx->fit_order && !d_sigma;
     hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->pairs_evaluated);
+    hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->largest_weight);
+    ctx->largest_weight_known = false;
     if (by_memory || typed) order_by_memory(ctx, ctx->mem_on, d_type, n, ctx->order_on, ctx->rank_on);
     const int64_t lds = ((int64_t)m + 3) & ~3ll;
     ctx->staged_n = ctx->staged_m = 0;
@@ -639,12 +667,13 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
                 configured = true;
             }
             hipLaunchKernelGGL(place_lds_kernel, dim3(n), dim3(PLACE_THREADS), sizeof(int32_t) * (size_t)lds, ctx->stream,
-                               ctx->staged, lds, ctx->rank_on, ctx->rank_off, n, m, d_W, ldw, wide);
+                               ctx->staged, lds, ctx->rank_on, ctx->rank_off, n, m, d_W, ldw, wide, ctx->largest_weight);
         } else {
             hipLaunchKernelGGL(place_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->staged, lds,
-                               ctx->rank_on, ctx->rank_off, n, m, d_W, ldw, wide);
+                               ctx->rank_on, ctx->rank_off, n, m, d_W, ldw, wide, ctx->largest_weight);
         }
         MF_HIP(hipGetLastError());
+        ctx->largest_weight_known = true;
     }
     MF_HIP(hipEventRecord(ctx->ev[8], ctx->stream));
     ctx->score_pending = true;
@@ -671,6 +700,7 @@ int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int
 {
     const int H = p->H, F = p->F;
     ctx->staged_n = ctx->staged_m = 0;       // the staged copy no longer matches the matrix
+    ctx->largest_weight_known = false;
     // the lists index device arrays: refuse anything out of range before a kernel trusts it
     hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->colmark);
     if (n_rows > 0)
