@@ -199,36 +199,38 @@ __global__ __launch_bounds__(256) void place_kernel(const int32_t *__restrict__ 
     note_largest<256>(mx, largest);
 }
 
-// The same through LDS, for rows of up to PLACE_MAX_COLS entries (measured faster than the
-// kernel above there, slower beyond): a workgroup per row loads the staged row in whole lines,
-// picks each output's entry out of LDS, and stores the row in whole lines - no scattered access
-// reaches the caches.
-constexpr int PLACE_THREADS = 1024, PLACE_GROUPS = 8;
-constexpr int PLACE_MAX_COLS = PLACE_THREADS * PLACE_GROUPS * 4;
+// The same through LDS, for rows that fit there (measured faster than the kernel above): a
+// workgroup per row loads the staged row in whole lines - only as far as its pairs can share,
+// everything beyond is a mark anyway - picks each output's entry out of LDS, and stores the row
+// in whole lines: no scattered access reaches the caches.
+constexpr int PLACE_THREADS = 1024;
+constexpr size_t PLACE_LDS_BYTES = 159 * 1024;            // of the 160 KB a gfx950 workgroup can have
 
 __global__ __launch_bounds__(PLACE_THREADS) void place_lds_kernel(
     const int32_t *__restrict__ S, int64_t lds, const int32_t *__restrict__ rank_on,
-    const int32_t *__restrict__ rank_off, int n, int m, int32_t *__restrict__ W, int64_t ldw, int wide_stores,
-    int *largest)
+    const int32_t *__restrict__ rank_off, const int32_t *__restrict__ fit_len, int n, int m,
+    int32_t *__restrict__ W, int64_t ldw, int wide_stores, int *largest)
 {
     extern __shared__ int32_t staged[];
     const int i = blockIdx.x, tid = threadIdx.x;
-    const int32_t *src = S + (size_t)rank_on[i] * lds;
+    const int from = rank_on[i];
+    const int32_t *src = S + (size_t)from * lds;
+    const int len = fit_len[from];                          // staged entries at or beyond it are marks
     int32_t *row = W + (size_t)i * ldw;
     int mx = 0;                                             // "cannot share" is the smallest integer
-    for (int t = tid * 4; t < m; t += PLACE_THREADS * 4) {
-        const int4 v = *(const int4 *)(src + t);            // entries beyond m in the last group are 0 or marks
+    for (int t = tid * 4; t < len; t += PLACE_THREADS * 4) {
+        const int4 v = *(const int4 *)(src + t);            // the last group may reach into the marks
         *(int4 *)(staged + t) = v;
         mx = max(max(mx, max(v.x, v.y)), max(v.z, v.w));
     }
     note_largest<PLACE_THREADS>(mx, largest);               // passes a barrier: the staged row is complete
-#pragma unroll
-    for (int g = 0; g < PLACE_GROUPS; ++g) {
-        const int j = (g * PLACE_THREADS + tid) * 4;
-        if (j >= m) break;
+    for (int j = tid * 4; j < m; j += PLACE_THREADS * 4) {
         int32_t w[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = j + e < m ? staged[rank_off[j + e]] : 0;
+        for (int e = 0; e < 4; ++e) {
+            const int p = rank_off[min(j + e, m - 1)];
+            w[e] = j + e < m ? (p < len ? staged[p] : MF_INFEASIBLE) : 0;
+        }
         if (wide_stores && j + 3 < m) {
             *(int4 *)(row + j) = make_int4(w[0], w[1], w[2], w[3]);
         } else {
@@ -659,15 +661,16 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
     if (by_memory) {
         const int chunks = (m + 4095) / 4096 < 16 ? (m + 4095) / 4096 : 16;
         const int wide = ((uintptr_t)d_W & 15u) == 0 && (ldw & 3) == 0;
-        if (m <= PLACE_MAX_COLS) {
+        if ((size_t)lds * sizeof(int32_t) <= PLACE_LDS_BYTES) {
             static bool configured = false;
             if (!configured) {
                 MF_HIP(hipFuncSetAttribute((const void *)place_lds_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)(sizeof(int32_t) * PLACE_MAX_COLS)));
+                                           (int)PLACE_LDS_BYTES));
                 configured = true;
             }
             hipLaunchKernelGGL(place_lds_kernel, dim3(n), dim3(PLACE_THREADS), sizeof(int32_t) * (size_t)lds, ctx->stream,
-                               ctx->staged, lds, ctx->rank_on, ctx->rank_off, n, m, d_W, ldw, wide, ctx->largest_weight);
+                               ctx->staged, lds, ctx->rank_on, ctx->rank_off, ctx->fit_len_on, n, m, d_W, ldw, wide,
+                               ctx->largest_weight);
         } else {
             hipLaunchKernelGGL(place_kernel, dim3(n, chunks), dim3(256), 0, ctx->stream, ctx->staged, lds,
                                ctx->rank_on, ctx->rank_off, n, m, d_W, ldw, wide, ctx->largest_weight);
