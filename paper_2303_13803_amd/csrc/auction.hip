@@ -107,6 +107,7 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const 
     if (threadIdx.x == 0) s_active = 0x7fffffff;
     const int count = stats->cnt[ring & 3];
     unsigned long long steps = 0, retries = 0, scanned = 0;
+    bool handing_back = false;              // block-uniform
     for (;;) {
         __syncthreads();
         if (threadIdx.x == 0) s_next = atomicAdd(&stats->head, 1);
@@ -114,6 +115,10 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const 
         const int item = s_next;
         if (item >= count) break;
         int b = list[item];
+        if (handing_back) {                 // pass on what nobody will bid for in this launch
+            if (threadIdx.x == 0) out_list[atomicAdd(&stats->cnt[(ring + 1) & 3], 1)] = b;
+            continue;
+        }
         bool fresh = false;                 // re-read the duals past the caches after a bid that lost
         while (b >= 0) {
             if ((steps & 3) == 0) {         // now and then: how many workgroups still follow a chain?
@@ -124,6 +129,7 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const 
             }
             if ((long long)steps >= step_cap || s_active <= hand_back_at) {
                 if (threadIdx.x == 0) out_list[atomicAdd(&stats->cnt[(ring + 1) & 3], 1)] = b;
+                handing_back = true;
                 break;
             }
             ++steps;
@@ -138,7 +144,8 @@ __global__ __launch_bounds__(CHAIN_THREADS) void chain_kernel(SideArgs s, const 
             if (fresh && threadIdx.x == 0) ++retries;
             b = s_next;
         }
-        if (b >= 0) break;                  // handed back: take no further bidder
+        // handed back: follow no further chain, but keep emptying the list - if every workgroup
+        // stopped here, entries nobody had claimed yet would never reach the next launch
     }
     if (threadIdx.x == 0) {
         atomicAdd(&stats->active, -1);      // this workgroup follows no chain any more

@@ -42,6 +42,12 @@ constexpr int PATH_FRONTIER_LOW = 128, PATH_FRONTIER_HIGH = 1024;
 struct alignas(128) PathCtl {
     unsigned long long sink;        // shortest complete path: length << 21 | kind << 20 | id (kind 1: row id gives up)
     unsigned long long low[3];      // smallest label still to be expanded, per slot
+    // Complete paths found during a step, per slot like `low`: `sink` above moves while a step
+    // runs, so two workgroups reading it at the top of the same step may see different values;
+    // whether the search is over must not depend on that, or they would leave it at different
+    // barriers.  Every workgroup folds the slot the previous step filled (nobody writes it any
+    // more) into a running minimum of its own, and all take the decision from that.
+    unsigned long long sink_found[3];
     // best value of the current bidder (bits of a double), by parity of its position in the list:
     // when a bidder rests, workgroup 0 may already be writing the next bidder's value while a
     // slower workgroup has yet to read this one
@@ -160,6 +166,9 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                 store_through(&ctl->low[0], PATH_INF);
                 store_through(&ctl->low[1], PATH_INF);
                 store_through(&ctl->low[2], PATH_INF);
+                store_through(&ctl->sink_found[0], PATH_INF);
+                store_through(&ctl->sink_found[1], PATH_INF);
+                store_through(&ctl->sink_found[2], PATH_INF);
                 if (v1 > s.eps) {                                       // pi_r = v1 - eps: rc(r, best column) = 0
                     store_through(&ctl->sink, ((unsigned long long)(long long)(v1 - s.eps) << 21) | (1ull << 20) |
                                                   (unsigned long long)r0);
@@ -174,6 +183,9 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         const double v1 = __longlong_as_double((long long)load_fresh_u64(&ctl->first_value[item & 1]));
         if (v1 <= s.eps) continue;                                      // rests with dual 0: nothing to move
         const double first_profit = v1 - s.eps;
+        // shortest complete path every workgroup agrees on: first "the bidder rests", as workgroup 0 wrote it
+        unsigned long long agreed_sink = ((unsigned long long)(long long)first_profit << 21) | (1ull << 20) |
+                                         (unsigned long long)r0;
 
         // ---- label-correcting search, one grid barrier per super-step ----
         // A step scans the rows on the current frontier; a label that falls inside the window
@@ -209,11 +221,16 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
             }
             __syncthreads();
             const int nf = step == 1u ? 1 : (int)s_first[PATH_SEGMENTS];
-            const unsigned long long sink_word = load_fresh_u64(&ctl->sink);
+            if (step > 1u) {
+                const unsigned long long found = load_fresh_u64(&ctl->sink_found[c]);
+                agreed_sink = found < agreed_sink ? found : agreed_sink;
+            }
+            // pruning may use whatever is known by now; decisions all workgroups must share may not
+            const unsigned long long sink_word = min(agreed_sink, load_fresh_u64(&ctl->sink));
             const double bound = (double)(long long)(sink_word >> 21);
             if (step > 1u && swept && nf == 0) {
                 const unsigned long long lo = load_fresh_u64(&ctl->low[c]);
-                if (lo == PATH_INF || lo >= (sink_word >> 21)) break;       // every label below the sink is final
+                if (lo == PATH_INF || lo >= (agreed_sink >> 21)) break;     // every label below the sink is final
                 low = (double)(long long)lo;                                // move the window to the next label
             }
             if (nf > PATH_FRONTIER_HIGH) width = fmax(s.eps, width * 0.5);
@@ -221,7 +238,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
             const double limit = fmin(low + width, bound);
             if (gtid < PATH_SEGMENTS)
                 __hip_atomic_store(&ctl->seg[z][gtid].count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (gtid == 0) store_through(&ctl->low[z], PATH_INF);
+            if (gtid == 0) { store_through(&ctl->low[z], PATH_INF); store_through(&ctl->sink_found[z], PATH_INF); }
             const int *frontier = buf.fr_col[step & 1u];
             int *next_frontier = buf.fr_col[(step + 1u) & 1u];
 
@@ -266,9 +283,12 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                         if (sl == 0 && lane == 0) {
                             store_through(&buf.expanded[mine_col], lw >> MF_ID_BITS);
                             __hip_atomic_store(&buf.held[i], mine_col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            if (dist + profit < bound)                      // it may also give up and rest
-                                atomicMin(&ctl->sink, ((unsigned long long)(long long)(dist + profit) << 21) |
-                                                          (1ull << 20) | (unsigned long long)i);
+                            if (dist + profit < bound) {                    // it may also give up and rest
+                                const unsigned long long rests = ((unsigned long long)(long long)(dist + profit) << 21) |
+                                                                 (1ull << 20) | (unsigned long long)i;
+                                atomicMin(&ctl->sink, rests);
+                                atomicMin(&ctl->sink_found[p], rests);
+                            }
                         }
                     }
                     const int32_t *row = s.A + (size_t)i * s.pitch;
@@ -291,10 +311,12 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                                 // search and the caches were emptied at its start): a safe first test
                                 if (mine < buf.label[k + q] && atomicMin(&buf.label[k + q], mine) > mine && cand < limit &&
                                     atomicExch(&buf.stamp[k + q], step) != step) {
-                                    if (word_id(load_fresh_u64(&s.otherword[k + q])) < 0)    // a column nobody holds ends a path
-                                        atomicMin(&ctl->sink, (unsigned long long)(long long)cand << 21 |
-                                                                  (unsigned long long)(k + q));
-                                    else push(k + q);
+                                    if (word_id(load_fresh_u64(&s.otherword[k + q])) < 0) {  // a column nobody holds ends a path
+                                        const unsigned long long ends = (unsigned long long)(long long)cand << 21 |
+                                                                        (unsigned long long)(k + q);
+                                        atomicMin(&ctl->sink, ends);
+                                        atomicMin(&ctl->sink_found[p], ends);
+                                    } else push(k + q);
                                 }
                             }
                         }
@@ -325,7 +347,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
             const unsigned pushed = min(s_pushes, (unsigned)PATH_PUSH_BUFFER);
             if (tid == 0) {
                 s_base = pushed ? atomicAdd(&ctl->seg[p][segment].count, pushed) : 0u;
-                if (s_sink != PATH_INF) atomicMin(&ctl->sink, s_sink);
+                if (s_sink != PATH_INF) { atomicMin(&ctl->sink, s_sink); atomicMin(&ctl->sink_found[p], s_sink); }
                 if (s_low != PATH_INF) atomicMin(&ctl->low[p], s_low);
             }
             __syncthreads();
