@@ -172,6 +172,39 @@ int mf_check_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t 
                          int64_t K, mf_result *h_res);
 
 /*
+ * The same check for callers that cannot allocate device memory or create a
+ * context at the point of the call: code running under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  It needs no context
+ * and calls no allocating routine: the partial sums and the per-column marks
+ * live in an array that is part of the library's image on every device
+ * (256 bytes + 4 bytes per column, 256 KiB in all, held until the process
+ * ends), so m is limited to MF_NOALLOC_MAX_COLS (MF_ERR_SHAPE beyond it, and
+ * for n above 2^20 - 2); arguments are otherwise as above (MF_ERR_ARG for a
+ * null pointer, a pitch that is not a multiple of 4, a d_W that is not
+ * 16-byte aligned, K < 1).  The work is enqueued on `hip_stream` (a
+ * hipStream_t, NULL = the default stream) of the CURRENT device and the call
+ * returns without waiting; the result is written to *d_out, a DEVICE buffer
+ * the caller owns, once the stream gets there.  The array is cleared by a
+ * kernel at the start of each call (no memset node is recorded).  All calls
+ * on one device share the one array: calls that overlap on a device (two
+ * streams, two threads) race and must be serialised by the caller.
+ */
+#define MF_NOALLOC_MAX_COLS 65536
+typedef struct {
+    int64_t primal;             /* sum of matched weights                               */
+    int64_t dual;               /* sum u + sum v                                        */
+    int64_t K;                  /* as passed                                            */
+    int64_t min_reduced_cost;   /* min over feasible (i,j) of u_i + v_j - K*W_ij        */
+    int32_t matched;            /* rows with a partner                                  */
+    int32_t flags;              /* bit 0 bad or duplicate column, 1 infeasible pair, 2 negative dual */
+    int32_t cert_ok;            /* 1: matching valid, duals feasible, 0 <= D - K*P < K  */
+    int32_t reserved;
+} mf_certificate;
+int mf_check_certificate_noalloc(void *hip_stream, const int32_t *d_W, int n, int m, int64_t ldw,
+                                 const int32_t *d_row2col, const int64_t *d_u, const int64_t *d_v,
+                                 int64_t K, mf_certificate *d_out);
+
+/*
  * One scheduling round: mf_score_pairs into d_W, then mf_solve_assignment on
  * it.  Returns MF_ERR_CERT if the certificate does not verify.
  */

@@ -17,7 +17,7 @@ INFEASIBLE = -2147483648
 OK, ERR_ARG, ERR_SHAPE, ERR_HIP, ERR_NOT_CONVERGED, ERR_CERT, ERR_RANGE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["mf_create", "mf_destroy", "mf_score_pairs", "mf_solve_assignment",
-           "mf_check_certificate", "mf_schedule_round", "mf_schedule_round_update", "mf_score_pairs_typed",
+           "mf_check_certificate", "mf_check_certificate_noalloc", "mf_schedule_round", "mf_schedule_round_update", "mf_score_pairs_typed",
            "mf_schedule_round_typed", "mf_set_option", "mf_last_timings", "mf_measure_ceilings",
            "mf_strerror", "mf_last_hip_error"]
 
@@ -48,6 +48,14 @@ class Result(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
+class Certificate(C.Structure):
+    _fields_ = [("primal", C.c_int64), ("dual", C.c_int64), ("K", C.c_int64), ("min_reduced_cost", C.c_int64),
+                ("matched", C.c_int32), ("flags", C.c_int32), ("cert_ok", C.c_int32), ("reserved", C.c_int32)]
+
+
+NOALLOC_MAX_COLS = 65536
+
+
 def load_library():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2303_13803_amd/build.py` "
@@ -59,6 +67,7 @@ def load_library():
     lib.mf_score_pairs.argtypes = [vp, C.POINTER(Predictor), vp, i32, vp, i32, vp, i64, vp]
     lib.mf_solve_assignment.argtypes = [vp, vp, i32, i32, i64, vp, vp, vp, C.POINTER(Result)]
     lib.mf_check_certificate.argtypes = [vp, vp, i32, i32, i64, vp, vp, vp, i64, C.POINTER(Result)]
+    lib.mf_check_certificate_noalloc.argtypes = [vp, vp, i32, i32, i64, vp, vp, vp, i64, vp]
     lib.mf_schedule_round.argtypes = [vp, C.POINTER(Predictor), vp, i32, vp, i32, vp, i64, vp, vp, vp,
                                       C.POINTER(Result)]
     lib.mf_schedule_round_update.argtypes = [vp, C.POINTER(Predictor), vp, i32, vp, i32, vp, i32, vp, i32, vp, i64,
@@ -212,6 +221,23 @@ class Context:
         arr = (C.c_float * 16)()
         self._check(_lib.mf_last_timings(self._h, C.byref(arr)))
         return {name: float(arr[i]) for i, name in enumerate(TIMING_NAMES)}
+
+
+def check_certificate_noalloc(W, n, m, row2col, u, v, K, out, stream=None):
+    """mf_check_certificate_noalloc on the current device: `out` is a uint8 device tensor of
+    ctypes.sizeof(Certificate) bytes that receives the result once `stream` gets there
+    (read it with read_certificate after synchronising).  Returns the call's status code."""
+    if not out.is_cuda or out.dtype != torch.uint8 or out.numel() < C.sizeof(Certificate) or not out.is_contiguous():
+        raise TypeError("out: a contiguous uint8 device tensor of at least sizeof(Certificate) bytes")
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return _lib.mf_check_certificate_noalloc(C.c_void_p(s.cuda_stream), _ptr(W, torch.int32), int(n), int(m),
+                                             W.stride(0), _ptr(row2col, torch.int32), _ptr(u, torch.int64),
+                                             _ptr(v, torch.int64), int(K), out.data_ptr())
+
+
+def read_certificate(out):
+    """The Certificate a finished mf_check_certificate_noalloc left in `out` (copies it to the host)."""
+    return Certificate.from_buffer_copy(out.cpu().numpy().tobytes()[:C.sizeof(Certificate)])
 
 
 def strerror(code):

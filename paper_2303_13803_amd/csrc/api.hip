@@ -375,7 +375,7 @@ const char *mf_strerror(int code)
     switch (code) {
     case MF_OK: return "ok";
     case MF_ERR_ARG: return "bad argument (null pointer, non-positive size, pitch or alignment)";
-    case MF_ERR_SHAPE: return "shape larger than the context was created for";
+    case MF_ERR_SHAPE: return "shape larger than the context was created for (or than the call supports)";
     case MF_ERR_HIP: return "HIP runtime error";
     case MF_ERR_NOT_CONVERGED: return "round limit reached before the auction finished";
     case MF_ERR_CERT: return "optimality certificate did not verify";

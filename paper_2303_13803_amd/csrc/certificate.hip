@@ -2,6 +2,7 @@
 // problem (paper: Section "Matching-based scheduling" states the problem whose optimum is asked
 // for) and the certificate that matching and duals are optimal together.
 #include "scan.h"
+#include <mutex>
 
 namespace {
 
@@ -228,4 +229,74 @@ int mf_extract_duals(mf_ctx *ctx, const int32_t *A, int64_t lda, int rn, int rm,
     }
     MF_HIP(hipGetLastError());
     return MF_OK;
+}
+
+namespace {
+
+// ---- the same certificate for callers that cannot allocate ----
+// Everything mf_check_certificate keeps in context scratch (the partial sums and the per-column
+// use marks) lives here in one array that is part of the library's image on every device.
+// In host code the array's name is only a handle: what kernels, copies and fills get is the
+// device address looked up once per device.
+constexpr int NOALLOC_HEADER_BYTES = 256;           // an mf_cert_out, padded
+static __device__ __align__(256) unsigned char scratch[NOALLOC_HEADER_BYTES + 4 * MF_NOALLOC_MAX_COLS];
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex noalloc_lock;
+unsigned char *noalloc_ptr[NOALLOC_MAX_DEVICES];    // scratch's address on each device (null: not looked up yet)
+
+__global__ void noalloc_begin_kernel(mf_cert_out *out, int *colmark, int m)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < m) colmark[j] = 0;
+    if (j == 0) { out->primal = 0; out->dual = 0; out->min_rc = INT64_MAX; out->matched = 0; out->flags = 0; }
+}
+
+__global__ void noalloc_finish_kernel(const mf_cert_out *in, long long K, mf_certificate *d_out)
+{
+    const long long min_rc = in->min_rc == INT64_MAX ? 0 : in->min_rc;
+    const long long gap = in->dual - K * in->primal;
+    d_out->primal = in->primal;
+    d_out->dual = in->dual;
+    d_out->K = K;
+    d_out->min_reduced_cost = min_rc;
+    d_out->matched = in->matched;
+    d_out->flags = in->flags;
+    d_out->cert_ok = (in->flags == 0 && min_rc >= 0 && gap >= 0 && gap < K) ? 1 : 0;
+    d_out->reserved = 0;
+}
+
+}  // namespace
+
+extern "C" int mf_check_certificate_noalloc(void *hip_stream, const int32_t *d_W, int n, int m, int64_t ldw,
+                                            const int32_t *d_row2col, const int64_t *d_u, const int64_t *d_v,
+                                            int64_t K, mf_certificate *d_out)
+{
+    if (!d_W || !d_row2col || !d_u || !d_v || !d_out || n <= 0 || m <= 0 || ldw < m || (ldw & 3) ||
+        ((uintptr_t)d_W & 15u) || K < 1)
+        return MF_ERR_ARG;
+    if (m > MF_NOALLOC_MAX_COLS || n > MF_MAX_DIM) return MF_ERR_SHAPE;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= NOALLOC_MAX_DEVICES) return MF_ERR_HIP;
+    unsigned char *base = nullptr;
+    {
+        std::lock_guard<std::mutex> hold(noalloc_lock);
+        if (!noalloc_ptr[device]) {
+            void *p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MF_ERR_HIP;
+            noalloc_ptr[device] = (unsigned char *)p;
+        }
+        base = noalloc_ptr[device];
+    }
+    mf_cert_out *out = (mf_cert_out *)base;
+    int *colmark = (int *)(base + NOALLOC_HEADER_BYTES);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    // the array keeps what the previous call left: both parts are cleared by a kernel (no
+    // memset node, so the sequence can be captured into a graph)
+    hipLaunchKernelGGL(noalloc_begin_kernel, dim3((m + 255) / 256), dim3(256), 0, stream, out, colmark, m);
+    const int groups = (n + CERT_ROWS - 1) / CERT_ROWS, grid = groups < MAX_GRID ? groups : MAX_GRID;
+    hipLaunchKernelGGL(K <= INT32_MAX ? certificate_kernel<true> : certificate_kernel<false>, dim3(grid),
+                       dim3(BID_THREADS), 0, stream, d_W, ldw, n, m, d_row2col, d_u, d_v, (long long)K, colmark, out);
+    hipLaunchKernelGGL(noalloc_finish_kernel, dim3(1), dim3(1), 0, stream, out, (long long)K, d_out);
+    return hipGetLastError() == hipSuccess ? MF_OK : MF_ERR_HIP;
 }
