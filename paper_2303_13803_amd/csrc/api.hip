@@ -97,6 +97,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->phase_stop = 16;
     ctx->phase_keep = 4;
     ctx->phase_growth = 1;
+    ctx->final_jump = 0;
     ctx->warm_eps_units = 0;
     ctx->warm_reset_cols = true;
     ctx->chain_grid = 256;
@@ -111,6 +112,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->fit_prefix_below = 50;
     ctx->path_max = 16;
     ctx->path_width = 1024;
+    ctx->path_frontier_rows = 1024;
     ctx->path_grid = 0;
     ctx->path_after = 256;
     ctx->path_spin_limit = 1u << 22;
@@ -151,7 +153,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->row2col, nm));
     TRY(dev_alloc(&ctx->col2row, nm));
     TRY(hipMalloc(&ctx->team_ctl, 128 * 1024));
-    TRY(hipMalloc(&ctx->path_ctl, 16384));
+    TRY(hipMalloc(&ctx->path_ctl, 32768));
     TRY(dev_alloc(&ctx->path_label, nm));
     TRY(dev_alloc(&ctx->path_expanded, nm));
     for (int k = 0; k < 2; ++k) {
@@ -335,6 +337,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!ctx || !name) return MF_ERR_ARG;
     if (!strcmp(name, "theta")) { if (value < 2 || value > 1024) return MF_ERR_ARG; ctx->theta = value; return MF_OK; }
     if (!strcmp(name, "phase_keep")) { if (value < 1 || value > 64) return MF_ERR_ARG; ctx->phase_keep = (int)value; return MF_OK; }
+    if (!strcmp(name, "final_jump")) { if (value < 0 || value > (1 << 30)) return MF_ERR_ARG; ctx->final_jump = value; return MF_OK; }
     if (!strcmp(name, "phase_growth")) { if (value < 1 || value > 64) return MF_ERR_ARG; ctx->phase_growth = (int)value; return MF_OK; }
     if (!strcmp(name, "phase_stop")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->phase_stop = (int)value; return MF_OK; }
     if (!strcmp(name, "tail_max")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->tail_max = (int)value; return MF_OK; }
@@ -347,10 +350,11 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "team_size")) { if (value < 2 || value > 32) return MF_ERR_ARG; ctx->team_size = (int)value; return MF_OK; }
     if (!strcmp(name, "team_threads")) { if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return MF_ERR_ARG; ctx->team_threads = (int)value; return MF_OK; }
     if (!strcmp(name, "chain_grid")) { if (value < 1 || value > 4096) return MF_ERR_ARG; ctx->chain_grid = (int)value; return MF_OK; }
-    if (!strcmp(name, "path_max")) { if (value < 0 || value > 4096) return MF_ERR_ARG; ctx->path_max = (int)value; return MF_OK; }
+    if (!strcmp(name, "path_max")) { if (value < 0 || value > 64) return MF_ERR_ARG; ctx->path_max = (int)value; return MF_OK; }
     if (!strcmp(name, "path_spin_limit")) { if (value < 0 || value > (1ll << 30)) return MF_ERR_ARG; ctx->path_spin_limit = (unsigned)value; ctx->path_off = false; return MF_OK; }
     if (!strcmp(name, "path_after")) { if (value < 0) return MF_ERR_ARG; ctx->path_after = value; return MF_OK; }
     if (!strcmp(name, "path_grid")) { if (value < 0 || value > 1024) return MF_ERR_ARG; ctx->path_grid = (int)value; return MF_OK; }
+    if (!strcmp(name, "path_frontier_rows")) { if (value < 8 || value > (1 << 20)) return MF_ERR_ARG; ctx->path_frontier_rows = (int)value; return MF_OK; }
     if (!strcmp(name, "path_width")) { if (value < 1 || value > (1 << 30)) return MF_ERR_ARG; ctx->path_width = (int)value; return MF_OK; }
     if (!strcmp(name, "fit_prefix_below")) { if (value < 0 || value > 101) return MF_ERR_ARG; ctx->fit_prefix_below = (int)value; return MF_OK; }
     if (!strcmp(name, "fit_prefix")) { ctx->fit_prefix = value != 0; return MF_OK; }

@@ -739,11 +739,27 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     SideArgs rev{At, (long long)ldat, rn, ctx->profit, ctx->roword, 0.0, Kd, flip ? len_rows : len_cols,
                  (int)(feasible / (double)rm)};
 
-    long long eps = cmax / ctx->theta;
-    if (warm && ctx->warm_eps_units * K < eps) eps = ctx->warm_eps_units * K;
-    if (eps < 1) eps = 1;
+    // The ladder of epsilons: divided by theta per phase down to 1.  Once epsilon is at most
+    // final_jump weight units (final_jump * K in dual units) the next phase is the last one:
+    // prices that good leave the phase at epsilon = 1 about one bid per row, and the phases in
+    // between would each cost a full re-bid and a tail of their own.
+    long long ladder[64];
+    int n_phases = 0;
+    {
+        long long e = cmax / ctx->theta;
+        if (warm && ctx->warm_eps_units * K < e) e = ctx->warm_eps_units * K;
+        if (e < 1) e = 1;
+        for (;;) {
+            ladder[n_phases++] = e;
+            if (e == 1 || n_phases == 64) break;
+            long long next = e / ctx->theta;
+            if (next < 1 || (ctx->final_jump > 0 && e <= ctx->final_jump * K) || n_phases == 63) next = 1;
+            e = next;
+        }
+    }
     int phases = 0;
-    for (;;) {
+    for (int ph = 0; ph < n_phases; ++ph) {
+        const long long eps = ladder[ph];
         ++phases;
         fwd.eps = rev.eps = (double)eps;
         hipLaunchKernelGGL(reset_kernel, dim3((nm + 255) / 256), dim3(256), 0, ctx->stream, rn, rm, ctx->price,
@@ -755,8 +771,8 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         // them settles what was left open, the last one is what makes the result exact.  The
         // second side runs whenever more columns than that are unused and still priced - skipping
         // it would carry their prices into ever finer phases, where taking them off costs far more.
-        int left_over = 0, phases_after = 0;
-        for (long long e = eps; e > 1; ++phases_after) { e /= ctx->theta; if (e < 1) e = 1; }
+        int left_over = 0;
+        const int phases_after = n_phases - 1 - ph;
         // The coarser the phase, the more may be left (phase_growth times more per phase), but
         // never more than one bidder in 64: small problems complete every phase.
         long long stop_ll = 0;
@@ -796,9 +812,6 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
                                A, lda, Kd, ctx->roword, ctx->price, ctx->row2col, ctx->col2row);
             MF_HIP(hipGetLastError());
         }
-        if (eps == 1) break;
-        eps /= ctx->theta;
-        if (eps < 1) eps = 1;
     }
     MF_HIP(hipEventRecord(ctx->ev[4], ctx->stream));
     {

@@ -86,6 +86,7 @@ struct mf_ctx {
     int phase_stop;                 // unplaced bidders at or below which a phase that only prepares prices ends
     int phase_growth;               // ... times this for every phase further from the ones that run to the end
     int phase_keep;                 // the last so many phases always run to the end
+    long long final_jump;           // epsilon (weight units) at or below which the next phase is the last (0: never)
     int tail_max;                   // bidder count at or below which chains are followed in one kernel
     int bulk_shape;                 // workgroup shape of rounds with many bidders (see launch_round)
     int team_max;                   // chains at or below which several workgroups share each chain (0: never)
@@ -103,6 +104,7 @@ struct mf_ctx {
     long long path_after;           // chain steps per run after which the searches take over
     int path_grid;                  // workgroups of a search (0: one per compute unit)
     int path_width;                 // label window of one super-step, in epsilons
+    int path_frontier_rows;         // frontier above which the window is halved (doubled below an eighth of it)
     unsigned path_spin_limit;       // polls a workgroup waits at a barrier of the search before it gives up
     bool path_off;                  // set after a wait of the search ran out
     int n_cus;                      // compute units of the device

@@ -7,51 +7,58 @@
 namespace {
 
 // A chain of bids is a greedy walk: every evicted holder moves to its own best
-// alternative, and with one or two bidders left such a walk takes thousands of
+// alternative, and with a few bidders left such a walk takes thousands of
 // dependent steps to reach a free line.  The shortest way to make room is far
 // shorter in hops, and finding it is a breadth-type search whose every step is
-// wide.  For a bidder r, in the notation of the header of auction.hip with
-// "rows" the bidding side, let rc(i,k) = pi_i + p_k - K W_ik + eps >= 0 (I1)
-// for every assigned row i and for r (pi_r = best value of r - eps); assigned
-// pairs have rc = eps.  A path r -> k1, holder(k1) -> k2, ... that ends in a
-// column nobody holds, or in a row giving up its column for profit 0 (at extra
-// length pi_i), frees a place for r; label(k) is the length sum(rc) of the
-// shortest such path to column k and d the length of the shortest complete
-// one.  Raising p_k by d - label(k) on every column with label(k) < d (their
-// holders' profits drop by as much) keeps I1 and I2 and makes the shortest
-// path tight; re-assigning along it, each row paying eps more for its new
-// column, keeps them too and leaves one bidder fewer.  Prices only rise, so
-// this mixes freely with bids.  (The successive-shortest-path step of the
-// Hungarian method, on costs relaxed by eps.)
+// wide.  In the notation of the header of auction.hip with "rows" the bidding
+// side, let rc(i,k) = pi_i + p_k - K W_ik + eps >= 0 (I1) for every assigned
+// row i and for every bidder r (pi_r = best value of r - eps); assigned pairs
+// have rc = eps.  A path r -> k1, holder(k1) -> k2, ... that ends in a column
+// nobody holds, or in a row giving up its column for profit 0 (at extra length
+// pi_i), frees a place for r; label(k) is the length sum(rc) of the shortest
+// such path to column k from ANY bidder still to be placed, and the columns
+// whose shortest path starts at bidder a form a's tree.  When the nearest end
+// of a path, at length d, is final, it belongs to one tree: raising p_k by
+// d - label(k) on that tree's columns with label(k) < d (their holders' profits
+// drop by as much) keeps I1 and I2 and makes the path tight; re-assigning
+// along it, each row paying eps more for its new column, keeps them too and
+// leaves one bidder fewer.  (The successive-shortest-path step of the Hungarian
+// method, on costs relaxed by eps, with every unplaced bidder a root at once.)
+// The search then goes on for the others: their trees, labels and pending
+// updates stay as they are - a later, longer path only raises what an earlier
+// one left - while the served tree's columns lose their labels and are reached
+// again, at prices already raised, from the rows the other trees have scanned
+// (all of which are scanned once more).  Searching for one bidder after another
+// instead would label the same few thousand columns again for each of them:
+// measured on cluster-scale rounds, successive trees share nine columns in ten.
+// Prices only rise, so this mixes freely with bids.
 //
 // All compute units run the search together: labels are corrected in
 // super-steps - every row whose column's label dropped into the current
 // window [low, low + width) is scanned against all columns, in parallel, with
-// an atomic minimum per improved label - separated by grid-wide barriers.
-// Data shared between workgroups moves only through atomics and uncached
-// loads/stores.  Every wait is bounded; if one runs out all workgroups leave,
-// nothing half-done (the price update alone is a valid state), and the host
-// falls back to the chain kernels.
+// an atomic compare-and-swap per improved label - separated by grid-wide
+// barriers.  Data shared between workgroups moves only through atomics and
+// uncached loads/stores.  Every wait is bounded; if one runs out all
+// workgroups leave, nothing half-done, and the host falls back to the chain
+// kernels.
 constexpr int PATH_THREADS = 1024;
 constexpr int PATH_MAX_SLICES = 1024;
 constexpr int PATH_GROUP = 16, PATH_MAX_GROUPS = 64;      // up to 1024 workgroups
 constexpr int PATH_SEGMENTS = 16, PATH_PUSH_BUFFER = 4096;
 constexpr unsigned long long PATH_INF = ~0ull;
-constexpr int PATH_FRONTIER_LOW = 128, PATH_FRONTIER_HIGH = 1024;
+constexpr int PATH_MAX_SOURCES = 64;                      // bidders one search places
+constexpr unsigned PATH_IN_TREE = 0xffffffffu;            // stamp of a column of the tree being served
 
 struct alignas(128) PathCtl {
-    unsigned long long sink;        // shortest complete path: length << 21 | kind << 20 | id (kind 1: row id gives up)
+    unsigned long long sink;        // nearest end of a path found so far: length << 21 | kind << 20 | id (kind 1: row id gives up)
     unsigned long long low[3];      // smallest label still to be expanded, per slot
-    // Complete paths found during a step, per slot like `low`: `sink` above moves while a step
+    // Ends of paths found during a step, per slot like `low`: `sink` above moves while a step
     // runs, so two workgroups reading it at the top of the same step may see different values;
-    // whether the search is over must not depend on that, or they would leave it at different
-    // barriers.  Every workgroup folds the slot the previous step filled (nobody writes it any
-    // more) into a running minimum of its own, and all take the decision from that.
+    // what all workgroups must decide alike (a path end is final) must not depend on that, or
+    // they would arrive at different barriers.  Every workgroup folds the slot the previous step
+    // filled (nobody writes it any more) into a running minimum of its own and decides from that.
     unsigned long long sink_found[3];
-    // best value of the current bidder (bits of a double), by parity of its position in the list:
-    // when a bidder rests, workgroup 0 may already be writing the next bidder's value while a
-    // slower workgroup has yet to read this one
-    unsigned long long first_value[2];
+    unsigned long long src_profit[PATH_MAX_SOURCES];     // bits of a double: best value - eps of each bidder (<= 0: it rests)
     // The barrier's two hot words each have a cache line to themselves: hundreds of polling loads
     // on the line of a counter that is being incremented (or of the sink above) slow both down.
     struct alignas(128) { unsigned int count; } arrive;       // whole groups that have arrived at barriers so far
@@ -65,6 +72,7 @@ struct alignas(128) PathCtl {
     // workgroup finished reading before the barrier that ended step t - 1.
     struct alignas(128) { unsigned int count; } seg[3][PATH_SEGMENTS];
 };
+static_assert(sizeof(PathCtl) <= 32768, "the context allocates 32 KiB for this block");
 
 struct PathBuffers {
     unsigned long long *label;      // [len] length << 20 | predecessor row
@@ -130,276 +138,394 @@ __device__ inline void store_dual(const SideArgs &s, int k, double dual, int hol
     store_through((unsigned long long *)&s.other_dual[k], (unsigned long long)__double_as_longlong(dual));
 }
 
+// Root of the tree column k belongs to: follow the predecessors back to a bidder (its index in
+// the list; bidders are marked in held[] by -1 - index).  -1 if the chain does not end within
+// `guard` hops, which sound labels rule out.  Labels stand still while this runs.
+__device__ inline int tree_root(const PathBuffers &buf, int k, int guard)
+{
+    while (guard-- > 0) {
+        const int i = (int)(load_fresh_u64(&buf.label[k]) & MF_ID_MASK);
+        const int h = __hip_atomic_load(&buf.held[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (h < 0) return -1 - h;
+        k = h;
+    }
+    return -1;
+}
+
+// Lowers label[k] to `mine` if that is a strictly shorter length (a tie keeps the predecessor
+// it has: swapping predecessors at equal length could close a cycle of zero-length edges).
+__device__ inline bool lower_label(unsigned long long *word, unsigned long long mine)
+{
+    unsigned long long seen = *word;        // possibly outdated, never below the true word: a safe first test
+    while ((mine >> MF_ID_BITS) < (seen >> MF_ID_BITS)) {
+        const unsigned long long was = atomicCAS(word, seen, mine);
+        if (was == seen) return true;
+        seen = was;
+    }
+    return false;
+}
+
 __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const int *__restrict__ list,
                                                             int *__restrict__ out_list, mf_device_stats *stats,
                                                             PathCtl *ctl, PathBuffers buf, int ring, int rows,
-                                                            double width_max, unsigned spin_limit)
+                                                            double width_max, unsigned spin_limit, int frontier_high)
 {
     __shared__ Top2 red[PATH_THREADS / 64];
     __shared__ unsigned s_pushes, s_base, s_first[PATH_SEGMENTS + 1];
     __shared__ unsigned long long s_sink, s_low;
     __shared__ int s_list[PATH_PUSH_BUFFER];
+    __shared__ double s_profit[PATH_MAX_SOURCES];       // of each bidder: best value - eps
+    __shared__ int s_row[PATH_MAX_SOURCES];
+    __shared__ int s_alive[PATH_MAX_SOURCES], s_n_alive, s_root;
     const unsigned G = gridDim.x;
     const int wg = blockIdx.x, tid = threadIdx.x;
     const int gtid = wg * PATH_THREADS + tid, gsize = (int)G * PATH_THREADS;
-    const int count = stats->cnt[ring & 3];
+    const int listed = stats->cnt[ring & 3];
+    const int count = min(listed, PATH_MAX_SOURCES);
     unsigned generation = 0;
-    int item = 0;
-    bool alive = true;
-    for (; item < count && alive; ++item) {
-        const int r0 = list[item];
-        // ---- clear the labels; workgroup 0 finds the bidder's best value ----
-        for (int k = gtid; k < s.len; k += gsize) {
-            store_through(&buf.label[k], PATH_INF);
-            store_through(&buf.expanded[k], PATH_INF);
-            __hip_atomic_store(&buf.stamp[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (wg == 0) {
-            const Top2 t = block_scan<PATH_THREADS>(s.A + (size_t)r0 * s.pitch, s.other_dual, line_length(s, r0),
-                                                    s.Kd, true, red, 0, 0);
-            if (tid < 3 * PATH_SEGMENTS)
-                __hip_atomic_store(&ctl->seg[tid / PATH_SEGMENTS][tid % PATH_SEGMENTS].count, 0u, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            if (tid == 0) {
-                const double v1 = t.b1;
-                store_through(&ctl->first_value[item & 1], (unsigned long long)__double_as_longlong(v1));
-                store_through(&ctl->low[0], PATH_INF);
-                store_through(&ctl->low[1], PATH_INF);
-                store_through(&ctl->low[2], PATH_INF);
-                store_through(&ctl->sink_found[0], PATH_INF);
-                store_through(&ctl->sink_found[1], PATH_INF);
-                store_through(&ctl->sink_found[2], PATH_INF);
-                if (v1 > s.eps) {                                       // pi_r = v1 - eps: rc(r, best column) = 0
-                    store_through(&ctl->sink, ((unsigned long long)(long long)(v1 - s.eps) << 21) | (1ull << 20) |
-                                                  (unsigned long long)r0);
-                    __hip_atomic_store(&buf.held[r0], -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-        }
-        if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
-        // duals stand still during a search: drop what the caches hold of them from before the
-        // last re-assignment once, then read them through the caches
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        const double v1 = __longlong_as_double((long long)load_fresh_u64(&ctl->first_value[item & 1]));
-        if (v1 <= s.eps) continue;                                      // rests with dual 0: nothing to move
-        const double first_profit = v1 - s.eps;
-        // shortest complete path every workgroup agrees on: first "the bidder rests", as workgroup 0 wrote it
-        unsigned long long agreed_sink = ((unsigned long long)(long long)first_profit << 21) | (1ull << 20) |
-                                         (unsigned long long)r0;
+    unsigned long long my_steps = 0, my_scans = 0, my_entries = 0;
+    bool ok = true;
 
-        // ---- label-correcting search, one grid barrier per super-step ----
-        // A step scans the rows on the current frontier; a label that falls inside the window
-        // puts its column on the next frontier at once (claimed through a per-step stamp, so once
-        // per step), whose holder is scanned in the next step from the label the column has by
-        // then.  Only when a frontier comes up empty does a pass over all columns pick up the
-        // labels that fell outside earlier windows, or move the window on.
-        double low = 0.0;
-        // The window adapts to what it yields: wide enough to keep the device busy, narrow enough
-        // that rows are not scanned long before their label is final (every workgroup derives the
-        // same width from the same counters).
-        double width = 4.0 * s.eps;
-        unsigned long long my_steps = 0, my_scans = 0, my_entries = 0;
-        const int segment = wg / PATH_GROUP % PATH_SEGMENTS;
-        unsigned step = 0;
-        bool swept = false;                      // the previous step was a pass over all columns
-        for (;;) {
-            // far more steps than a search over sound duals can take: give the bidder back to the
-            // chains (every workgroup counts the same steps, so all leave here together)
-            if (++step > 4u * (unsigned)s.len + 4096u) { alive = false; break; }
-            const unsigned c = step % 3u, p = (step + 1u) % 3u, z = (step + 2u) % 3u;
-            // frontier of this step: its segments' lengths (the very first holds just the bidder)
-            if (tid < 64) {
-                unsigned n_seg = 0;
-                if (tid < PATH_SEGMENTS && step > 1u) n_seg = load_fresh_u32(&ctl->seg[c][tid].count);
-                unsigned run = n_seg;                               // inclusive prefix sums over 16 lanes
-                for (int d = 1; d < PATH_SEGMENTS; d <<= 1) {
-                    const unsigned o = __shfl_up(run, d);
-                    if ((int)tid >= d) run += o;
-                }
-                if (tid < PATH_SEGMENTS) s_first[tid + 1] = run;
-                if (tid == 0) { s_first[0] = 0u; s_pushes = 0u; s_sink = PATH_INF; s_low = PATH_INF; }
-            }
-            __syncthreads();
-            const int nf = step == 1u ? 1 : (int)s_first[PATH_SEGMENTS];
-            if (step > 1u) {
-                const unsigned long long found = load_fresh_u64(&ctl->sink_found[c]);
-                agreed_sink = found < agreed_sink ? found : agreed_sink;
-            }
-            // pruning may use whatever is known by now; decisions all workgroups must share may not
-            const unsigned long long sink_word = min(agreed_sink, load_fresh_u64(&ctl->sink));
-            const double bound = (double)(long long)(sink_word >> 21);
-            if (step > 1u && swept && nf == 0) {
-                const unsigned long long lo = load_fresh_u64(&ctl->low[c]);
-                if (lo == PATH_INF || lo >= (agreed_sink >> 21)) break;     // every label below the sink is final
-                low = (double)(long long)lo;                                // move the window to the next label
-            }
-            if (nf > PATH_FRONTIER_HIGH) width = fmax(s.eps, width * 0.5);
-            else if (nf < PATH_FRONTIER_LOW) width = fmin(width_max, width * 2.0);
-            const double limit = fmin(low + width, bound);
-            if (gtid < PATH_SEGMENTS)
-                __hip_atomic_store(&ctl->seg[z][gtid].count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (gtid == 0) { store_through(&ctl->low[z], PATH_INF); store_through(&ctl->sink_found[z], PATH_INF); }
-            const int *frontier = buf.fr_col[step & 1u];
-            int *next_frontier = buf.fr_col[(step + 1u) & 1u];
-
-            // puts column k on the next frontier (through the workgroup's LDS list while it has room)
-            auto push = [&](int k) {
-                const unsigned slot = atomicAdd(&s_pushes, 1u);
-                if (slot < (unsigned)PATH_PUSH_BUFFER) s_list[slot] = k;
-                else {
-                    const unsigned pos = atomicAdd(&ctl->seg[p][segment].count, 1u);
-                    __hip_atomic_store(&next_frontier[(size_t)segment * s.len + pos], k, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-                }
-            };
-
-            if (nf > 0) {
-                swept = false;
-                // one wavefront per (row, slice of columns): enough independent loads in flight to
-                // stream the rows at memory speed whether the frontier holds one row or thousands
-                constexpr int WAVES = PATH_THREADS / 64;
-                const int total_waves = (int)G * WAVES, wave_id = wg * WAVES + (tid >> 6), lane = tid & 63;
-                int slices = total_waves / nf;
-                slices = slices < 1 ? 1 : (slices > PATH_MAX_SLICES ? PATH_MAX_SLICES : slices);
-                const int span = (((s.len + slices - 1) / slices) + 255) & ~255;
-                slices = (s.len + span - 1) / span;
-                const int items = nf * slices;
-                for (int it = wave_id; it < items; it += total_waves) {
-                    const int e = it / slices, sl = it - e * slices;
-                    int i, mine_col;
-                    double dist, profit;
-                    if (step == 1u) {
-                        i = r0; mine_col = -1; dist = 0.0; profit = first_profit;
-                    } else {
-                        int g = 0;
-                        while ((unsigned)e >= s_first[g + 1]) ++g;
-                        mine_col = __hip_atomic_load(&frontier[(size_t)g * s.len + (e - s_first[g])], __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-                        const unsigned long long lw = load_fresh_u64(&buf.label[mine_col]);
-                        i = word_id(load_fresh_u64(&s.otherword[mine_col]));
-                        dist = (double)(long long)(lw >> MF_ID_BITS);
-                        // the row's profit: what it holds minus that column's dual
-                        profit = s.Kd * (double)s.A[(size_t)i * s.pitch + mine_col] - s.other_dual[mine_col];
-                        if (sl == 0 && lane == 0) {
-                            store_through(&buf.expanded[mine_col], lw >> MF_ID_BITS);
-                            __hip_atomic_store(&buf.held[i], mine_col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            if (dist + profit < bound) {                    // it may also give up and rest
-                                const unsigned long long rests = ((unsigned long long)(long long)(dist + profit) << 21) |
-                                                                 (1ull << 20) | (unsigned long long)i;
-                                atomicMin(&ctl->sink, rests);
-                                atomicMin(&ctl->sink_found[p], rests);
-                            }
-                        }
-                    }
-                    const int32_t *row = s.A + (size_t)i * s.pitch;
-                    const double base = dist + profit + s.eps;
-                    const int from = sl * span, to = min(line_length(s, i), from + span);
-#pragma unroll 2
-                    for (int k = from + lane * 4; k < to; k += 256) {
-                        const int4 w4 = *(const int4 *)(row + k);
-                        const double2 p01 = *(const double2 *)(s.other_dual + k);
-                        const double2 p23 = *(const double2 *)(s.other_dual + k + 2);
-                        const int32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
-                        const double pr[4] = {p01.x, p01.y, p23.x, p23.y};
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const double cand = base - fma(s.Kd, (double)w[q], -pr[q]);
-                            if (k + q < to && w[q] != MF_INFEASIBLE && cand < bound) {
-                                const unsigned long long mine = ((unsigned long long)(long long)cand << MF_ID_BITS) |
-                                                                (unsigned long long)i;
-                                // a cached label is never below the true one (labels only fall during a
-                                // search and the caches were emptied at its start): a safe first test
-                                if (mine < buf.label[k + q] && atomicMin(&buf.label[k + q], mine) > mine && cand < limit &&
-                                    atomicExch(&buf.stamp[k + q], step) != step) {
-                                    if (word_id(load_fresh_u64(&s.otherword[k + q])) < 0) {  // a column nobody holds ends a path
-                                        const unsigned long long ends = (unsigned long long)(long long)cand << 21 |
-                                                                        (unsigned long long)(k + q);
-                                        atomicMin(&ctl->sink, ends);
-                                        atomicMin(&ctl->sink_found[p], ends);
-                                    } else push(k + q);
-                                }
-                            }
-                        }
-                    }
-                    if (sl == 0 && lane == 0) { ++my_scans; my_entries += (unsigned long long)line_length(s, i); }
-                }
-            } else {
-                // ---- nothing on the frontier: look at every column ----
-                swept = true;
-                for (int first = 0; first < s.len; first += gsize) {
-                    const int k = first + gtid;
-                    if (k < s.len) {
-                        const unsigned long long lw = load_fresh_u64(&buf.label[k]);
-                        const unsigned long long ex = load_fresh_u64(&buf.expanded[k]);
-                        const unsigned long long d_int = lw >> MF_ID_BITS;
-                        const double d = (double)(long long)d_int;
-                        if (lw != PATH_INF && d < bound && d_int < ex) {
-                            if (d >= limit) atomicMin(&s_low, d_int);
-                            else if (word_id(load_fresh_u64(&s.otherword[k])) < 0)
-                                atomicMin(&s_sink, (d_int << 21) | (unsigned long long)k);
-                            else push(k);
-                        }
-                    }
-                }
-            }
-            // ---- hand the workgroup's pushes, sink and window candidates over ----
-            __syncthreads();
-            const unsigned pushed = min(s_pushes, (unsigned)PATH_PUSH_BUFFER);
-            if (tid == 0) {
-                s_base = pushed ? atomicAdd(&ctl->seg[p][segment].count, pushed) : 0u;
-                if (s_sink != PATH_INF) { atomicMin(&ctl->sink, s_sink); atomicMin(&ctl->sink_found[p], s_sink); }
-                if (s_low != PATH_INF) atomicMin(&ctl->low[p], s_low);
-            }
-            __syncthreads();
-            for (unsigned t = tid; t < pushed; t += PATH_THREADS)
-                __hip_atomic_store(&next_frontier[(size_t)segment * s.len + s_base + t], s_list[t], __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            ++my_steps;
-            if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }
-        }
-        if (!alive) break;
-
-        // ---- make the shortest path tight, then re-assign along it ----
-        // Workgroup 0 does both on its own, and only behind one more barrier: passing it proves
-        // that every workgroup finished its share of the search, so no wait that runs out can
-        // leave the duals half-updated or updated from incomplete labels.
-        if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; break; }      // r0 not placed: handed back below
-        if (wg == 0) {
-            const unsigned long long sink = load_fresh_u64(&ctl->sink);
-            const unsigned long long d_star = sink >> 21;
-            for (int k = tid; k < s.len; k += PATH_THREADS) {
-                const unsigned long long lw = load_fresh_u64(&buf.label[k]);
-                if (lw == PATH_INF) continue;
-                const unsigned long long d_int = lw >> MF_ID_BITS;
-                if (d_int < d_star) {
-                    const unsigned long long cw = load_fresh_u64(&s.otherword[k]);
-                    store_dual(s, k, word_dual(cw) + (double)(long long)(d_star - d_int), (int)(cw & MF_ID_MASK));
-                }
-            }
-            __threadfence();
-            __syncthreads();
-            if (tid == 0) {
-                const int id = (int)(sink & 0xfffffull);
-                int k = ((sink >> 20) & 1ull) ? (id == r0 ? -1 : __hip_atomic_load(&buf.held[id], __ATOMIC_RELAXED,
-                                                                                     __HIP_MEMORY_SCOPE_AGENT))
-                                              : id;
-                int guard = 0;
-                while (k >= 0 && guard++ <= rows) {
-                    const int i = (int)(load_fresh_u64(&buf.label[k]) & MF_ID_MASK);
-                    const int before = __hip_atomic_load(&buf.held[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    store_dual(s, k, word_dual(load_fresh_u64(&s.otherword[k])) + s.eps, i + 1);
-                    k = (i == r0) ? -1 : before;
-                }
-                atomicAdd(&ctl->steps, my_steps);
-            }
-        }
-        if ((tid & 63) == 0 && my_scans) { atomicAdd(&ctl->scans, my_scans); atomicAdd(&ctl->entries, my_entries); }
-        if (!grid_barrier(ctl, G, generation, spin_limit)) { alive = false; ++item; break; }   // r0 is placed
+    // ---- set-up: no labels; one workgroup per bidder finds its best value ----
+    for (int k = gtid; k < s.len; k += gsize) {
+        store_through(&buf.label[k], PATH_INF);
+        store_through(&buf.expanded[k], PATH_INF);
+        __hip_atomic_store(&buf.stamp[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    for (int item = wg; item < count; item += (int)G) {
+        const int r = list[item];
+        const Top2 t = block_scan<PATH_THREADS>(s.A + (size_t)r * s.pitch, s.other_dual, line_length(s, r), s.Kd,
+                                                true, red, 0, 0);
+        if (tid == 0) {
+            store_through(&ctl->src_profit[item], (unsigned long long)__double_as_longlong(t.b1 - s.eps));
+            __hip_atomic_store(&buf.held[r], -1 - item, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    if (wg == 0) {
+        if (tid < 3 * PATH_SEGMENTS)
+            __hip_atomic_store(&ctl->seg[tid / PATH_SEGMENTS][tid % PATH_SEGMENTS].count, 0u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) {
+            store_through(&ctl->sink, PATH_INF);
+            for (int q = 0; q < 3; ++q) { store_through(&ctl->low[q], PATH_INF); store_through(&ctl->sink_found[q], PATH_INF); }
+        }
+    }
+    const bool started = grid_barrier(ctl, G, generation, spin_limit);      // false: nobody's best value can be trusted
+    ok = started;
+    // duals stand still between two re-assignments: drop what the caches hold of them from before
+    // once, then read them through the caches
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    if (tid < count) {
+        s_profit[tid] = __longlong_as_double((long long)load_fresh_u64(&ctl->src_profit[tid]));
+        s_row[tid] = list[tid];
+    }
+    __syncthreads();
+    // Every workgroup keeps its own copy of the list of bidders still to be placed; all copies
+    // change alike because every decision below is taken from the same published words.
+    if (tid == 0) {
+        int n = 0;
+        for (int j = 0; j < count; ++j)
+            if (s_profit[j] > 0.0) s_alive[n++] = j;        // a bidder whose best value is at most eps rests with dual 0
+        s_n_alive = n;
+    }
+    __syncthreads();
+    int n_alive = s_n_alive;
+
+    // what "the bidder rests after all" costs, the nearest of them: the first path ends every workgroup agrees on
+    auto resting_bidders = [&]() {
+        unsigned long long best = PATH_INF;
+        for (int e = 0; e < n_alive; ++e) {
+            const int j = s_alive[e];
+            const unsigned long long w = ((unsigned long long)(long long)s_profit[j] << 21) | (1ull << 20) |
+                                         (unsigned long long)s_row[j];
+            best = w < best ? w : best;
+        }
+        return best;
+    };
+    unsigned long long agreed_sink = resting_bidders();
+
+    // ---- label-correcting search, one grid barrier per super-step ----
+    // A step scans the rows on the current frontier; a label that falls inside the window puts
+    // its column on the next frontier at once (claimed through a per-step stamp, so once per
+    // step), whose holder is scanned in the next step from the label the column has by then.
+    // Only when a frontier comes up empty does a pass over all columns pick up the labels that
+    // fell outside earlier windows, or move the window on, or find that the nearest path end is final.
+    double low = 0.0;
+    // The window adapts to what it yields: wide enough to keep the device busy, narrow enough
+    // that rows are not scanned long before their label is final (every workgroup derives the
+    // same width from the same counters).
+    double width = 4.0 * s.eps;
+    const int segment = wg / PATH_GROUP % PATH_SEGMENTS;
+    unsigned step = 0, since_served = 0;
+    bool swept = false;                      // the previous step was a pass over all columns
+    bool from_bidders = true;                // this step scans the bidders themselves (the first, and the one after a re-assignment)
+    bool sweep_next = false;                 // ... and the step after that looks at every column
+    while (ok && n_alive > 0) {
+        // far more steps than a search over sound duals can take: give the bidders back to the
+        // chains (every workgroup counts the same steps, so all leave here together)
+        if (++since_served > 4u * (unsigned)s.len + 4096u) { ok = false; break; }
+        ++step;
+        const unsigned c = step % 3u, p = (step + 1u) % 3u, z = (step + 2u) % 3u;
+        // frontier of this step: its segments' lengths
+        if (tid < 64) {
+            unsigned n_seg = 0;
+            if (tid < PATH_SEGMENTS && !from_bidders) n_seg = load_fresh_u32(&ctl->seg[c][tid].count);
+            unsigned run = n_seg;                               // inclusive prefix sums over 16 lanes
+            for (int d = 1; d < PATH_SEGMENTS; d <<= 1) {
+                const unsigned o = __shfl_up(run, d);
+                if ((int)tid >= d) run += o;
+            }
+            if (tid < PATH_SEGMENTS) s_first[tid + 1] = run;
+            if (tid == 0) { s_first[0] = 0u; s_pushes = 0u; s_sink = PATH_INF; s_low = PATH_INF; }
+        }
+        __syncthreads();
+        const bool sweeping = !from_bidders && (sweep_next || s_first[PATH_SEGMENTS] == 0u);
+        const int nf = from_bidders ? n_alive : (sweeping ? 0 : (int)s_first[PATH_SEGMENTS]);
+        {
+            const unsigned long long found = load_fresh_u64(&ctl->sink_found[c]);
+            agreed_sink = found < agreed_sink ? found : agreed_sink;
+        }
+        if (!from_bidders && !sweep_next && swept && nf == 0) {
+            const unsigned long long lo = load_fresh_u64(&ctl->low[c]);
+            if (lo == PATH_INF || lo >= (agreed_sink >> 21)) {
+                // ---- every label below the nearest path end is final: serve its tree ----
+                // Nothing the others can see changes before the barrier that proves every
+                // workgroup got here (a wait that runs out before it leaves the state as it
+                // was); then workgroup 0 alone raises the tree's prices and re-assigns along the
+                // path, so no wait that runs out later can leave that half-done.
+                const unsigned long long sink = agreed_sink, d_star = sink >> 21;
+                const int sink_id = (int)(sink & 0xfffffull);
+                const bool gives_up = ((sink >> 20) & 1ull) != 0;
+                if (tid == 0) {
+                    int root;
+                    if (gives_up) {
+                        const int h = __hip_atomic_load(&buf.held[sink_id], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        root = h < 0 ? -1 - h : tree_root(buf, h, rows + 1);
+                    } else {
+                        root = tree_root(buf, sink_id, rows + 1);
+                    }
+                    s_root = root;
+                }
+                __syncthreads();
+                const int root = s_root;
+                if (root < 0 || root >= count) { ok = false; break; }          // (the same in every workgroup)
+                for (int k = gtid; k < s.len; k += gsize) {
+                    const unsigned long long lw = load_fresh_u64(&buf.label[k]);
+                    if (lw != PATH_INF && tree_root(buf, k, rows + 1) == root)
+                        __hip_atomic_store(&buf.stamp[k], PATH_IN_TREE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (!grid_barrier(ctl, G, generation, spin_limit)) { ok = false; break; }
+                if (wg == 0) {
+                    for (int k = tid; k < s.len; k += PATH_THREADS) {
+                        if (__hip_atomic_load(&buf.stamp[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != PATH_IN_TREE) continue;
+                        const unsigned long long d_int = load_fresh_u64(&buf.label[k]) >> MF_ID_BITS;
+                        if (d_int < d_star) {
+                            const unsigned long long cw = load_fresh_u64(&s.otherword[k]);
+                            store_dual(s, k, word_dual(cw) + (double)(long long)(d_star - d_int), (int)(cw & MF_ID_MASK));
+                        }
+                    }
+                    __threadfence();
+                    __syncthreads();
+                    if (tid == 0) {
+                        // the column the path ends in: a free one, or the one its last row gives up (none if the bidder itself rests)
+                        int k = sink_id;
+                        if (gives_up) {
+                            const int h = __hip_atomic_load(&buf.held[sink_id], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            k = h < 0 ? -1 : h;
+                        }
+                        int guard = 0;
+                        while (k >= 0 && guard++ <= rows) {
+                            const int i = (int)(load_fresh_u64(&buf.label[k]) & MF_ID_MASK);
+                            const int before = __hip_atomic_load(&buf.held[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            store_dual(s, k, word_dual(load_fresh_u64(&s.otherword[k])) + s.eps, i + 1);
+                            k = before;                     // negative: i is the bidder, the path is done
+                        }
+                        // path ends found so far may belong to the tree that is gone: start again from
+                        // "a bidder rests"; the pass over all columns below finds the others again
+                        store_through(&ctl->sink, PATH_INF);
+                        for (int q = 0; q < 3; ++q) store_through(&ctl->sink_found[q], PATH_INF);
+                    }
+                }
+                if (!grid_barrier(ctl, G, generation, spin_limit)) {
+                    // the bidder is placed; whoever leaves here must not hand it back
+                    if (tid == 0) {
+                        int n = 0;
+                        for (int e = 0; e < n_alive; ++e) if (s_alive[e] != root) s_alive[n++] = s_alive[e];
+                        s_n_alive = n;
+                    }
+                    __syncthreads();
+                    n_alive = s_n_alive;
+                    ok = false;
+                    break;
+                }
+                // The served tree's columns lose their labels; every other labelled column is due
+                // for another scan of its holder: columns of the served tree may now be nearer
+                // through it, and labels beyond the old path end were never recorded.
+                for (int k = gtid; k < s.len; k += gsize) {
+                    if (__hip_atomic_load(&buf.stamp[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == PATH_IN_TREE) {
+                        store_through(&buf.label[k], PATH_INF);
+                        __hip_atomic_store(&buf.stamp[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    store_through(&buf.expanded[k], PATH_INF);
+                }
+                if (tid == 0) {
+                    int n = 0;
+                    for (int e = 0; e < n_alive; ++e) if (s_alive[e] != root) s_alive[n++] = s_alive[e];
+                    s_n_alive = n;
+                }
+                if (!grid_barrier(ctl, G, generation, spin_limit)) { __syncthreads(); n_alive = s_n_alive; ok = false; break; }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");     // prices and labels changed: nothing cached is good any more
+                n_alive = s_n_alive;
+                agreed_sink = resting_bidders();
+                from_bidders = true; sweep_next = false; swept = false; since_served = 0;
+                --step;                                                // this was no step: the slots keep their turn
+                continue;
+            }
+            low = (double)(long long)lo;                                // move the window to the next label
+        }
+        // pruning may use whatever is known by now; decisions all workgroups must share may not
+        const unsigned long long sink_word = min(agreed_sink, load_fresh_u64(&ctl->sink));
+        const double bound = (double)(long long)(sink_word >> 21);
+        if (nf > frontier_high) width = fmax(s.eps, width * 0.5);
+        else if (nf < frontier_high / 8) width = fmin(width_max, width * 2.0);
+        const double limit = fmin(low + width, bound);
+        if (gtid < PATH_SEGMENTS)
+            __hip_atomic_store(&ctl->seg[z][gtid].count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (gtid == 0) { store_through(&ctl->low[z], PATH_INF); store_through(&ctl->sink_found[z], PATH_INF); }
+        const int *frontier = buf.fr_col[step & 1u];
+        int *next_frontier = buf.fr_col[(step + 1u) & 1u];
+
+        // puts column k on the next frontier (through the workgroup's LDS list while it has room)
+        auto push = [&](int k) {
+            const unsigned slot = atomicAdd(&s_pushes, 1u);
+            if (slot < (unsigned)PATH_PUSH_BUFFER) s_list[slot] = k;
+            else {
+                const unsigned pos = atomicAdd(&ctl->seg[p][segment].count, 1u);
+                __hip_atomic_store(&next_frontier[(size_t)segment * s.len + pos], k, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        };
+
+        if (nf > 0) {
+            swept = false;
+            // one wavefront per (row, slice of columns): enough independent loads in flight to
+            // stream the rows at memory speed whether the frontier holds one row or thousands
+            constexpr int WAVES = PATH_THREADS / 64;
+            const int total_waves = (int)G * WAVES, wave_id = wg * WAVES + (tid >> 6), lane = tid & 63;
+            int slices = total_waves / nf;
+            slices = slices < 1 ? 1 : (slices > PATH_MAX_SLICES ? PATH_MAX_SLICES : slices);
+            const int span = (((s.len + slices - 1) / slices) + 255) & ~255;
+            slices = (s.len + span - 1) / span;
+            const int items = nf * slices;
+            for (int it = wave_id; it < items; it += total_waves) {
+                const int e = it / slices, sl = it - e * slices;
+                int i, mine_col;
+                double dist, profit;
+                if (from_bidders) {
+                    const int j = s_alive[e];
+                    i = s_row[j]; mine_col = -1; dist = 0.0; profit = s_profit[j];
+                } else {
+                    int g = 0;
+                    while ((unsigned)e >= s_first[g + 1]) ++g;
+                    mine_col = __hip_atomic_load(&frontier[(size_t)g * s.len + (e - s_first[g])], __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+                    const unsigned long long lw = load_fresh_u64(&buf.label[mine_col]);
+                    if (lw == PATH_INF) continue;               // (cannot be: a column on a frontier has a label)
+                    i = word_id(load_fresh_u64(&s.otherword[mine_col]));
+                    dist = (double)(long long)(lw >> MF_ID_BITS);
+                    // the row's profit: what it holds minus that column's dual
+                    profit = s.Kd * (double)s.A[(size_t)i * s.pitch + mine_col] - s.other_dual[mine_col];
+                    if (sl == 0 && lane == 0) {
+                        store_through(&buf.expanded[mine_col], lw >> MF_ID_BITS);
+                        __hip_atomic_store(&buf.held[i], mine_col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (dist + profit < bound) {                    // it may also give up and rest
+                            const unsigned long long rests = ((unsigned long long)(long long)(dist + profit) << 21) |
+                                                             (1ull << 20) | (unsigned long long)i;
+                            atomicMin(&ctl->sink, rests);
+                            atomicMin(&ctl->sink_found[p], rests);
+                        }
+                    }
+                }
+                const int32_t *row = s.A + (size_t)i * s.pitch;
+                const double base = dist + profit + s.eps;
+                const int from = sl * span, to = min(line_length(s, i), from + span);
+#pragma unroll 2
+                for (int k = from + lane * 4; k < to; k += 256) {
+                    const int4 w4 = *(const int4 *)(row + k);
+                    const double2 p01 = *(const double2 *)(s.other_dual + k);
+                    const double2 p23 = *(const double2 *)(s.other_dual + k + 2);
+                    const int32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
+                    const double pr[4] = {p01.x, p01.y, p23.x, p23.y};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const double cand = base - fma(s.Kd, (double)w[q], -pr[q]);
+                        if (k + q < to && w[q] != MF_INFEASIBLE && cand < bound) {
+                            const unsigned long long mine = ((unsigned long long)(long long)cand << MF_ID_BITS) |
+                                                            (unsigned long long)i;
+                            if (lower_label(&buf.label[k + q], mine) && cand < limit &&
+                                atomicExch(&buf.stamp[k + q], step) != step) {
+                                if (word_id(load_fresh_u64(&s.otherword[k + q])) < 0) {  // a column nobody holds ends a path
+                                    const unsigned long long ends = (unsigned long long)(long long)cand << 21 |
+                                                                    (unsigned long long)(k + q);
+                                    atomicMin(&ctl->sink, ends);
+                                    atomicMin(&ctl->sink_found[p], ends);
+                                } else push(k + q);
+                            }
+                        }
+                    }
+                }
+                if (sl == 0 && lane == 0) { ++my_scans; my_entries += (unsigned long long)line_length(s, i); }
+            }
+            sweep_next = from_bidders && step > 1u;     // after a re-assignment: every labelled column is due
+            from_bidders = false;
+        } else {
+            // ---- nothing on the frontier (or everything is due): look at every column ----
+            swept = true;
+            sweep_next = false;
+            for (int first = 0; first < s.len; first += gsize) {
+                const int k = first + gtid;
+                if (k < s.len) {
+                    const unsigned long long lw = load_fresh_u64(&buf.label[k]);
+                    const unsigned long long ex = load_fresh_u64(&buf.expanded[k]);
+                    const unsigned long long d_int = lw >> MF_ID_BITS;
+                    const double d = (double)(long long)d_int;
+                    if (lw != PATH_INF && d < bound && d_int < ex) {
+                        if (word_id(load_fresh_u64(&s.otherword[k])) < 0)
+                            atomicMin(&s_sink, (d_int << 21) | (unsigned long long)k);
+                        else if (d >= limit) atomicMin(&s_low, d_int);
+                        else push(k);
+                    }
+                }
+            }
+        }
+        // ---- hand the workgroup's pushes, path ends and window candidates over ----
+        __syncthreads();
+        const unsigned pushed = min(s_pushes, (unsigned)PATH_PUSH_BUFFER);
+        if (tid == 0) {
+            s_base = pushed ? atomicAdd(&ctl->seg[p][segment].count, pushed) : 0u;
+            if (s_sink != PATH_INF) { atomicMin(&ctl->sink, s_sink); atomicMin(&ctl->sink_found[p], s_sink); }
+            if (s_low != PATH_INF) atomicMin(&ctl->low[p], s_low);
+        }
+        __syncthreads();
+        for (unsigned t = tid; t < pushed; t += PATH_THREADS)
+            __hip_atomic_store(&next_frontier[(size_t)segment * s.len + s_base + t], s_list[t], __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        ++my_steps;
+        if (!grid_barrier(ctl, G, generation, spin_limit)) { ok = false; break; }
+    }
+
+    if ((tid & 63) == 0 && my_scans) { atomicAdd(&ctl->scans, my_scans); atomicAdd(&ctl->entries, my_entries); }
+    if (gtid == 0) atomicAdd(&ctl->steps, my_steps);
+    // the totals below are read by one thread after everybody's additions: one more barrier, whose
+    // outcome no longer matters
+    (void)grid_barrier(ctl, G, generation, spin_limit);
     if (gtid == 0) {
-        for (int rest = item; rest < count; ++rest)                         // whoever was not served bids again
+        if (started)
+            for (int e = 0; e < n_alive; ++e)                               // whoever was not served bids again
+                out_list[atomicAdd(&stats->cnt[(ring + 1) & 3], 1)] = s_row[s_alive[e]];
+        for (int rest = started ? count : 0; rest < listed; ++rest)
             out_list[atomicAdd(&stats->cnt[(ring + 1) & 3], 1)] = list[rest];
-        if (!alive) atomicExch(&stats->team_abort, 2);
+        if (!ok) atomicExch(&stats->team_abort, 2);
         const unsigned long long steps = load_fresh_u64(&ctl->steps), scans = load_fresh_u64(&ctl->scans);
         stats->launch_max = steps;
         stats->bids += scans;
@@ -412,8 +538,8 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
 
 }  // namespace
 
-// Places the bidders listed in list[ring & 1] (stats->cnt[ring & 3] of them) one after another;
-// whoever is not served (a wait ran out) is handed on in list[(ring + 1) & 1].
+// Places the bidders listed in list[ring & 1] (stats->cnt[ring & 3] of them) by one search from
+// all of them; whoever is not served (a wait ran out) is handed on in list[(ring + 1) & 1].
 int mf_launch_path_search(mf_ctx *ctx, const SideArgs &s, int ring)
 {
     PathBuffers buf{ctx->path_label, ctx->path_expanded, ctx->path_stamp,
@@ -423,7 +549,7 @@ int mf_launch_path_search(mf_ctx *ctx, const SideArgs &s, int ring)
     hipLaunchKernelGGL(path_kernel, dim3(path_wgs), dim3(PATH_THREADS), 0, ctx->stream, s,
                        ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, (PathCtl *)ctx->path_ctl,
                        buf, ring, ctx->max_n > ctx->max_m ? ctx->max_n : ctx->max_m,
-                       (double)ctx->path_width * s.eps, ctx->path_spin_limit);
+                       (double)ctx->path_width * s.eps, ctx->path_spin_limit, ctx->path_frontier_rows);
     MF_HIP(hipGetLastError());
     return MF_OK;
 }
