@@ -116,7 +116,14 @@ typedef struct {
     int32_t status;             /* same code the call returned                          */
     float   ms_solve;           /* device time of the auction (HIP events)              */
     float   ms_certify;         /* device time of dual extraction + certificate         */
+    int32_t fallbacks;          /* MF_FALLBACK_* bits: kernels this solve had to do without */
 } mf_result;
+
+/* A bounded wait between cooperating workgroups ran out during the solve, and from then on it
+ * went without the kernels that use such waits (every solve starts with all of them again).  The
+ * result is exact either way; a set bit says the solve was slower than it should have been. */
+#define MF_FALLBACK_TEAMS    1  /* several workgroups per chain of bids          */
+#define MF_FALLBACK_SEARCHES 2  /* shortest-augmenting-path searches             */
 
 /*
  * Creates a context bound to HIP device `device` and to `hip_stream` (a

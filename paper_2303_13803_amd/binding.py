@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(HERE, "libmuxmatch.so")
 
 INFEASIBLE = -2147483648
 OK, ERR_ARG, ERR_SHAPE, ERR_HIP, ERR_NOT_CONVERGED, ERR_CERT, ERR_RANGE = 0, -1, -2, -3, -4, -5, -6
+FALLBACK_TEAMS, FALLBACK_SEARCHES = 1, 2
 
 EXPORTS = ["mf_create", "mf_destroy", "mf_score_pairs", "mf_solve_assignment",
            "mf_check_certificate", "mf_check_certificate_noalloc", "mf_schedule_round", "mf_schedule_round_update", "mf_score_pairs_typed",
@@ -42,7 +43,7 @@ class Result(C.Structure):
                 ("path_scans", C.c_int64),
                 ("matched", C.c_int32), ("phases", C.c_int32),
                 ("cert_ok", C.c_int32), ("status", C.c_int32), ("ms_solve", C.c_float),
-                ("ms_certify", C.c_float)]
+                ("ms_certify", C.c_float), ("fallbacks", C.c_int32)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}

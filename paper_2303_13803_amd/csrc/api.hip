@@ -98,10 +98,14 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->phase_keep = 4;
     ctx->phase_growth = 1;
     ctx->final_jump = 0;
+    ctx->phase_tail_steps = 64;
+    ctx->phase_tail_sides = 1;
+    ctx->phase_tail_from = 8192;
     ctx->warm_eps_units = 0;
     ctx->warm_reset_cols = true;
     ctx->chain_grid = 256;
     ctx->bulk_shape = 1;
+    ctx->bulk_grid = 0;
     ctx->team_max = 8;
     ctx->team_size = 16;
     ctx->team_wide = 64;
@@ -337,10 +341,14 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!ctx || !name) return MF_ERR_ARG;
     if (!strcmp(name, "theta")) { if (value < 2 || value > 1024) return MF_ERR_ARG; ctx->theta = value; return MF_OK; }
     if (!strcmp(name, "phase_keep")) { if (value < 1 || value > 64) return MF_ERR_ARG; ctx->phase_keep = (int)value; return MF_OK; }
+    if (!strcmp(name, "phase_tail_steps")) { if (value < 0) return MF_ERR_ARG; ctx->phase_tail_steps = value; return MF_OK; }
+    if (!strcmp(name, "phase_tail_from")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->phase_tail_from = (int)value; return MF_OK; }
+    if (!strcmp(name, "phase_tail_sides")) { if (value < 0 || value > 3) return MF_ERR_ARG; ctx->phase_tail_sides = (int)value; return MF_OK; }
     if (!strcmp(name, "final_jump")) { if (value < 0 || value > (1 << 30)) return MF_ERR_ARG; ctx->final_jump = value; return MF_OK; }
     if (!strcmp(name, "phase_growth")) { if (value < 1 || value > 64) return MF_ERR_ARG; ctx->phase_growth = (int)value; return MF_OK; }
     if (!strcmp(name, "phase_stop")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->phase_stop = (int)value; return MF_OK; }
     if (!strcmp(name, "tail_max")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->tail_max = (int)value; return MF_OK; }
+    if (!strcmp(name, "bulk_grid")) { if (value < 0 || value > 8192) return MF_ERR_ARG; ctx->bulk_grid = (int)value; return MF_OK; }
     if (!strcmp(name, "bulk_shape")) { if (value < 0 || value > 4) return MF_ERR_ARG; ctx->bulk_shape = (int)value; return MF_OK; }
     if (!strcmp(name, "warm_reset_cols")) { ctx->warm_reset_cols = value != 0; return MF_OK; }
     if (!strcmp(name, "warm_eps_units")) { if (value < 0 || value > (1 << 30)) return MF_ERR_ARG; ctx->warm_eps_units = value; return MF_OK; }
@@ -351,7 +359,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "team_threads")) { if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return MF_ERR_ARG; ctx->team_threads = (int)value; return MF_OK; }
     if (!strcmp(name, "chain_grid")) { if (value < 1 || value > 4096) return MF_ERR_ARG; ctx->chain_grid = (int)value; return MF_OK; }
     if (!strcmp(name, "path_max")) { if (value < 0 || value > 64) return MF_ERR_ARG; ctx->path_max = (int)value; return MF_OK; }
-    if (!strcmp(name, "path_spin_limit")) { if (value < 0 || value > (1ll << 30)) return MF_ERR_ARG; ctx->path_spin_limit = (unsigned)value; ctx->path_off = false; return MF_OK; }
+    if (!strcmp(name, "path_spin_limit")) { if (value < 0 || value > (1ll << 30)) return MF_ERR_ARG; ctx->path_spin_limit = (unsigned)value; return MF_OK; }
     if (!strcmp(name, "path_after")) { if (value < 0) return MF_ERR_ARG; ctx->path_after = value; return MF_OK; }
     if (!strcmp(name, "path_grid")) { if (value < 0 || value > 1024) return MF_ERR_ARG; ctx->path_grid = (int)value; return MF_OK; }
     if (!strcmp(name, "path_frontier_rows")) { if (value < 8 || value > (1 << 20)) return MF_ERR_ARG; ctx->path_frontier_rows = (int)value; return MF_OK; }

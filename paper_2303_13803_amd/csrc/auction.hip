@@ -35,12 +35,20 @@ namespace {
 // older dual): the auction tolerates both because duals only move one way and a
 // bid computed from an outdated dual simply fails to win.  The counters form a
 // ring: round r reads cnt[r], fills cnt[r+1] and clears cnt[r+2].
+constexpr int ROUND_GROUPS_PER_WORKGROUP = 128;
+
 template <int NT, int RB>
-__global__ __launch_bounds__(NT) void round_kernel(SideArgs s, const int *__restrict__ list,
+__global__ __launch_bounds__(NT, 3) void round_kernel(SideArgs s, const int *__restrict__ list,
                                                    int *__restrict__ next, mf_device_stats *stats,
                                                    int ring)
 {
+    // Bidders this workgroup has to pass on are collected here and handed over together: the
+    // list counter is a single address, every atomic on it takes its turn, and thousands of
+    // workgroups that finish at the same moment would queue up behind it (measured: one such
+    // atomic per group of four lines costs a full-matrix round a fifth of its time).
+    // The launch gives every workgroup at most ROUND_GROUPS_PER_WORKGROUP groups of lines.
     __shared__ Top2 red[RB + RB * (NT / 64)];
+    __shared__ int s_hold[RB * ROUND_GROUPS_PER_WORKGROUP];
     const int count = stats->cnt[ring & 3];
     int *ncnt = &stats->cnt[(ring + 1) & 3];
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -51,6 +59,7 @@ __global__ __launch_bounds__(NT) void round_kernel(SideArgs s, const int *__rest
             stats->bids += (unsigned long long)count;
         }
     }
+    int held = 0;                                           // entries of s_hold in use (first wavefront, same in every lane)
     unsigned long long entries = 0;                         // scanned by this workgroup (thread 0 keeps count)
     for (int item = blockIdx.x * RB; item < count; item += gridDim.x * RB) {
         int salt[RB];
@@ -72,19 +81,23 @@ __global__ __launch_bounds__(NT) void round_kernel(SideArgs s, const int *__rest
                 const int b = list[item + threadIdx.x];
                 Top2 t = red[threadIdx.x];
                 t.idx ^= tie_salt(b);
-                again = decide_and_bid(s, b, t);
+                again = decide_and_bid<true>(s, b, t);
             }
-            // one counter update per workgroup: the list counter is a single hot address
             const unsigned long long pushing = __ballot(again >= 0);
             if (pushing) {
-                int base = 0;
-                if (threadIdx.x == 0) base = atomicAdd(ncnt, __popcll(pushing));
-                base = __shfl(base, 0);
-                if (again >= 0) next[base + __popcll(pushing & ((1ull << threadIdx.x) - 1ull))] = again;
+                if (again >= 0) s_hold[held + __popcll(pushing & ((1ull << threadIdx.x) - 1ull))] = again;
+                held += __popcll(pushing);
             }
         }
     }
-    if (threadIdx.x == 0 && entries) atomicAdd(&stats->bytes, entries * 4ull);
+    if (threadIdx.x < 64 && held > 0) {
+        int base = 0;
+        if (threadIdx.x == 0) base = atomicAdd(ncnt, held);
+        base = __shfl(base, 0);
+        for (int k = threadIdx.x; k < held; k += 64) next[base + k] = s_hold[k];
+    }
+    // (a word with a cache line to itself: not behind the list counter)
+    if (threadIdx.x == 0 && entries) atomicAdd(&stats->round_bytes, entries * 4ull);
 }
 
 // The tail of a run.  When few bidders are left, rounds are bound by launch
@@ -536,7 +549,7 @@ __global__ void init_solver_kernel(int n, int m, double *price, double *profit, 
     if (i < n + 4) profit[i] = 0.0;
     if (i < m + 4 && (!keep_prices || i >= m)) price[i] = 0.0;
     if (i == 0) {
-        stats->rounds = 0; stats->bids = 0; stats->bytes = 0; stats->head = 0;
+        stats->rounds = 0; stats->bids = 0; stats->bytes = 0; stats->round_bytes = 0; stats->head = 0;
         stats->chain_bids = 0; stats->chain_depth = 0; stats->launch_max = 0; stats->chain_retries = 0; stats->team_bids = 0; stats->path_steps = 0; stats->path_scans = 0; stats->team_abort = 0; stats->active = 0; stats->max_weight = 0;
         stats->cnt[0] = 0; stats->cnt[1] = 0; stats->cnt[2] = 0; stats->cnt[3] = 0;
     }
@@ -547,6 +560,12 @@ void launch_round_shape(mf_ctx *ctx, const SideArgs &s, int count, int ring)
 {
     int grid = (count + RB - 1) / RB;
     if (grid > MAX_GRID) grid = MAX_GRID;
+    // ten workgroups per compute unit read a matrix faster than one per group of lines: those that
+    // finish early take another group, and fewer of them queue for the list counter at the end
+    const int cap = ctx->bulk_grid > 0 ? ctx->bulk_grid : 10 * (ctx->n_cus > 0 ? ctx->n_cus : 256);
+    if (grid > cap) grid = cap;
+    const int groups = (count + RB - 1) / RB;               // (a workgroup's list of bidders to pass on holds so many groups)
+    if ((long long)grid * ROUND_GROUPS_PER_WORKGROUP < groups) grid = (groups + ROUND_GROUPS_PER_WORKGROUP - 1) / ROUND_GROUPS_PER_WORKGROUP;
     hipLaunchKernelGGL((round_kernel<NT, RB>), dim3(grid), dim3(NT), 0, ctx->stream, s, ctx->list[ring & 1],
                        ctx->list[(ring + 1) & 1], ctx->stats, ring);
 }
@@ -565,16 +584,20 @@ void launch_round(mf_ctx *ctx, const SideArgs &s, int count, int ring)
 // Runs one side until at most `stop_at` bidders are left (0: until nobody is left to bid).
 // list[0] / cnt[0] hold the first bidders (`count` of them).  Returns MF_OK or an error;
 // *left_over is the number of bidders still unplaced.
-int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int stop_at, int *left_over)
+int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int stop_at, long long tail_budget, int *left_over)
 {
     int ring = 0;
     // Short chains are cheapest followed step by step; a chain that is still going after
     // `path_after` steps is ended by shortest-path searches instead.
     long long team_steps = 0;
+    int idle_launches = 0;
+    long long tail_steps = 0;               // dependent steps of the chain kernels of this run, longest workgroup of each
     *left_over = count;
     while (count > stop_at) {
-        bool timed = false, counted_teams = false;
-        const unsigned long long bytes_before = ctx->h_stats->bytes;
+        // a side that only prepares prices (stop_at > 0) does not follow chains for ever
+        if (stop_at > 0 && tail_budget > 0 && tail_steps >= tail_budget) break;
+        bool timed = false, counted_teams = false, chained = false;
+        const unsigned long long bytes_before = ctx->h_stats->bytes + ctx->h_stats->round_bytes, bids_before = ctx->h_stats->bids;
         const bool paths_ok = ctx->path_max > 0 && !ctx->path_off && ctx->n_cus > 0;
         const bool teams_ok = ctx->team_max > 0 && !ctx->team_off;
         const int cus = ctx->n_cus > 0 ? ctx->n_cus : 256;
@@ -602,7 +625,12 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
             ++ring;
         } else if (!teams_ok || count > team_from) {
             const int grid = count < ctx->chain_grid ? count : ctx->chain_grid;
-            const int hand_back = teams_ok ? team_from : (paths_ok ? ctx->path_max : -1);
+            // Workgroups hand their bidders back once so few chains are left that teams (or searches)
+            // do better.  Never at a count the grid starts below: then every workgroup would hand
+            // back before its first bid and the same launch would repeat for ever.
+            int hand_back = teams_ok ? team_from : (paths_ok ? ctx->path_max : -1);
+            if (hand_back >= grid) hand_back = grid - 1;
+            chained = true;
             hipLaunchKernelGGL(chain_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats, ring, grid);
             hipLaunchKernelGGL(chain_kernel, dim3(grid), dim3(CHAIN_THREADS), 0, ctx->stream, s,
                                ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, ring,
@@ -621,6 +649,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
                                                       : (count > ctx->team_max ? ctx->team_regroup : team_cap);
             if (stop_after < team_cap) team_cap = stop_after;
             counted_teams = before_paths;
+            chained = true;
             hipLaunchKernelGGL(team_begin_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->stats,
                                (TeamCtl *)ctx->team_ctl, ring);
             const dim3 grid(teams * size);
@@ -642,13 +671,19 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
             MF_HIP(hipEventElapsedTime(&ms, ctx->ev[6], ctx->ev[7]));
             ctx->timings[T_BID_BULK] += ms;
             ctx->timings[T_BID_BULK_LAUNCHES] += 1.0f;
-            ctx->timings[T_BID_BULK_BYTES] += (float)((double)(ctx->h_stats->bytes - bytes_before));
+            ctx->timings[T_BID_BULK_BYTES] += (float)((double)(ctx->h_stats->bytes + ctx->h_stats->round_bytes - bytes_before));
         }
         time_first = false;
+        // a launch that neither evaluated a bid nor placed anybody must not repeat for ever
+        if ((long long)ctx->h_stats->bids == (long long)bids_before && ctx->h_stats->cnt[ring & 3] >= count) {
+            if (++idle_launches > 64) return MF_ERR_NOT_CONVERGED;
+        } else idle_launches = 0;
         count = ctx->h_stats->cnt[ring & 3];
         if (counted_teams) team_steps += (long long)ctx->h_stats->launch_max;     // the longest any leader went
-        if (ctx->h_stats->team_abort == 1) ctx->team_off = true;   // a bounded wait ran out: one workgroup per chain from now on
-        if (ctx->h_stats->team_abort == 2) ctx->path_off = true;   // ... or no more shortest-path searches
+        if (chained) tail_steps += (long long)ctx->h_stats->launch_max;
+        // a bounded wait ran out: one workgroup per chain, or no more searches, for the rest of this solve
+        if (ctx->h_stats->team_abort == 1) { ctx->team_off = true; ctx->fallbacks |= MF_FALLBACK_TEAMS; }
+        if (ctx->h_stats->team_abort == 2) { ctx->path_off = true; ctx->fallbacks |= MF_FALLBACK_SEARCHES; }
         *left_over = count;
     }
     return MF_OK;
@@ -669,6 +704,8 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     // order of memory fraction, where the pairs that can share are a prefix of every row and of
     // every column: the auction then runs on that copy and reads only the prefixes; the
     // certificate below is still evaluated on the caller's matrix, in the caller's coordinates.
+    ctx->team_off = ctx->path_off = false;      // every solve starts with all of its kernels
+    ctx->fallbacks = 0;
     const bool candidate = may_use_staged && ctx->fit_prefix && ctx->staged_n == n && ctx->staged_m == m;
     const bool flip = n > m;
     warm = warm && !flip && !candidate && ctx->warm_n == n && ctx->warm_m == m;
@@ -785,7 +822,7 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
             if (stop_ll > rn / 64) stop_ll = rn / 64;
         }
         const int stop_at = (int)stop_ll;
-        int rc = run_side(ctx, fwd, rn, true, stop_at, &left_over);
+        int rc = run_side(ctx, fwd, rn, true, stop_at, (ctx->phase_tail_sides & 1) && rn >= ctx->phase_tail_from ? ctx->phase_tail_steps : 0, &left_over);
         if (rc != MF_OK) return rc;
         // who holds what after the forward rounds; unassigned priced columns go to list[0]
         hipLaunchKernelGGL(clear_counts_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats);
@@ -804,7 +841,7 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         const int rev_count = ctx->h_stats->cnt[0];
         if (rev_count > stop_at) {
             if (!have_transpose) make_transpose();
-            rc = run_side(ctx, rev, rev_count, false, stop_at, &left_over);
+            rc = run_side(ctx, rev, rev_count, false, stop_at, (ctx->phase_tail_sides & 2) && rn >= ctx->phase_tail_from ? ctx->phase_tail_steps : 0, &left_over);
             if (rc != MF_OK) return rc;
             hipLaunchKernelGGL(reverse_done_cols_kernel, dim3((rm + 255) / 256), dim3(256), 0, ctx->stream, rm,
                                ctx->price, ctx->col2row);
@@ -833,7 +870,7 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     ctx->timings[T_CERT] = ms_cert;
     h_res->rounds = (int64_t)ctx->h_stats->rounds;
     h_res->bids = (int64_t)ctx->h_stats->bids;
-    h_res->bytes_scanned = (int64_t)ctx->h_stats->bytes;
+    h_res->bytes_scanned = (int64_t)(ctx->h_stats->bytes + ctx->h_stats->round_bytes);
     h_res->chain_bids = (int64_t)ctx->h_stats->chain_bids;
     h_res->chain_retries = (int64_t)ctx->h_stats->chain_retries;
     h_res->team_bids = (int64_t)ctx->h_stats->team_bids;
@@ -841,6 +878,7 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     h_res->path_scans = (int64_t)ctx->h_stats->path_scans;
     h_res->chain_depth = (int64_t)(ctx->h_stats->chain_depth + ctx->h_stats->launch_max);
     h_res->phases = phases;
+    h_res->fallbacks = ctx->fallbacks;
     h_res->ms_solve = ms_solve;
     h_res->ms_certify = ms_duals + ms_cert;
     if (h_res->cert_ok && !staged) { ctx->warm_n = n; ctx->warm_m = m; }      // these prices may seed the next solve

@@ -41,6 +41,9 @@ struct mf_device_stats {            // lives in device memory, cleared per solve
     int head;                       // next unclaimed entry of the list a chain kernel works through
     int active;                     // workgroups of the running chain kernel still following a chain
     int team_abort;                 // a bounded wait between cooperating workgroups ran out (1: chain teams, 2: path search)
+    // weight bytes the rounds with many bidders read: every workgroup of such a round adds to it as
+    // it leaves, so it sits on a cache line of its own, away from the list counters above
+    alignas(128) unsigned long long round_bytes;
 };
 
 struct mf_cert_out {                // lives in device memory, cleared per check
@@ -86,14 +89,19 @@ struct mf_ctx {
     int phase_stop;                 // unplaced bidders at or below which a phase that only prepares prices ends
     int phase_growth;               // ... times this for every phase further from the ones that run to the end
     int phase_keep;                 // the last so many phases always run to the end
+    long long phase_tail_steps;     // dependent chain steps after which a side that only prepares prices ends (0: no limit)
+    int phase_tail_from;            // ... for problems with at least this many bidding lines
+    int phase_tail_sides;           // ... on which sides: bit 0 the first (rows bid), bit 1 the second
     long long final_jump;           // epsilon (weight units) at or below which the next phase is the last (0: never)
     int tail_max;                   // bidder count at or below which chains are followed in one kernel
+    int bulk_grid;                  // most workgroups of such a round (0: one per group of lines, up to 8192)
     int bulk_shape;                 // workgroup shape of rounds with many bidders (see launch_round)
     int team_max;                   // chains at or below which several workgroups share each chain (0: never)
     int team_size, team_threads;    // most workgroups per chain, threads per such workgroup
     int team_wide;                  // chains at or below which smaller teams already take over from chain_kernel
     long long team_regroup;         // steps after which such teams stop so that the chains left can be regrouped
-    bool team_off;                  // set after a team wait ran out
+    bool team_off;                  // set after a team wait ran out, for the rest of the solve
+    int fallbacks;                  // MF_FALLBACK_* bits of the running solve
     void *team_ctl;                 // control blocks of the cooperating workgroups
     void *path_ctl;                 // control block of the shortest-path search
     unsigned long long *path_label, *path_expanded;   // [max(max_n, max_m)] each
@@ -106,7 +114,7 @@ struct mf_ctx {
     int path_width;                 // label window of one super-step, in epsilons
     int path_frontier_rows;         // frontier above which the window is halved (doubled below an eighth of it)
     unsigned path_spin_limit;       // polls a workgroup waits at a barrier of the search before it gives up
-    bool path_off;                  // set after a wait of the search ran out
+    bool path_off;                  // set after a wait of the search ran out, for the rest of the solve
     int n_cus;                      // compute units of the device
     int chain_grid;                 // workgroups of that kernel
     int *list[2];

@@ -278,19 +278,29 @@ __device__ __forceinline__ void block_scan_rows(const int32_t *const (&rows)[RB]
 // dual the scan happened to read, which may have moved since.
 // Returns the workload that has to bid next because of this bid (the bidder
 // itself if it was outbid in the meantime, the previous holder if it won), or -1.
+// LOOK_FIRST: read the word before bidding and do without the atomic when the bid has lost
+// already.  For rounds in which thousands bid at once, many of them for the same few entries; a
+// bidder following a chain on its own would only wait one more memory round trip per step.
+template <bool LOOK_FIRST = false>
 __device__ inline int decide_and_bid(const SideArgs &s, int b, const Top2 &t)
 {
     if (t.b1 <= s.eps) return -1;
     const double keep = fmax(t.b2 - s.eps, 0.0);
     const double offer = s.Kd * (double)t.w - keep;
     const unsigned long long mine = pack_word(offer, b + 1);
-    const unsigned long long old = atomicMax(&s.otherword[t.idx], mine);
     unsigned long long *dual_bits = (unsigned long long *)&s.other_dual[t.idx];
+    unsigned long long old = LOOK_FIRST ? load_fresh_u64(&s.otherword[t.idx]) : 0ull;
+    if (old < mine) old = atomicMax(&s.otherword[t.idx], mine);
     if (old < mine) {
         atomicMax(dual_bits, (unsigned long long)__double_as_longlong(offer));
         return word_id(old);
     }
-    atomicMax(dual_bits, (unsigned long long)__double_as_longlong(word_dual(old)));
+    // Outbid: whoever holds the word now has written, or is about to write, at least its dual to
+    // the copy the scans read; make sure of it, but without an atomic when it is there already -
+    // hundreds of bidders may lose on the same popular entry in one round, and every atomic on a
+    // line that all scans are reading holds those reads up.
+    const unsigned long long least = (unsigned long long)__double_as_longlong(word_dual(old));
+    if (load_fresh_u64(dual_bits) < least) atomicMax(dual_bits, least);
     return b;
 }
 

@@ -18,10 +18,12 @@ INF = synth.INFEASIBLE
 @pytest.fixture(scope="module")
 def mm():
     import paper_2303_13803_amd as mm
+    import paper_2303_13803_amd.binding  # noqa: F401  (mm.binding: the bit names)
     return mm
 
 
-def _solve_and_verify(ctx, orc, W, expect):
+def _solve_and_verify(ctx, orc, W, expect, fallbacks=0):
+    """fallbacks: the bits mf_result must report (None: whatever), 0 for a solve nothing was forced to give up in."""
     n, m = W.shape
     r2c = torch.empty(n, dtype=torch.int32, device="cuda")
     u = torch.empty(n, dtype=torch.int64, device="cuda")
@@ -31,6 +33,8 @@ def _solve_and_verify(ctx, orc, W, expect):
     assert code == 0 and res.cert_ok == 1
     assert (P, D) == (res.primal, res.dual)
     assert res.primal == expect
+    if fallbacks is not None:
+        assert res.fallbacks == fallbacks
     return res
 
 
@@ -92,24 +96,46 @@ def test_a_search_that_gives_up_hands_back_to_the_chains(mm, orc, polls):
     expect = orc.max_weight_matching(W)[0]
     ctx = mm.Context(800, 800)
     ctx.set_option("path_after", 0)
-    for attempt in range(3):
-        ctx.set_option("path_spin_limit", polls)          # also re-arms the searches
-        _solve_and_verify(ctx, orc, W, expect)
+    ctx.set_option("path_spin_limit", polls)
+    gave_up = 0
+    for attempt in range(3):                              # every solve starts with its searches switched on again
+        res = _solve_and_verify(ctx, orc, W, expect, fallbacks=None)
+        assert res.fallbacks in (0, mm.binding.FALLBACK_SEARCHES)
+        gave_up += res.fallbacks != 0
+    if polls == 0:
+        assert gave_up == 3                               # no wait at all: the first barrier of every solve runs out
     ctx.set_option("path_spin_limit", 1 << 22)
-    res = _solve_and_verify(ctx, orc, W, expect)
+    res = _solve_and_verify(ctx, orc, W, expect)          # ... and reports nothing once the waits are long enough
     assert res.path_steps > 0
     ctx.close()
+
+
+@pytest.mark.parametrize("chain_grid", [1, 8, 64])
+def test_chain_kernel_with_fewer_workgroups_than_it_hands_back_at(mm, orc, chain_grid):
+    """With so few workgroups every one of them hands its bidder back at its first step; the
+    entries of the list nobody claimed must still reach the next kernel."""
+    for name, W in [("uniform square", synth.uniform_matrix(51, 900, 900, 2 ** 20, 0.1)),
+                    ("wide", synth.uniform_matrix(52, 500, 1300, 2 ** 24, 0.3)),
+                    ("few levels", synth.threshold_matrix(53, 600, 900, 256, 0.9))]:
+        ctx = mm.Context(*W.shape)
+        ctx.set_option("chain_grid", chain_grid)
+        _solve_and_verify(ctx, orc, W, _optimum(orc, W))
+        ctx.close()
 
 
 @pytest.mark.parametrize("options", [{"phase_stop": 0}, {"phase_stop": 8, "phase_keep": 1},
                                      {"phase_stop": 64, "phase_keep": 2, "phase_growth": 4, "path_after": 0},
                                      {"phase_stop": 1 << 20, "phase_keep": 1},
-                                     {"phase_stop": 3, "phase_keep": 64}])
+                                     {"phase_stop": 3, "phase_keep": 64},
+                                     {"phase_tail_steps": 1, "phase_tail_from": 0, "phase_tail_sides": 3},
+                                     {"phase_tail_steps": 8, "phase_tail_from": 0, "phase_tail_sides": 2, "phase_stop": 64},
+                                     {"phase_tail_steps": 4, "phase_tail_from": 0, "phase_tail_sides": 1, "phase_keep": 1}])
 def test_phases_that_end_early_leave_the_optimum_alone(mm, orc, options):
     """Phases at a coarse epsilon may stop with bidders unplaced (they only prepare prices); with
     more columns than rows the other side then runs from profits that cover the unplaced rows.
     Whatever the setting - every phase completed, only the last one, as many bidders left over as
-    the library allows - the last phase makes the result exactly optimal."""
+    the library allows, chains of bids cut off after a few steps on either side - the last phase
+    makes the result exactly optimal."""
     cases = list(_cases()) + [("one more column than rows", synth.uniform_matrix(48, 300, 301, 2 ** 24, 0.2)),
                               ("one more row than columns", synth.uniform_matrix(49, 301, 300, 2 ** 24, 0.2))]
     for name, W in cases:

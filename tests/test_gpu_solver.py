@@ -37,6 +37,7 @@ def _verify(orc, W, res, r2c, u, v, exact_total=None):
     assert (P, D) == (res.primal, res.dual)
     assert res.matched == int((r2c >= 0).sum())
     assert res.min_reduced_cost >= 0
+    assert res.fallbacks == 0, "a bounded wait ran out in a solve nothing was forced to give up in"
     if exact_total is not None:
         assert res.primal == exact_total
 
