@@ -632,6 +632,10 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
             if (hand_back >= grid) hand_back = grid - 1;
             chained = true;
             hipLaunchKernelGGL(chain_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats, ring, grid);
+            // (the budget of a side that only prepares prices is checked between launches, not inside
+            // this one: where rows that will end up unmatched fight over every column they fit
+            // beside, cutting this launch short leaves hundreds of them to the finer phases, which
+            // then take seconds - measured)
             hipLaunchKernelGGL(chain_kernel, dim3(grid), dim3(CHAIN_THREADS), 0, ctx->stream, s,
                                ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, ring,
                                left / grid + 1, hand_back);
@@ -772,9 +776,10 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     // with per-line lengths a scan reads, on average, the pairs that can share divided by the lines
     const double feasible = staged ? (double)*ctx->h_feasible_pairs : (double)n * (double)m;
     SideArgs fwd{A, (long long)lda, rm, ctx->price, ctx->colword, 0.0, Kd, flip ? len_cols : len_rows,
-                 (int)(feasible / (double)rn)};
+                 (int)(feasible / (double)rn), nullptr, (long long)ldat, rn, flip ? len_rows : len_cols};
     SideArgs rev{At, (long long)ldat, rn, ctx->profit, ctx->roword, 0.0, Kd, flip ? len_rows : len_cols,
-                 (int)(feasible / (double)rm)};
+                 (int)(feasible / (double)rm), A, (long long)lda, rm, flip ? len_cols : len_rows};
+    if (flip) fwd.T = At;                       // (the other copy of the matrix: made on demand unless it is the one solved on)
 
     // The ladder of epsilons: divided by theta per phase down to 1.  Once epsilon is at most
     // final_jump weight units (final_jump * K in dual units) the next phase is the last one:
@@ -822,6 +827,10 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
             if (stop_ll > rn / 64) stop_ll = rn / 64;
         }
         const int stop_at = (int)stop_ll;
+        // a phase that runs to the end places its last bidders by a search, which re-labels the
+        // columns of a served tree from the other copy of the matrix
+        if (!have_transpose && stop_at == 0 && ctx->path_max > 1 && rn > 1) make_transpose();
+        if (have_transpose) fwd.T = At;
         int rc = run_side(ctx, fwd, rn, true, stop_at, (ctx->phase_tail_sides & 1) && rn >= ctx->phase_tail_from ? ctx->phase_tail_steps : 0, &left_over);
         if (rc != MF_OK) return rc;
         // who holds what after the forward rounds; unassigned priced columns go to list[0]

@@ -108,10 +108,13 @@ struct mf_ctx {
     unsigned int *path_stamp;
     int *path_frontier[2];          // 16 segments of max(max_n, max_m) columns each
     int *path_held;
+    double *path_base;              // per bidding line: length of the shortest path to it plus what it would pay, or +inf
+    int *path_tree;                 // columns of the tree being served
     int path_max;                   // bidders at or below which shortest-path searches place them (0: never)
     long long path_after;           // chain steps per run after which the searches take over
     int path_grid;                  // workgroups of a search (0: one per compute unit)
     int path_width;                 // label window of one super-step, in epsilons
+    bool path_pull;                 // re-label a served tree's columns from the other copy of the matrix
     int path_frontier_rows;         // frontier above which the window is halved (doubled below an eighth of it)
     unsigned path_spin_limit;       // polls a workgroup waits at a barrier of the search before it gives up
     bool path_off;                  // set after a wait of the search ran out, for the rest of the solve
@@ -142,6 +145,12 @@ struct SideArgs {
     double eps, Kd;
     const int *line_len;                // optional: every entry of line b at or beyond line_len[b] is infeasible
     int typical_len;                    // what a scan reads on average (host-side choice of kernels only)
+    // the same matrix by lines of the other side (line k of T is entry k of every line of A), when
+    // that copy exists (else null): lets a search look at one entry of all bidding lines at once
+    const int32_t *T;
+    long long pitch_t;
+    int len_t;                          // entries of a line of T = lines of A
+    const int *line_len_t;              // optional, as line_len
 };
 
 // score.hip

@@ -65,6 +65,7 @@ struct alignas(128) PathCtl {
     struct alignas(128) { unsigned int number; } open;        // barriers completed so far | PATH_GAVE_UP
     alignas(128) unsigned long long steps;
     unsigned long long scans, entries;
+    alignas(128) unsigned int tree_count;                     // columns of the tree being served (list in PathBuffers::tree)
     struct alignas(128) { unsigned int arrive; } group[PATH_MAX_GROUPS];
     // Frontier lengths: one counter per segment (a segment collects the pushes of sixteen
     // workgroups, so no counter is hit by more than sixteen atomics per step), in three slots:
@@ -79,8 +80,12 @@ struct PathBuffers {
     unsigned long long *expanded;   // [len] label at which the column's holder was last scanned
     unsigned int *stamp;            // [len] last step in which the column was put on a frontier
     int *fr_col[2];                 // frontiers (by step parity): PATH_SEGMENTS segments of len columns each
-    int *held;                      // [rows] column a frontier row holds
+    int *held;                      // [rows] column a frontier row holds (-1 - index for a bidder)
+    double *base;                   // [rows + 8] for a row that has been scanned: its path length + its profit + eps
+                                    // (a column's label through that row is base - K w + the column's dual); else PATH_FAR
+    int *tree;                      // [len] columns of the tree being served
 };
+constexpr double PATH_FAR = 1.0e300;
 
 // Grid-wide barrier in two levels: workgroups arrive at their group's counter, the last of a
 // group at the top counter, and the last of all publishes the barrier's number in a word that
@@ -123,7 +128,7 @@ __device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned 
 
 __global__ void path_begin_kernel(mf_device_stats *stats, PathCtl *ctl, int ring)
 {
-    ctl->arrive.count = 0u; ctl->open.number = 0u; ctl->steps = 0ull; ctl->scans = 0ull; ctl->entries = 0ull;
+    ctl->arrive.count = 0u; ctl->open.number = 0u; ctl->steps = 0ull; ctl->scans = 0ull; ctl->entries = 0ull; ctl->tree_count = 0u;
     for (int g = 0; g < PATH_MAX_GROUPS; ++g) ctl->group[g].arrive = 0u;
     stats->cnt[(ring + 1) & 3] = 0;
     stats->cnt[(ring + 2) & 3] = 0;
@@ -192,6 +197,10 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         store_through(&buf.expanded[k], PATH_INF);
         __hip_atomic_store(&buf.stamp[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    for (int i = gtid; i < ((s.len_t + 7) & ~3); i += gsize)
+        store_through((unsigned long long *)&buf.base[i], (unsigned long long)__double_as_longlong(PATH_FAR));
+    // (a barrier of its own: the bidders' entries below must not be overwritten by a late clearing store)
+    const bool cleared = grid_barrier(ctl, G, generation, spin_limit);
     for (int item = wg; item < count; item += (int)G) {
         const int r = list[item];
         const Top2 t = block_scan<PATH_THREADS>(s.A + (size_t)r * s.pitch, s.other_dual, line_length(s, r), s.Kd,
@@ -199,6 +208,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         if (tid == 0) {
             store_through(&ctl->src_profit[item], (unsigned long long)__double_as_longlong(t.b1 - s.eps));
             __hip_atomic_store(&buf.held[r], -1 - item, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (t.b1 > s.eps) store_through((unsigned long long *)&buf.base[r], (unsigned long long)__double_as_longlong(t.b1));
         }
     }
     if (wg == 0) {
@@ -210,7 +220,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
             for (int q = 0; q < 3; ++q) { store_through(&ctl->low[q], PATH_INF); store_through(&ctl->sink_found[q], PATH_INF); }
         }
     }
-    const bool started = grid_barrier(ctl, G, generation, spin_limit);      // false: nobody's best value can be trusted
+    const bool started = grid_barrier(ctl, G, generation, spin_limit) && cleared;   // false: nobody's best value can be trusted
     ok = started;
     // duals stand still between two re-assignments: drop what the caches hold of them from before
     // once, then read them through the caches
@@ -243,6 +253,17 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         return best;
     };
     unsigned long long agreed_sink = resting_bidders();
+    // ... and the farthest: no bidder's path is longer than what resting costs it, so labels at or
+    // beyond that are of no use to anybody
+    auto farthest_rest = [&]() {
+        double far = 0.0;
+        for (int e = 0; e < n_alive; ++e) far = fmax(far, s_profit[s_alive[e]]);
+        return far;
+    };
+    double far_bound = farthest_rest();
+    // With the other copy of the matrix at hand, the columns of a served tree get their new labels
+    // by one look each at all scanned rows; without it, every scanned row is scanned again.
+    const bool pull = s.T != nullptr;
 
     // ---- label-correcting search, one grid barrier per super-step ----
     // A step scans the rows on the current frontier; a label that falls inside the window puts
@@ -309,10 +330,32 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                 __syncthreads();
                 const int root = s_root;
                 if (root < 0 || root >= count) { ok = false; break; }          // (the same in every workgroup)
+                if (tid == 0) s_pushes = 0u;
+                __syncthreads();
                 for (int k = gtid; k < s.len; k += gsize) {
                     const unsigned long long lw = load_fresh_u64(&buf.label[k]);
-                    if (lw != PATH_INF && tree_root(buf, k, rows + 1) == root)
+                    if (lw != PATH_INF && tree_root(buf, k, rows + 1) == root) {
                         __hip_atomic_store(&buf.stamp[k], PATH_IN_TREE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (pull) {
+                            // its holder's scan no longer counts (workgroup 0 is about to change what it holds and pays)
+                            const int holder = word_id(load_fresh_u64(&s.otherword[k]));
+                            if (holder >= 0)
+                                store_through((unsigned long long *)&buf.base[holder], (unsigned long long)__double_as_longlong(PATH_FAR));
+                            const unsigned slot = atomicAdd(&s_pushes, 1u);
+                            if (slot < (unsigned)PATH_PUSH_BUFFER) s_list[slot] = k;
+                            else __hip_atomic_store(&buf.tree[atomicAdd(&ctl->tree_count, 1u)], k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    }
+                }
+                __syncthreads();
+                if (pull) {
+                    const unsigned mine = min(s_pushes, (unsigned)PATH_PUSH_BUFFER);
+                    if (tid == 0) s_base = mine ? atomicAdd(&ctl->tree_count, mine) : 0u;
+                    __syncthreads();
+                    for (unsigned t = tid; t < mine; t += PATH_THREADS)
+                        __hip_atomic_store(&buf.tree[s_base + t], s_list[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (gtid == 0)          // the bidder itself is no root any more
+                        store_through((unsigned long long *)&buf.base[s_row[root]], (unsigned long long)__double_as_longlong(PATH_FAR));
                 }
                 if (!grid_barrier(ctl, G, generation, spin_limit)) { ok = false; break; }
                 if (wg == 0) {
@@ -362,11 +405,12 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                 // for another scan of its holder: columns of the served tree may now be nearer
                 // through it, and labels beyond the old path end were never recorded.
                 for (int k = gtid; k < s.len; k += gsize) {
-                    if (__hip_atomic_load(&buf.stamp[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == PATH_IN_TREE) {
+                    const bool in_tree = __hip_atomic_load(&buf.stamp[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == PATH_IN_TREE;
+                    if (in_tree) {
                         store_through(&buf.label[k], PATH_INF);
                         __hip_atomic_store(&buf.stamp[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
-                    store_through(&buf.expanded[k], PATH_INF);
+                    if (in_tree || !pull) store_through(&buf.expanded[k], PATH_INF);
                 }
                 if (tid == 0) {
                     int n = 0;
@@ -377,15 +421,56 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");     // prices and labels changed: nothing cached is good any more
                 n_alive = s_n_alive;
                 agreed_sink = resting_bidders();
-                from_bidders = true; sweep_next = false; swept = false; since_served = 0;
+                far_bound = farthest_rest();
+                since_served = 0;
                 --step;                                                // this was no step: the slots keep their turn
+                if (!pull) { from_bidders = true; sweep_next = false; swept = false; continue; }
+                if (n_alive > 0) {
+                    // ---- new labels for the served tree's columns: one wavefront per column looks at
+                    // every row that has been scanned (and at the bidders) in the other copy of the matrix ----
+                    const unsigned n_tree = load_fresh_u32(&ctl->tree_count);
+                    constexpr int WAVES = PATH_THREADS / 64;
+                    const int lane = tid & 63;
+                    for (unsigned it = (unsigned)(wg * WAVES + (tid >> 6)); it < n_tree; it += G * WAVES) {
+                        const int k = __hip_atomic_load(&buf.tree[it], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const int32_t *line = s.T + (size_t)k * s.pitch_t;
+                        const int to = s.line_len_t ? min(s.line_len_t[k], s.len_t) : s.len_t;
+                        double best = PATH_FAR;
+                        int who = 0x7fffffff;
+#pragma unroll 2
+                        for (int i = lane * 4; i < to; i += 256) {
+                            const int4 w4 = *(const int4 *)(line + i);
+                            const double2 b01 = *(const double2 *)(buf.base + i);
+                            const double2 b23 = *(const double2 *)(buf.base + i + 2);
+                            const int32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
+                            const double bs[4] = {b01.x, b01.y, b23.x, b23.y};
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const double cand = fma(-s.Kd, (double)w[q], bs[q]);
+                                if (i + q < to && w[q] != MF_INFEASIBLE && bs[q] < PATH_FAR && cand < best) { best = cand; who = i + q; }
+                            }
+                        }
+                        const double least = -wave_max(-best);
+                        const int row = wave_min(best == least ? who : 0x7fffffff);
+                        if (lane == 0 && least < PATH_FAR) {
+                            const double length = least + s.other_dual[k];          // >= 0: a path length plus a reduced cost
+                            store_through(&buf.label[k], ((unsigned long long)(long long)length << MF_ID_BITS) | (unsigned long long)row);
+                        }
+                    }
+                }
+                if (gtid == 0) __hip_atomic_store(&ctl->tree_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (!grid_barrier(ctl, G, generation, spin_limit)) { ok = false; break; }
+                from_bidders = false; sweep_next = true; swept = false;    // next: a pass over all columns picks them up
                 continue;
             }
             low = (double)(long long)lo;                                // move the window to the next label
         }
         // pruning may use whatever is known by now; decisions all workgroups must share may not
-        const unsigned long long sink_word = min(agreed_sink, load_fresh_u64(&ctl->sink));
-        const double bound = (double)(long long)(sink_word >> 21);
+        // Labels beyond the nearest path end are of no use to the last bidder; with more bidders to
+        // place they are what the search goes on from, and only what lies beyond every bidder's
+        // own way out is left out.
+        const double bound = (n_alive == 1 || !pull) ? (double)(long long)(min(agreed_sink, load_fresh_u64(&ctl->sink)) >> 21)
+                                                     : far_bound;
         if (nf > frontier_high) width = fmax(s.eps, width * 0.5);
         else if (nf < frontier_high / 8) width = fmin(width_max, width * 2.0);
         const double limit = fmin(low + width, bound);
@@ -438,6 +523,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                     if (sl == 0 && lane == 0) {
                         store_through(&buf.expanded[mine_col], lw >> MF_ID_BITS);
                         __hip_atomic_store(&buf.held[i], mine_col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        store_through((unsigned long long *)&buf.base[i], (unsigned long long)__double_as_longlong(dist + profit + s.eps));
                         if (dist + profit < bound) {                    // it may also give up and rest
                             const unsigned long long rests = ((unsigned long long)(long long)(dist + profit) << 21) |
                                                              (1ull << 20) | (unsigned long long)i;
@@ -489,11 +575,19 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                     const unsigned long long ex = load_fresh_u64(&buf.expanded[k]);
                     const unsigned long long d_int = lw >> MF_ID_BITS;
                     const double d = (double)(long long)d_int;
+                    const int holder = lw != PATH_INF ? word_id(load_fresh_u64(&s.otherword[k])) : -1;
                     if (lw != PATH_INF && d < bound && d_int < ex) {
-                        if (word_id(load_fresh_u64(&s.otherword[k])) < 0)
+                        if (holder < 0)
                             atomicMin(&s_sink, (d_int << 21) | (unsigned long long)k);
                         else if (d >= limit) atomicMin(&s_low, d_int);
                         else push(k);
+                    }
+                    // a row that has been scanned may also give its column up and rest (found when it was
+                    // scanned, but path ends found before a re-assignment are forgotten with it)
+                    if (pull && holder >= 0 && ex != PATH_INF) {
+                        const double rests = __longlong_as_double((long long)load_fresh_u64((const unsigned long long *)&buf.base[holder])) - s.eps;
+                        if (rests < bound)
+                            atomicMin(&s_sink, ((unsigned long long)(long long)rests << 21) | (1ull << 20) | (unsigned long long)holder);
                     }
                 }
             }
@@ -543,10 +637,12 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
 int mf_launch_path_search(mf_ctx *ctx, const SideArgs &s, int ring)
 {
     PathBuffers buf{ctx->path_label, ctx->path_expanded, ctx->path_stamp,
-                    {ctx->path_frontier[0], ctx->path_frontier[1]}, ctx->path_held};
+                    {ctx->path_frontier[0], ctx->path_frontier[1]}, ctx->path_held, ctx->path_base, ctx->path_tree};
     hipLaunchKernelGGL(path_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats, (PathCtl *)ctx->path_ctl, ring);
     const int path_wgs = ctx->path_grid > 0 && ctx->path_grid < ctx->n_cus ? ctx->path_grid : ctx->n_cus;
-    hipLaunchKernelGGL(path_kernel, dim3(path_wgs), dim3(PATH_THREADS), 0, ctx->stream, s,
+    SideArgs side = s;
+    if (!ctx->path_pull) side.T = nullptr;
+    hipLaunchKernelGGL(path_kernel, dim3(path_wgs), dim3(PATH_THREADS), 0, ctx->stream, side,
                        ctx->list[ring & 1], ctx->list[(ring + 1) & 1], ctx->stats, (PathCtl *)ctx->path_ctl,
                        buf, ring, ctx->max_n > ctx->max_m ? ctx->max_n : ctx->max_m,
                        (double)ctx->path_width * s.eps, ctx->path_spin_limit, ctx->path_frontier_rows);

@@ -60,6 +60,8 @@ def _optimum(orc, W):
 
 
 @pytest.mark.parametrize("options", [{"path_after": 0}, {"path_after": 0, "path_max": 64, "team_max": 0},
+                                     {"path_after": 0, "path_pull": 1}, {"path_after": 0, "path_max": 64, "team_max": 0, "path_pull": 1},
+                                     {"path_after": 20, "path_pull": 1, "path_width": 2},
                                      {"path_after": 0, "path_width": 1}, {"path_after": 40},
                                      {"team_wide": 64, "team_regroup": 16, "path_after": 30},
                                      {"team_wide": 24, "team_size": 4, "path_max": 0}])
@@ -80,10 +82,12 @@ def test_scored_round_with_searches_only(mm, orc):
     r = synth.scheduling_round("C4", 3, n=1500, m=1500)
     W = orc.score_pairs(r["x_on"], r["x_off"], r["params"], r["cfg"].scale, wide=False)[1]
     ctx = mm.Context(1500, 1500)
-    ctx.set_option("path_after", 0)
-    ctx.set_option("team_wide", 0)                  # no teams between the chain kernel and the searches
-    res = _solve_and_verify(ctx, orc, W, orc.max_weight_matching(W)[0])
-    assert res.path_steps > 0 and res.team_bids == 0
+    for pull in (0, 1):
+        ctx.set_option("path_after", 0)
+        ctx.set_option("path_pull", pull)
+        ctx.set_option("team_wide", 0)                  # no teams between the chain kernel and the searches
+        res = _solve_and_verify(ctx, orc, W, orc.max_weight_matching(W)[0])
+        assert res.path_steps > 0 and res.team_bids == 0
     ctx.close()
 
 
@@ -96,6 +100,7 @@ def test_a_search_that_gives_up_hands_back_to_the_chains(mm, orc, polls):
     expect = orc.max_weight_matching(W)[0]
     ctx = mm.Context(800, 800)
     ctx.set_option("path_after", 0)
+    ctx.set_option("path_pull", polls % 2)                # one of the two ways a served tree's columns are labelled again
     ctx.set_option("path_spin_limit", polls)
     gave_up = 0
     for attempt in range(3):                              # every solve starts with its searches switched on again
