@@ -23,14 +23,20 @@
  *     in these calls (all scratch lives in the context, sized at mf_create),
  *     never frees a caller buffer and keeps no caller pointer after return.
  *   - Matrices are row-major.  The weight matrix W has n rows (online) and m
- *     columns (offline) of int32 with a row pitch of ldw elements (ldw >= m,
- *     ldw a multiple of 4 and d_W 16-byte aligned).  An entry equal to
- *     MF_INFEASIBLE means "this pair must not share a GPU"; every other entry
- *     is a weight in [0, 2^30].
- *   - Work is enqueued on the stream given to mf_create.  A call that is
- *     handed a non-NULL h_res waits for its own work and fills *h_res; with
- *     h_res == NULL mf_score_pairs returns without waiting.  The solver
- *     always waits (it steers its iteration from the host).
+ *     columns (offline) of int32 with a row pitch of ldw elements (ldw >= m).
+ *     An entry equal to MF_INFEASIBLE means "this pair must not share a GPU";
+ *     every other entry is a weight in [0, 2^30].  The calls that READ a
+ *     matrix (mf_solve_assignment, mf_check_certificate*, mf_schedule_round*,
+ *     which solves on what it scored) also need ldw to be a multiple of 4 and
+ *     d_W 16-byte aligned (MF_ERR_ARG otherwise); mf_score_pairs* alone
+ *     writes any pitch and alignment.
+ *   - Work is enqueued on the stream given to mf_create.  mf_score_pairs*
+ *     returns without waiting for its kernels (the typed variant waits once, to
+ *     check the types; the next call on the same
+ *     stream, or a synchronisation of it, orders after them); every call
+ *     that takes an mf_result *h_res (required, not NULL) steers its
+ *     iteration from the host, waits for its own work and fills *h_res.
+ *     mf_check_certificate_noalloc takes its own stream and never waits.
  *   - Return value: MF_OK (0) or a negative MF_ERR_* code; nothing is thrown
  *     across this boundary.  On error the output buffers are unspecified.
  *   - A context may be used by one thread at a time.
@@ -265,34 +271,42 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
                             const float *d_on, int n, const float *d_off, int m, int32_t *d_W, int64_t ldw,
                             int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res);
 
-/* Solver knobs: "theta" (epsilon divisor per phase, default 24), "phase_stop" / "phase_keep" /
- * "phase_growth" (either side of a phase that only prepares prices for later ones ends once at
- * most phase_stop bidders are unplaced, default 16; phase_growth times as many, default 1, for
- * every phase before that one; never more than one bidder in 64, and at least "path_max" so that
- * such a phase runs no searches; the last phase_keep phases, default 4 and at least 1, always run
- * until nobody is left to bid, so the result stays exactly optimal; phase_stop 0 completes every
- * phase), "max_rounds" (limit on
- * evaluated bids, default 4,000,000,000), "tail_max" (bidder count at or below which one
- * kernel follows the remaining eviction chains, default 1024), "chain_grid" (workgroups of
- * that kernel, default 256), "team_wide" (chains at or below which teams of workgroups take the
- * chains over, as many workgroups per chain as the device has per chain, default 64; 0: only at
- * "team_max"), "team_regroup" (steps after which such teams stop so that the chains still going
- * get larger teams, default 128), "team_max" (chains at or below which teams take the chains over
- * when lines are too short for "team_wide" to pay, and below which such a launch is no longer cut
- * short for regrouping, default 8), "team_size" / "team_threads" (most workgroups per
- * chain and threads per workgroup there, default 16 / 1024), "path_max" (bidders at or below which each is placed by
- * a device-wide shortest-augmenting-path search once the chains have gone on for "path_after"
- * steps, defaults 16 and 256; path_max 0 turns the searches off), "path_grid" (workgroups of a search, default 0 = one per compute unit), "path_width" (widest label
- * window of a search step, in epsilons, default 1024), "path_spin_limit" (polls a workgroup of a
- * search waits for the others before all give up and the chains take over again, default 2^22;
- * setting it also re-arms the searches after such a fallback), "bulk_shape" (0..4: threads x lines
- * per workgroup in rounds with many bidders: 256x1, 64x4 (default), 64x2, 128x4, 256x4),
- * "warm_eps_units" (0, the default: mf_schedule_round_update matches from scratch; > 0: from
- * the previous prices at that epsilon, in weight units), "warm_reset_cols", "fit_order" (1,
- * the default: scoring skips pairs that cannot fit in memory; 0: every pair goes through the
- * MLP), "fit_prefix_below" (percent, default 50: when fewer of the pairs just scored can share
- * GPU memory, mf_schedule_round matches on the context's memory-ordered copy of the matrix, where
- * those pairs are a prefix of every row and column, and reads only the prefixes; 0: never). */
+/*
+ * Options of a context, by name.  Unknown names and values out of range give MF_ERR_ARG.
+ *
+ * STABLE (what they mean will not change):
+ *   "theta"            epsilon divisor per phase of the matching, 2..1024, default 24
+ *   "max_rounds"       limit on evaluated bids per solve (MF_ERR_NOT_CONVERGED beyond), default 4e9
+ *   "fit_order"        1 (default): scoring walks workloads in order of memory fraction and runs no
+ *                      MLP for pairs that cannot fit; 0: every pair goes through the MLP
+ *   "fit_prefix"       1 (default) / 0: allow mf_schedule_round to match on the context's
+ *                      memory-ordered copy of the matrix, reading only each line's feasible prefix
+ *   "fit_prefix_below" percent (default 50): ... when fewer of the pairs just scored can share; 0: never
+ *   "warm_eps_units"   0 (default): mf_schedule_round_update matches from scratch; > 0: from the
+ *                      previous prices at that epsilon, in weight units
+ *   "warm_reset_cols"  1 (default): such a start takes replaced columns at price 0
+ *
+ * TUNING (defaults were measured on the benchmark rounds; names and meanings may change with
+ * the kernels they steer; every setting leaves the result exactly optimal):
+ *   phases   "phase_stop" (16) / "phase_keep" (4) / "phase_growth" (1): either side of a phase that
+ *            only prepares prices ends once at most phase_stop bidders are unplaced (times
+ *            phase_growth per phase before; never more than one bidder in 64, at least path_max);
+ *            the last phase_keep phases run until nobody is left to bid.  "phase_tail_steps" (64) /
+ *            "phase_tail_sides" (1: rows bidding; 2: columns; 3: both) / "phase_tail_from" (8192
+ *            lines): such a side also ends after that many dependent chain steps.  "final_jump" (0:
+ *            off): epsilon in weight units at or below which the next phase is the last.
+ *   rounds   "tail_max" (1024 bidders: below, one kernel follows the eviction chains), "bulk_shape"
+ *            (0..4: threads x lines per workgroup with many bidders: 256x1, 64x4 (default), 64x2,
+ *            128x4, 256x4), "bulk_grid" (0: ten workgroups per compute unit)
+ *   chains   "chain_grid" (256 workgroups), "team_wide" (64) / "team_max" (8) / "team_size" (16) /
+ *            "team_threads" (1024) / "team_regroup" (128): several workgroups per chain once so few
+ *            chains are left
+ *   searches "path_max" (16, at most 64; 0: none): bidders at or below which one device-wide
+ *            shortest-augmenting-path search places them all, after "path_after" (256) chain
+ *            steps; "path_grid" (0: one workgroup per compute unit), "path_width" (1024 epsilons),
+ *            "path_frontier_rows" (1024), "path_pull" (0), "path_spin_limit" (2^22 polls a workgroup
+ *            waits for the others before all give up; see mf_result.fallbacks)
+ */
 int mf_set_option(mf_ctx *ctx, const char *name, int64_t value);
 
 /*

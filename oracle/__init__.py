@@ -9,7 +9,7 @@ import os
 
 import numpy as np
 
-from .build import LIB, build
+from .build import LIB, LIB_SAN, build
 
 INFEASIBLE = np.int32(-2147483648)
 _lib = None
@@ -22,9 +22,11 @@ _i64p = np.ctypeslib.ndpointer(np.int64, flags="C_CONTIGUOUS")
 def lib():
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB):
-            build()
-        _lib = C.CDLL(LIB)
+        sanitized = os.environ.get("ORACLE_SANITIZED") == "1"
+        path = LIB_SAN if sanitized else LIB
+        if not os.path.exists(path):
+            build(sanitize=sanitized)
+        _lib = C.CDLL(path)
         _lib.orc_score_pairs.restype = C.c_int
         _lib.orc_score_pairs.argtypes = [_f32p, C.c_int, _f32p, C.c_int, C.c_int, C.c_int,
                                          _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, C.c_float,

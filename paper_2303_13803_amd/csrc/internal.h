@@ -59,6 +59,7 @@ struct mf_ctx {
     hipStream_t stream;
     int max_n, max_m;
     hipError_t hip_error;
+    unsigned kernels_configured;    // kernels whose dynamic shared memory limit has been raised on this device (bits)
     // scoring scratch
     float *proj_on, *proj_off;      // [max_n][H], [max_m][H]
     float *mem_on, *mem_off;        // [max_n], [max_m]

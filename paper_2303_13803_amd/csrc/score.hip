@@ -485,11 +485,12 @@ int launch_pair_variant(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_
                         const int32_t *segment, int grid_rows)
 {
     using S = PairShape<H>;
-    static bool configured = false;
-    if (!configured) {
+    // (the attribute belongs to the device, so what has been set is remembered per context)
+    const unsigned flag = 1u << ((H == 128 ? 2 : 0) + (PAIR_SM ? 1 : 0));
+    if (!(ctx->kernels_configured & flag)) {
         MF_HIP(hipFuncSetAttribute((const void *)pair_mlp_kernel<H, PAIR_SM>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS_BYTES));
-        configured = true;
+        ctx->kernels_configured |= flag;
     }
     // x covers the rows this launch scores (a segment of the row map, or all n), padded to a
     // multiple of 8: every XCD then meets the same row tiles for each column tile
@@ -662,11 +663,10 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
         const int chunks = (m + 4095) / 4096 < 16 ? (m + 4095) / 4096 : 16;
         const int wide = ((uintptr_t)d_W & 15u) == 0 && (ldw & 3) == 0;
         if ((size_t)lds * sizeof(int32_t) <= PLACE_LDS_BYTES) {
-            static bool configured = false;
-            if (!configured) {
+            if (!(ctx->kernels_configured & 16u)) {
                 MF_HIP(hipFuncSetAttribute((const void *)place_lds_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)PLACE_LDS_BYTES));
-                configured = true;
+                ctx->kernels_configured |= 16u;
             }
             hipLaunchKernelGGL(place_lds_kernel, dim3(n), dim3(PLACE_THREADS), sizeof(int32_t) * (size_t)lds, ctx->stream,
                                ctx->staged, lds, ctx->rank_on, ctx->rank_off, ctx->fit_len_on, n, m, d_W, ldw, wide,

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import synth
-from gpu_util import dev, dev_params, empty_matrix, weight_tolerance
+from gpu_util import assert_weights_close, dev, dev_params, empty_matrix, weight_tolerance
 
 pytestmark = pytest.mark.gpu
 INF = synth.INFEASIBLE
@@ -38,8 +38,7 @@ def _compare(orc, r, Wg, sg, scale=None):
     rel = np.abs(sg.astype(np.float64) - sig) / sig
     assert rel.max() <= 1e-5, f"score relative error {rel.max():.3e}"
     ok = W != INF
-    dw = np.abs(Wg[ok].astype(np.int64) - W[ok].astype(np.int64))
-    assert dw.max() <= weight_tolerance(scale), f"weight difference {dw.max()}"
+    assert_weights_close(Wg, W, scale, ok)
     # the GPU's own quantisation of its own score is exact
     q = np.clip(np.rint(sg * np.float32(scale)), 0, scale).astype(np.int64)
     assert (Wg[ok] == q[ok]).all()
@@ -86,7 +85,7 @@ def test_memory_ordered_pass_gives_the_same_matrix(mm, orc, cfg, n, m):
     assert ((Wg == INF) == (W == INF)).all(), "mask bits differ"
     ok = W != INF
     if ok.any():
-        assert np.abs(Wg[ok].astype(np.int64) - W[ok].astype(np.int64)).max() <= weight_tolerance(r["cfg"].scale)
+        assert_weights_close(Wg, W, r["cfg"].scale, ok)
     # every feasible pair went through the MLP; skipped ones are only whole 32-column runs
     feasible = ok.mean()
     assert feasible - 1e-6 <= part <= 1.0
@@ -115,7 +114,7 @@ def test_memory_order_with_ties_and_odd_pitch(mm, orc):
         Wg = Wg[:, :m]
         assert ((Wg == INF) == (W == INF)).all()
         ok = W != INF
-        assert np.abs(Wg[ok].astype(np.int64) - W[ok].astype(np.int64)).max() <= weight_tolerance(r["cfg"].scale)
+        assert_weights_close(Wg, W, r["cfg"].scale, ok)
     ctx.close()
 
 

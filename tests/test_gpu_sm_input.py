@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import synth
-from gpu_util import dev, empty_matrix, weight_tolerance
+from gpu_util import assert_weights_close, dev, empty_matrix, weight_tolerance
 
 pytestmark = pytest.mark.gpu
 INF = synth.INFEASIBLE
@@ -46,7 +46,7 @@ def test_scores_with_sm_input_match_checker(mm, orc, cfg, n, m):
     rel = np.abs(sg.cpu().numpy().astype(np.float64) - sig) / sig
     assert rel.max() <= 1e-5, f"score relative error {rel.max():.3e}"
     ok = W != INF
-    assert np.abs(Wg[ok].astype(np.int64) - W[ok].astype(np.int64)).max() <= weight_tolerance(S)
+    assert_weights_close(Wg, W, S, ok)
     Wd2 = empty_matrix(n, m)                       # weights only: memory order, skipping
     ctx.score_pairs(pred, x_on, x_off, Wd2)
     torch.cuda.synchronize()
@@ -68,7 +68,7 @@ def test_round_with_sm_input_and_argument_errors(mm, orc):
     _, Wc = orc.score_pairs(r["x_on"], r["x_off"], full, S, sm=SM)
     assert ((Wg == INF) == (Wc == INF)).all()
     okm = Wc != INF
-    assert np.abs(Wg[okm].astype(np.int64) - Wc[okm].astype(np.int64)).max() <= weight_tolerance(S)
+    assert_weights_close(Wg, Wc, S, okm)
     assert res.cert_ok == 1 and res.primal == orc.max_weight_matching(Wg)[0]
     # a feature index outside [0, F)
     p = {k: dev(val) for k, val in full.items() if k != "W1"}

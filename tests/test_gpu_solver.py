@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import synth
-from gpu_util import dev, dev_params, empty_matrix, padded_matrix, weight_tolerance
+from gpu_util import assert_weights_close, dev, dev_params, empty_matrix, padded_matrix, weight_tolerance
 
 pytestmark = pytest.mark.gpu
 INF = synth.INFEASIBLE
@@ -122,7 +122,7 @@ def test_largest_dimension_the_packed_words_allow(mm, orc):
     _, Wc = orc.score_pairs(r["x_on"], r["x_off"], r["params"], r["cfg"].scale)
     assert ((W == INF) == (Wc == INF)).all()
     ok = Wc != INF
-    assert np.abs(W[ok].astype(np.int64) - Wc[ok].astype(np.int64)).max() <= weight_tolerance(r["cfg"].scale)
+    assert_weights_close(W, Wc, r["cfg"].scale, ok)
     _verify(orc, W, res, r2c.cpu().numpy(), u.cpu().numpy(), v.cpu().numpy(), orc.max_weight_matching(W)[0])
     ctx.close()
     Wt = np.ascontiguousarray(W.T)                                    # 1,048,574 rows x 3 columns
@@ -265,7 +265,7 @@ def test_schedule_round(mm, orc, cfg, n, m, exact, prefix_below):
     _, Wc = orc.score_pairs(r["x_on"], r["x_off"], r["params"], S)
     assert ((Wg == INF) == (Wc == INF)).all()
     ok = Wc != INF
-    assert np.abs(Wg[ok].astype(np.int64) - Wc[ok]).max() <= weight_tolerance(S)
+    assert_weights_close(Wg, Wc, S, ok)
     # the matching is optimal for the matrix the GPU scored: bit-exact total, host-verified duals
     exact_total = orc.max_weight_matching(Wg if n <= m else np.ascontiguousarray(Wg.T))[0] if exact else None
     _verify(orc, Wg, res, r2c.cpu().numpy(), u.cpu().numpy(), v.cpu().numpy(), exact_total)

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import synth
-from gpu_util import dev, dev_params, empty_matrix, weight_tolerance
+from gpu_util import assert_weights_close, dev, dev_params, empty_matrix, weight_tolerance
 
 pytestmark = pytest.mark.gpu
 INF = synth.INFEASIBLE
@@ -44,7 +44,7 @@ def test_typed_scores_match_checker(mm, orc, cfg, n, m, hidden):
     assert ((Wg == INF) == (W == INF)).all(), "mask bits differ"
     rel = np.abs(sg.cpu().numpy().astype(np.float64) - sig) / sig
     assert rel.max() <= 1e-5, f"score relative error {rel.max():.3e}"
-    assert np.abs(Wg[ok].astype(np.int64) - W[ok].astype(np.int64)).max() <= weight_tolerance(S)
+    assert_weights_close(Wg, W, S, ok)
     # weights only: memory order with skipping gives the same matrix
     Wd2 = empty_matrix(n, m)
     ctx.score_pairs_typed(preds, types, x_on, x_off, Wd2)
@@ -80,7 +80,7 @@ def test_typed_round_and_errors(mm, orc):
     _, Wc = orc.score_pairs_typed(r["x_on"], r["x_off"], r["plist"], r["types"], S)
     assert ((Wg == INF) == (Wc == INF)).all()
     okm = Wc != INF
-    assert np.abs(Wg[okm].astype(np.int64) - Wc[okm].astype(np.int64)).max() <= weight_tolerance(S)
+    assert_weights_close(Wg, Wc, S, okm)
     assert res.cert_ok == 1 and res.primal == orc.max_weight_matching(Wg)[0]
     code, P, D = orc.check_certificate(Wg, r2c.cpu().numpy(), u.cpu().numpy(), v.cpu().numpy(), res.K)
     assert code == 0 and (P, D) == (res.primal, res.dual)

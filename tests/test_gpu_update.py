@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import synth
-from gpu_util import dev, dev_params, empty_matrix, weight_tolerance
+from gpu_util import assert_weights_close, dev, dev_params, empty_matrix, weight_tolerance
 
 pytestmark = pytest.mark.gpu
 INF = synth.INFEASIBLE
@@ -62,7 +62,7 @@ def test_update_round_equals_full_round(mm, orc, cfg, n, m, share, warm):
     _, Wc = orc.score_pairs(r["x_on"], r["x_off"], r["params"], S)
     ok = Wc != INF
     assert ((Wg == INF) == (Wc == INF)).all()
-    assert np.abs(Wg[ok].astype(np.int64) - Wc[ok]).max() <= weight_tolerance(S)
+    assert_weights_close(Wg, Wc, S, ok)
     ctx.close()
 
 
@@ -112,5 +112,5 @@ def test_update_round_at_cluster_scale(mm, orc):
     _, Wr = orc.score_pairs(x_on[rows[:32]], x_off, r["params"], S)
     ok = Wr != INF
     assert ((Wg[rows[:32]] == INF) == (Wr == INF)).all()
-    assert np.abs(Wg[rows[:32]][ok].astype(np.int64) - Wr[ok]).max() <= weight_tolerance(S)
+    assert_weights_close(Wg[rows[:32]], Wr, S, ok)
     ctx.close()
