@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--all-configs", default="C1,C2,C3,C5",
                     help="also run whole rounds of these configurations, each with its certificate checked on the "
                          "device and, with the CPU baseline on, again on the host ('' to skip)")
+    ap.add_argument("--no-masked-matrix", dest="masked_matrix", action="store_false",
+                    help="skip matching a caller-brought matrix with an arbitrary 90 percent mask")
     ap.add_argument("--types", type=int, default=3,
                     help="also time scoring with this many per-GPU-type predictors (0: skip)")
     ap.add_argument("--calib-mib", type=int, default=0,
@@ -270,6 +272,30 @@ def main():
                                     "rescore_ms_last": tm["pair_scoring_ms"] + tm["projections_ms"],
                                     "phases_last": last.phases, "bids_last": last.bids,
                                     "sequential_steps_last": last.chain_depth}
+    if args.masked_matrix:
+        # a matrix the caller brings, one pair in ten feasible in no pattern: matched from per-row
+        # edge lists (default) and, for comparison, from the rows themselves
+        Wm = synth.device_masked_matrix(args.seed, n, m, int(cfg.scale), 10, pitch=ld)
+        entry = {"feasible_share": 0.1, "n": n, "m": m}
+        for label, lists_from in (("edge_lists", None), ("rows", 0)):
+            if lists_from is not None:
+                ctx.set_option("edge_lists_from", lists_from)
+            ms = []
+            for _ in range(3):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                rm_ = ctx.solve_assignment(Wm, n, m, r2c, u, v)
+                torch.cuda.synchronize()
+                ms.append((time.perf_counter() - t0) * 1e3)
+                assert rm_.cert_ok == 1 and rm_.fallbacks == 0
+            tm = ctx.last_timings()
+            entry[label] = {"solve_ms": float(np.median(ms)), "auction_ms": tm["auction_ms"], "prepare_ms": tm["prepare_ms"],
+                            "bytes_scanned": rm_.bytes_scanned, "phases": rm_.phases, "rounds": rm_.rounds,
+                            "primal": rm_.primal, "cert_ok": rm_.cert_ok}
+        ctx.set_option("edge_lists_from", 4096)
+        assert entry["edge_lists"]["primal"] == entry["rows"]["primal"]
+        out["masked_matrix"] = entry
+        del Wm
     if args.types > 0:
         # one predictor per GPU type: same shapes, other weights; rows are scored by their type's
         plist = [{k: dev(v) for k, v in p.items()} for p in synth.typed_predictors(args.seed + 7, cfg.F, [cfg.H] * args.types)]

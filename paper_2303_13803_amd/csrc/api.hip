@@ -114,6 +114,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->fit_order = true;
     ctx->fit_prefix = true;
     ctx->fit_prefix_below = 50;
+    ctx->edge_lists_from = 4096;
     ctx->path_max = 16;
     ctx->path_width = 1024;
     ctx->path_frontier_rows = 1024;
@@ -166,6 +167,8 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     }
     TRY(dev_alloc(&ctx->path_held, nm));
     TRY(dev_alloc(&ctx->path_base, nm + 8));
+    TRY(dev_alloc(&ctx->edge_count, nm));
+    TRY(dev_alloc(&ctx->edge_start, nm + 1));
     TRY(dev_alloc(&ctx->path_tree, nm));
     TRY(dev_alloc(&ctx->path_stamp, nm));
     TRY(dev_alloc(&ctx->list[0], nm));
@@ -192,7 +195,7 @@ int mf_destroy(mf_ctx *ctx)
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->rank_off, ctx->rank_on, ctx->mem_on_sorted, ctx->mem_off_sorted, ctx->fit_len_on, ctx->fit_len_off, ctx->staged, ctx->type_segment, ctx->pairs_evaluated, ctx->feasible_pairs, ctx->largest_weight, ctx->wt, ctx->price,
-                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_frontier[0], ctx->path_frontier[1], ctx->path_stamp, ctx->path_held, ctx->path_base, ctx->path_tree, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
+                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_frontier[0], ctx->path_frontier[1], ctx->path_stamp, ctx->path_held, ctx->path_base, ctx->path_tree, ctx->edge_count, ctx->edge_start, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (ctx->h_stats) (void)hipHostFree(ctx->h_stats);
@@ -368,6 +371,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "path_pull")) { ctx->path_pull = value != 0; return MF_OK; }
     if (!strcmp(name, "path_frontier_rows")) { if (value < 8 || value > (1 << 20)) return MF_ERR_ARG; ctx->path_frontier_rows = (int)value; return MF_OK; }
     if (!strcmp(name, "path_width")) { if (value < 1 || value > (1 << 30)) return MF_ERR_ARG; ctx->path_width = (int)value; return MF_OK; }
+    if (!strcmp(name, "edge_lists_from")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->edge_lists_from = (int)value; return MF_OK; }
     if (!strcmp(name, "fit_prefix_below")) { if (value < 0 || value > 101) return MF_ERR_ARG; ctx->fit_prefix_below = (int)value; return MF_OK; }
     if (!strcmp(name, "fit_prefix")) { ctx->fit_prefix = value != 0; return MF_OK; }
     if (!strcmp(name, "fit_order")) { ctx->fit_order = value != 0; return MF_OK; }

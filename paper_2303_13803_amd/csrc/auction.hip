@@ -516,6 +516,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const int32_t *__restric
 }
 
 __global__ void known_weight_kernel(const int *largest, mf_device_stats *stats) { stats->max_weight = *largest; }
+__global__ void fill_counter_kernel(unsigned long long *counter) { *counter = 0ull; }
 
 // The largest weight alone (it sets the first epsilon), for solves that may never need W^T.
 __global__ __launch_bounds__(256) void max_weight_kernel(const int32_t *__restrict__ W, int n, int m, int64_t ldw,
@@ -572,6 +573,7 @@ void launch_round_shape(mf_ctx *ctx, const SideArgs &s, int count, int ring)
 
 void launch_round(mf_ctx *ctx, const SideArgs &s, int count, int ring)
 {
+    if (s.edge_start && count >= 2048) { mf_launch_list_round(ctx, s, count, ring); return; }
     switch (count >= 2048 ? ctx->bulk_shape : 0) {      // small rounds: one line per workgroup
     case 1: launch_round_shape<64, 4>(ctx, s, count, ring); break;
     case 2: launch_round_shape<64, 2>(ctx, s, count, ring); break;
@@ -720,6 +722,10 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     const double Kd = (double)K;
     const int nm = rm;
 
+    // A matrix the caller brings (no memory-ordered copy, no prefixes) may still be mostly
+    // infeasible pairs, in any pattern: its rows are then also kept as lists of feasible pairs.
+    const bool lists_possible = !candidate && !flip && !warm && ctx->edge_lists_from > 0 && n >= ctx->edge_lists_from &&
+                                ctx->fit_prefix_below > 0;
     MF_HIP(hipEventRecord(ctx->ev[3], ctx->stream));
     {
         // the largest weight sets the first epsilon
@@ -729,13 +735,18 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         // (when the matrix was scored here a moment ago its largest weight was noted on the way)
         if (candidate && ctx->largest_weight_known)
             hipLaunchKernelGGL(known_weight_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->largest_weight, ctx->stats);
-        else
+        else if (lists_possible) {
+            // the same pass also counts the feasible pairs of every row: with few of them the rounds read lists
+            hipLaunchKernelGGL(fill_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->feasible_pairs);
+            const int rc = mf_count_edges(ctx, d_W, n, m, ldw);
+            if (rc != MF_OK) return rc;
+        } else
             hipLaunchKernelGGL(max_weight_kernel, dim3(chunks, n < 1024 ? n : 1024), dim3(256), 0, ctx->stream, d_W, n,
                                m, ldw, ctx->stats);
         MF_HIP(hipGetLastError());
     }
     *ctx->h_feasible_pairs = ~0ull;
-    if (candidate)
+    if (candidate || lists_possible)
         MF_HIP(hipMemcpyAsync(ctx->h_feasible_pairs, ctx->feasible_pairs, sizeof(unsigned long long),
                               hipMemcpyDeviceToHost, ctx->stream));
     MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
@@ -776,10 +787,17 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     // with per-line lengths a scan reads, on average, the pairs that can share divided by the lines
     const double feasible = staged ? (double)*ctx->h_feasible_pairs : (double)n * (double)m;
     SideArgs fwd{A, (long long)lda, rm, ctx->price, ctx->colword, 0.0, Kd, flip ? len_cols : len_rows,
-                 (int)(feasible / (double)rn), nullptr, (long long)ldat, rn, flip ? len_rows : len_cols};
+                 (int)(feasible / (double)rn), nullptr, (long long)ldat, rn, flip ? len_rows : len_cols,
+                 nullptr, nullptr, nullptr};
     SideArgs rev{At, (long long)ldat, rn, ctx->profit, ctx->roword, 0.0, Kd, flip ? len_rows : len_cols,
-                 (int)(feasible / (double)rm), A, (long long)lda, rm, flip ? len_cols : len_rows};
+                 (int)(feasible / (double)rm), A, (long long)lda, rm, flip ? len_cols : len_rows,
+                 nullptr, nullptr, nullptr};
     if (flip) fwd.T = At;                       // (the other copy of the matrix: made on demand unless it is the one solved on)
+    if (lists_possible && (double)*ctx->h_feasible_pairs * 100.0 < (double)ctx->fit_prefix_below * (double)n * (double)m &&
+        *ctx->h_feasible_pairs + 4ull * (unsigned long long)n <= (unsigned long long)mf_edge_capacity(ctx)) {
+        const int rc = mf_build_edge_lists(ctx, d_W, n, m, ldw, &fwd);
+        if (rc != MF_OK) return rc;
+    }
 
     // The ladder of epsilons: divided by theta per phase down to 1.  Once epsilon is at most
     // final_jump weight units (final_jump * K in dual units) the next phase is the last one:

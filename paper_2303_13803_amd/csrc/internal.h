@@ -71,6 +71,9 @@ struct mf_ctx {
     int32_t *fit_len_on, *fit_len_off;   // per staged row / column: how many entries from the start can share
     unsigned long long *feasible_pairs, *h_feasible_pairs;    // how many pairs of the staged matrix can share (device, pinned)
     int fit_prefix_below;           // percent of pairs that can share below which the solve uses the staged matrix
+    int *edge_count;                // [max(max_n, max_m)] feasible pairs per row of a matrix the caller brought, padded to 4
+    long long *edge_start;          // [max(max_n, max_m) + 1] where each row's list starts
+    int edge_lists_from;            // rows from which such a matrix is turned into lists when few pairs are feasible (0: never)
     int staged_n, staged_m;         // shape of the staged matrix the solver may use (0: none)
     int *largest_weight;            // largest weight of the matrix just scored (device), noted while it was put in place
     bool largest_weight_known;      // ... and whether it is that of the matrix the staged copy belongs to
@@ -152,6 +155,11 @@ struct SideArgs {
     long long pitch_t;
     int len_t;                          // entries of a line of T = lines of A
     const int *line_len_t;              // optional, as line_len
+    // optional: every line of A once more as a list of its feasible entries (position, weight),
+    // list b at [edge_start[b], edge_start[b + 1]), both multiples of four, padding (0, infeasible)
+    const long long *edge_start;
+    const int *edge_col;
+    const int32_t *edge_weight;
 };
 
 // score.hip
@@ -165,6 +173,14 @@ int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *pred, const float *d_on, 
 int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
                   int32_t *d_row2col, int64_t *d_u, int64_t *d_v, mf_result *h_res,
                   bool warm, const int32_t *d_reset_cols, int n_reset_cols, bool may_use_staged);
+// edges.hip
+int mf_count_edges(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw);
+int mf_build_edge_lists(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw, SideArgs *side);
+void mf_launch_list_round(mf_ctx *ctx, const SideArgs &s, int count, int ring);
+inline size_t mf_edge_capacity(const mf_ctx *ctx)      // entries the lists may hold: half the staged copy's words each for columns and weights
+{
+    return ((size_t)ctx->max_n * ((((size_t)ctx->max_m + 3) & ~(size_t)3)) / 2) & ~(size_t)3;
+}
 // paths.hip
 int mf_launch_path_search(mf_ctx *ctx, const SideArgs &s, int ring);
 // certificate.hip

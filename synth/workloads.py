@@ -163,6 +163,28 @@ def uniform_matrix(seed, n, m, high, masked=0.0):
     return w
 
 
+def device_masked_matrix(seed, n, m, high, keep_one_in, device="cuda", pitch=None):
+    """uniform_matrix for cluster-sized shapes, drawn on the device: an int32 torch tensor [n, pitch]
+    (pitch >= m, default m rounded up to a multiple of four; padding columns hold -7) with weights
+    uniform in [0, high], of which one entry in `keep_one_in`, chosen independently per entry, stays
+    feasible.  Hundreds of millions of entries take minutes through the counter-based generator on
+    the host; the framework's seeded device generator draws them in a blink, and whoever needs the
+    matrix on the host copies it back, so both sides still see the same numbers."""
+    import torch
+    pitch = (m + 3) // 4 * 4 if pitch is None else pitch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    out = torch.full((n, pitch), -7, dtype=torch.int32, device=device)
+    step = max(1, (1 << 27) // max(m, 1))                       # about 128 M entries at a time
+    for i0 in range(0, n, step):
+        rows = min(step, n - i0)
+        w = torch.randint(0, int(high) + 1, (rows, m), generator=gen, device=device, dtype=torch.int32)
+        drop = torch.randint(0, int(keep_one_in), (rows, m), generator=gen, device=device, dtype=torch.int32) != 0
+        w[drop] = int(INFEASIBLE)
+        out[i0:i0 + rows, :m] = w
+    return out
+
+
 def permutation(seed, count, salt=0):
     """A seeded permutation of range(count)."""
     return np.argsort(rng.bits64(seed, rng.STREAM_PERM, count, offset=salt * count), kind="stable")

@@ -151,3 +151,25 @@ def test_cluster_scale_scoring_with_the_pair_dependent_sm_input(mm, orc):
     cols = np.sort(synth.permutation(20, m)[:64])
     _, Wc = orc.score_pairs(r["x_on"], r["x_off"][cols], full, S, sm=sm)
     assert_weights_close(Wg[:, cols], Wc, S, Wc != INF)
+
+
+def test_cluster_scale_matrix_with_an_arbitrary_mask(mm, orc):
+    """20,000 x 40,000 weights of which one pair in ten, in no pattern at all, may share: the caller
+    brings the matrix, the rounds with many bidders read per-row lists of the feasible pairs, and
+    the host re-checks the proof of optimality on the whole matrix."""
+    n, m = 20000, 40000
+    W = synth.device_masked_matrix(9, n, m, 2 ** 24, 10)
+    ctx = mm.Context(n, m)
+    r2c = torch.empty(n, dtype=torch.int32, device="cuda")
+    u = torch.empty(n, dtype=torch.int64, device="cuda")
+    v = torch.empty(m, dtype=torch.int64, device="cuda")
+    res = ctx.solve_assignment(W, n, m, r2c, u, v)
+    dense_bytes_of_first_rounds = 4.0 * n * m * res.phases
+    assert res.bytes_scanned < dense_bytes_of_first_rounds, "the rounds did not read the lists"
+    Wh = np.ascontiguousarray(W[:, :m].cpu().numpy())
+    ctx.close()
+    del W
+    torch.cuda.empty_cache()
+    assert abs((Wh == INF).mean() - 0.9) < 0.002
+    _check_certificate(orc, Wh, res, r2c.cpu().numpy(), u.cpu().numpy(), v.cpu().numpy())
+    assert res.fallbacks == 0
