@@ -82,6 +82,14 @@ typedef struct mf_ctx mf_ctx;
  * offline workload can use, enters layer 1 with weights d_W1sm[H] (the column
  * 2F of a [H][2F+1] first layer).  With d_W1sm NULL the two indices are ignored
  * and the SM share is whatever feature of the online workload carries it.
+ * Optional second constraint (paper: Section "Lessons and future direction",
+ * paragraph "Slowdown of online workloads": sharing must not slow the online
+ * workload down too much, and what "too much" is stays the operator's choice):
+ * with d_W3_slow not NULL the predictor has a second output unit on the same
+ * hidden layers, logistic(d_W3_slow . h2 + d_b3_slow), read as the predicted
+ * slowdown of the online workload of the pair as a fraction in (0, 1); a pair
+ * whose prediction exceeds slow_limit is infeasible like one that does not fit
+ * in memory.
  * All parameter pointers are DEVICE pointers to float32, row-major.
  */
 typedef struct {
@@ -99,6 +107,9 @@ typedef struct {
     const float *d_W1sm;        /* [H] or NULL: weights of the pair-dependent SM input  */
     int32_t sm_on_feature;      /* online feature: SM activity of the online workload   */
     int32_t sm_off_feature;     /* offline feature: SM share the offline one can use    */
+    const float *d_W3_slow;     /* [H] or NULL: output weights of the slowdown unit     */
+    const float *d_b3_slow;     /* [1]  (with d_W3_slow)                                */
+    float   slow_limit;         /* pairs predicted above it are infeasible              */
 } mf_predictor;
 
 /* Filled on the host by the solving calls. */

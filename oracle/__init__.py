@@ -49,13 +49,26 @@ def threads():
     return int(lib().orc_threads())
 
 
-def score_pairs(x_on, x_off, params, scale, mem_feature=0, mem_limit=1.0, wide=True, nthreads=0, sm=None):
+def score_pairs(x_on, x_off, params, scale, mem_feature=0, mem_limit=1.0, wide=True, nthreads=0, sm=None,
+                slow_limit=None):
     """Scores and quantised weights for every (online, offline) pair.
 
     sm = (online feature, offline feature): the SM share depends on the pair,
     sm(u, v) = min(1 - x_u[online feature], x_v[offline feature]), and is a third input of the
     predictor; params["W1"] then has 2F + 1 columns.
+    slow_limit: the predictor has a second output unit, params["W3slow"], params["b3slow"], on the
+    same hidden layers: the predicted slowdown of the pair's online workload (paper: Section
+    "Lessons and future direction", the threshold on the online workloads' degradation); pairs
+    predicted above slow_limit are infeasible.  It is the scorer run once more with that unit's
+    output weights, then a comparison.
     Returns (sigma float32 [n,m], W int32 [n,m]); masked pairs hold INFEASIBLE in W."""
+    if slow_limit is not None:
+        main = {k: v for k, v in params.items() if k not in ("W3slow", "b3slow")}
+        unit = dict(main, W3=params["W3slow"], b3=params["b3slow"])
+        sigma, w = score_pairs(x_on, x_off, main, scale, mem_feature, mem_limit, wide, nthreads, sm)
+        slow = score_pairs(x_on, x_off, unit, scale, mem_feature, mem_limit, wide, nthreads, sm)[0]
+        w[slow > np.float32(slow_limit)] = INFEASIBLE
+        return sigma, w
     x_on = np.ascontiguousarray(x_on, np.float32)
     x_off = np.ascontiguousarray(x_off, np.float32)
     n, F = x_on.shape

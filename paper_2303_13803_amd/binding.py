@@ -32,7 +32,8 @@ class Predictor(C.Structure):
                 ("mem_feature", C.c_int32), ("mem_limit", C.c_float),
                 ("d_W1", C.c_void_p), ("d_b1", C.c_void_p), ("d_W2", C.c_void_p),
                 ("d_b2", C.c_void_p), ("d_W3", C.c_void_p), ("d_b3", C.c_void_p),
-                ("d_W1sm", C.c_void_p), ("sm_on_feature", C.c_int32), ("sm_off_feature", C.c_int32)]
+                ("d_W1sm", C.c_void_p), ("sm_on_feature", C.c_int32), ("sm_off_feature", C.c_int32),
+                ("d_W3_slow", C.c_void_p), ("d_b3_slow", C.c_void_p), ("slow_limit", C.c_float)]
 
 
 class Result(C.Structure):
@@ -133,16 +134,20 @@ class Context:
             raise MuxmatchError(rc, detail)
         return rc
 
-    def predictor(self, params, scale, mem_feature=0, mem_limit=1.0, sm=None):
+    def predictor(self, params, scale, mem_feature=0, mem_limit=1.0, sm=None, slow_limit=None):
         """params: dict of float32 device tensors W1 [H,2F], b1, W2 [H,H], b2, W3 [H], b3 [1];
         with sm = (online feature, offline feature) also W1sm [H], the weights of the
-        pair-dependent SM input."""
+        pair-dependent SM input; with slow_limit also W3slow [H], b3slow [1], the second output
+        unit that predicts the online workload's slowdown (pairs above slow_limit are infeasible)."""
         H = params["b1"].numel()
         F = params["W1"].shape[1] // 2
         p = Predictor(F, H, float(scale), int(mem_feature), float(mem_limit),
                       *[_ptr(params[k], torch.float32) for k in ("W1", "b1", "W2", "b2", "W3", "b3")],
                       _ptr(params["W1sm"], torch.float32) if sm is not None else None,
-                      0 if sm is None else int(sm[0]), 0 if sm is None else int(sm[1]))
+                      0 if sm is None else int(sm[0]), 0 if sm is None else int(sm[1]),
+                      _ptr(params["W3slow"], torch.float32) if slow_limit is not None else None,
+                      _ptr(params["b3slow"], torch.float32) if slow_limit is not None else None,
+                      0.0 if slow_limit is None else float(slow_limit))
         p._keep = params
         return p
 

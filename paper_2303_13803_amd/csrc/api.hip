@@ -27,6 +27,7 @@ int check_predictor(const mf_predictor *p)
     if (!(p->scale > 0.0f) || p->scale > 1073741824.0f) return MF_ERR_ARG;
     if (p->mem_feature < 0 || p->mem_feature >= p->F) return MF_ERR_ARG;
     if (!aligned16(p->d_W2) || !aligned16(p->d_b2) || !aligned16(p->d_W3)) return MF_ERR_ARG;
+    if (p->d_W3_slow && (!aligned16(p->d_W3_slow) || !p->d_b3_slow || !(p->slow_limit == p->slow_limit))) return MF_ERR_ARG;
     if (p->d_W1sm && (!aligned16(p->d_W1sm) || p->sm_on_feature < 0 || p->sm_on_feature >= p->F ||
                       p->sm_off_feature < 0 || p->sm_off_feature >= p->F))
         return MF_ERR_ARG;
@@ -43,6 +44,7 @@ int check_predictors(const mf_predictor *preds, int n_types)
         if (preds[t].F != preds[0].F || preds[t].mem_feature != preds[0].mem_feature ||
             preds[t].mem_limit != preds[0].mem_limit || preds[t].scale != preds[0].scale ||
             (preds[t].d_W1sm != nullptr) != (preds[0].d_W1sm != nullptr) ||
+            (preds[t].d_W3_slow != nullptr) != (preds[0].d_W3_slow != nullptr) ||
             (preds[0].d_W1sm && (preds[t].sm_on_feature != preds[0].sm_on_feature ||
                                  preds[t].sm_off_feature != preds[0].sm_off_feature)))
             return MF_ERR_ARG;

@@ -265,7 +265,7 @@ template <int H> struct PairShape {
     static constexpr int ROWS = 64;                        // online rows per workgroup
     static constexpr int KS = H / 2;                       // k-steps of the 32x32x2 tile
     static constexpr int MB = H / 32;                      // 32-row blocks of the hidden layer
-    static constexpr size_t LDS_BYTES = sizeof(float) * ((size_t)H * H + (size_t)ROWS * H + 3 * H + 2 * ROWS);
+    static constexpr size_t LDS_BYTES = sizeof(float) * ((size_t)H * H + (size_t)ROWS * H + 4 * H + 2 * ROWS);
 };
 
 // One wavefront owns 32 offline columns (lane & 31) and walks down the online
@@ -279,7 +279,9 @@ template <int H> struct PairShape {
 // D[8*(r/4) + 4*(l/32) + r%4][l%32].
 // PAIR_SM: the predictor has a third input, the SM share of the pair
 // min(1 - sm_on[i], sm_off[j]); its layer-1 weights w_sm[H] add w_sm[k] * share to hidden unit k.
-template <int H, bool PAIR_SM>
+// SLOWDOWN: a second output unit on the same hidden layers (weights w3_slow[H], b3_slow) predicts
+// how much the online workload of the pair slows down; a pair above slow_limit is infeasible.
+template <int H, bool PAIR_SM, bool SLOWDOWN>
 __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     const float *__restrict__ P_on, const float *__restrict__ P_off,
     const float *__restrict__ W2, const float *__restrict__ b2, const float *__restrict__ W3,
@@ -288,7 +290,8 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     int32_t *__restrict__ W, int64_t ldw, float *__restrict__ sigma,
     const int32_t *__restrict__ row_map, const int32_t *__restrict__ col_map, int by_memory,
     unsigned long long *__restrict__ evaluated, const int32_t *__restrict__ segment,
-    const float *__restrict__ w_sm, const float *__restrict__ sm_on, const float *__restrict__ sm_off)
+    const float *__restrict__ w_sm, const float *__restrict__ sm_on, const float *__restrict__ sm_off,
+    const float *__restrict__ w3_slow, const float *__restrict__ b3_slow, float slow_limit)
 {
     using S = PairShape<H>;
     constexpr int KS = S::KS, MB = S::MB, ROWS = S::ROWS, Q = KS / 4;
@@ -300,6 +303,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     float *mon_lds = w3_lds + H;                           // [ROWS] memory fraction of the tile's rows
     float *wsm_lds = mon_lds + ROWS;                       // [H] layer-1 weights of the SM share
     float *son_lds = wsm_lds + H;                          // [ROWS] 1 - SM activity of the tile's rows
+    float *w3s_lds = son_lds + ROWS;                       // [H] output weights of the slowdown unit
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hh = lane >> 5, nn = lane & 31;
@@ -338,6 +342,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
         if (tid < H) wsm_lds[tid] = w_sm[tid];
         if (tid < nrows) son_lds[tid] = 1.0f - sm_on[row_map ? row_map[row0 + tid] : row0 + tid];
     }
+    if (SLOWDOWN && tid < H) w3s_lds[tid] = w3_slow[tid];
     __syncthreads();
     if (j0 >= m) return;
 
@@ -352,6 +357,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     const float moff = mem_off[jc];
     const float soff = PAIR_SM ? sm_off[jc] : 0.0f;
     const float bias3 = b3[0];
+    const float bias3_slow = SLOWDOWN ? b3_slow[0] : 0.0f;
     // by_memory: the maps list rows and columns by ascending memory fraction, so this
     // wavefront's first column has its smallest one, and once a row does not fit next to
     // that column (float addition is monotone) no later row of the tile fits any of its columns
@@ -448,13 +454,29 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
                 }
             const float z = zp + __shfl_xor(zp, 32) + bias3;
             const float sg = 1.0f / (1.0f + expf(-z));
+            bool too_slow = false;
+            if (SLOWDOWN) {                 // the same output layer once more with the other unit's weights
+                float sp = 0.0f;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        float4 wv = *(const float4 *)(w3s_lds + mb * 32 + 8 * g + 4 * hh);
+                        sp = fmaf(wv.x, fmaxf(acc[x][mb][4 * g], 0.0f), sp);
+                        sp = fmaf(wv.y, fmaxf(acc[x][mb][4 * g + 1], 0.0f), sp);
+                        sp = fmaf(wv.z, fmaxf(acc[x][mb][4 * g + 2], 0.0f), sp);
+                        sp = fmaf(wv.w, fmaxf(acc[x][mb][4 * g + 3], 0.0f), sp);
+                    }
+                const float zs = sp + __shfl_xor(sp, 32) + bias3_slow;
+                too_slow = 1.0f / (1.0f + expf(-zs)) > slow_limit;
+            }
             if (hh == 0 && j < m) {
                 const int i = row_map ? row_map[row0 + r + x] : row0 + r + x;
                 float qv = rintf(sg * scale);
                 qv = fminf(fmaxf(qv, 0.0f), scale);
                 int32_t w = (int32_t)qv;
                 const float memsum = mon_lds[r + x] + moff;
-                if (memsum > mem_limit) w = MF_INFEASIBLE;
+                if (memsum > mem_limit || too_slow) w = MF_INFEASIBLE;
                 if (by_memory) {
                     // the staged matrix: rows and columns both in memory order, one whole line per wave
                     W[(size_t)(staged_row0 + row0 + r + x) * ldw + j] = w;
@@ -479,26 +501,27 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     if (evaluated && lane == 0 && r > 0) atomicAdd(evaluated, (unsigned long long)r * (unsigned)min(32, m - j0));
 }
 
-template <int H, bool PAIR_SM>
+template <int H, bool PAIR_SM, bool SLOWDOWN>
 int launch_pair_variant(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
                         float *d_sigma, const int32_t *row_map, const int32_t *col_map, bool by_memory,
                         const int32_t *segment, int grid_rows)
 {
     using S = PairShape<H>;
     // (the attribute belongs to the device, so what has been set is remembered per context)
-    const unsigned flag = 1u << ((H == 128 ? 2 : 0) + (PAIR_SM ? 1 : 0));
+    const unsigned flag = 1u << (5 + (H == 128 ? 4 : 0) + (PAIR_SM ? 2 : 0) + (SLOWDOWN ? 1 : 0));
     if (!(ctx->kernels_configured & flag)) {
-        MF_HIP(hipFuncSetAttribute((const void *)pair_mlp_kernel<H, PAIR_SM>,
+        MF_HIP(hipFuncSetAttribute((const void *)pair_mlp_kernel<H, PAIR_SM, SLOWDOWN>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS_BYTES));
         ctx->kernels_configured |= flag;
     }
     // x covers the rows this launch scores (a segment of the row map, or all n), padded to a
     // multiple of 8: every XCD then meets the same row tiles for each column tile
     dim3 grid((((grid_rows + S::ROWS - 1) / S::ROWS) + 7) & ~7, (m + PAIR_COLS - 1) / PAIR_COLS);
-    hipLaunchKernelGGL((pair_mlp_kernel<H, PAIR_SM>), grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
+    hipLaunchKernelGGL((pair_mlp_kernel<H, PAIR_SM, SLOWDOWN>), grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
                        ctx->proj_on, ctx->proj_off, p->d_W2, p->d_b2, p->d_W3, p->d_b3,
                        ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma, row_map, col_map,
-                       by_memory ? 1 : 0, ctx->pairs_evaluated, segment, p->d_W1sm, ctx->sm_on, ctx->sm_off);
+                       by_memory ? 1 : 0, ctx->pairs_evaluated, segment, p->d_W1sm, ctx->sm_on, ctx->sm_off,
+                       p->d_W3_slow, p->d_b3_slow, p->slow_limit);
     MF_HIP(hipGetLastError());
     return MF_OK;
 }
@@ -509,8 +532,11 @@ int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, 
                 const int32_t *segment = nullptr, int segment_rows = -1)
 {
     const int grid_rows = segment_rows >= 0 ? segment_rows : n;
-    return p->d_W1sm ? launch_pair_variant<H, true>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows)
-                     : launch_pair_variant<H, false>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows);
+    if (p->d_W3_slow)
+        return p->d_W1sm ? launch_pair_variant<H, true, true>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows)
+                         : launch_pair_variant<H, false, true>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows);
+    return p->d_W1sm ? launch_pair_variant<H, true, false>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows)
+                     : launch_pair_variant<H, false, false>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows);
 }
 
 // order[k] = the workload with the k-th smallest (group, key); rank[i] = its position k

@@ -18,6 +18,7 @@ _GOLD = np.uint64(0x9E3779B97F4A7C15)
 STREAM_X_ON, STREAM_X_OFF = 0, 1
 STREAM_W1, STREAM_B1, STREAM_W2, STREAM_B2, STREAM_W3, STREAM_B3 = 2, 3, 4, 5, 6, 7
 STREAM_MIXTURE, STREAM_MATRIX, STREAM_MASK, STREAM_PERM, STREAM_TYPE, STREAM_SM = 8, 9, 10, 11, 12, 13
+STREAM_SLOW = 14
 
 
 def _mix(z):

@@ -117,6 +117,18 @@ def with_sm_input(params, seed):
     return out
 
 
+def with_slowdown_unit(params, seed):
+    """The same predictor with a second output unit on the same hidden layers (the predicted
+    slowdown of the online workload): W3slow [H], b3slow [1], drawn like W3 and b3."""
+    H = params["W3"].shape[0]
+    a = np.sqrt(6.0 / (H + 1))
+    u = rng.uniform53(seed, rng.STREAM_SLOW, H + 1)
+    out = dict(params)
+    out["W3slow"] = ((2.0 * u[:H] - 1.0) * a).astype(np.float32)
+    out["b3slow"] = ((2.0 * u[H:] - 1.0) * 0.1).astype(np.float32)
+    return out
+
+
 def gpu_types(seed, n, n_types):
     """GPU type of each online workload's device: type t has a share proportional to 1/(t+1)
     (a cluster holds a few GPU generations in uneven numbers).  Returns int32 [n]."""

@@ -169,3 +169,44 @@ def test_pair_dependent_sm_input(orc):
     np.testing.assert_allclose(got.astype(np.float64), ref, rtol=1e-7)
     with pytest.raises(ValueError):
         orc.score_pairs(x_on, x_off, pp, S, sm=(2, F))
+
+
+def test_slowdown_unit_masks_pairs(orc):
+    """Pins the second output unit: logistic(W3slow . h2 + b3slow) on the same hidden layers, pairs
+    above the limit infeasible, everything else untouched."""
+    F, H, S = 6, 8, float(2 ** 20)
+    x_on = synth.uniform_features(6, 0, 12, F); x_off = synth.uniform_features(6, 1, 17, F)
+    base = synth.predictor_params(6, F, H)
+    s_plain, w_plain = orc.score_pairs(x_on, x_off, base, S)
+    # (i) a zero unit predicts 1/2 for every pair: the limit decides for all of them at once
+    p0 = synth.with_slowdown_unit(base, 6); p0["W3slow"][:] = 0.0; p0["b3slow"][:] = 0.0
+    s_hi, w_hi = orc.score_pairs(x_on, x_off, p0, S, slow_limit=0.5)         # 1/2 > 1/2 is false
+    assert (s_hi == s_plain).all() and (w_hi == w_plain).all()
+    s_lo, w_lo = orc.score_pairs(x_on, x_off, p0, S, slow_limit=0.4999)
+    assert (s_lo == s_plain).all() and (w_lo == INF).all()
+    # (ii) black box: a float64 library MLP with two output units
+    pp = synth.with_slowdown_unit(base, 8); pp["W3slow"] *= 3.0
+    limit = 0.5
+    sig, w = orc.score_pairs(x_on, x_off, pp, S, slow_limit=limit)
+    lin1 = torch.nn.Linear(2 * F, H, dtype=torch.float64); lin2 = torch.nn.Linear(H, H, dtype=torch.float64)
+    lin3 = torch.nn.Linear(H, 2, dtype=torch.float64)
+    with torch.no_grad():
+        lin1.weight.copy_(torch.from_numpy(pp["W1"]).double()); lin1.bias.copy_(torch.from_numpy(pp["b1"]).double())
+        lin2.weight.copy_(torch.from_numpy(pp["W2"]).double()); lin2.bias.copy_(torch.from_numpy(pp["b2"]).double())
+        lin3.weight.copy_(torch.from_numpy(np.stack([pp["W3"], pp["W3slow"]])).double())
+        lin3.bias.copy_(torch.from_numpy(np.concatenate([pp["b3"], pp["b3slow"]])).double())
+        net = torch.nn.Sequential(lin1, torch.nn.ReLU(), lin2, torch.nn.ReLU(), lin3, torch.nn.Sigmoid())
+        xo = torch.from_numpy(x_on).double(); xf = torch.from_numpy(x_off).double()
+        pairs = torch.cat([xo[:, None, :].expand(-1, 17, -1), xf[None, :, :].expand(12, -1, -1)], dim=2)
+        ref = net(pairs).numpy()
+    np.testing.assert_allclose(sig.astype(np.float64), ref[..., 0], rtol=1e-7)
+    clear = np.abs(ref[..., 1] - limit) > 1e-6                # away from the limit both sides must agree
+    too_slow = ref[..., 1] > limit
+    assert too_slow.any() and (~too_slow).any()
+    assert ((w == INF) == (too_slow | (w_plain == INF)))[clear].all()
+    keep = (w != INF)
+    assert (w[keep] == w_plain[keep]).all()                   # surviving pairs keep their weights
+    # (iii) the memory mask and the slowdown mask add up
+    tight, w_mem = orc.score_pairs(x_on, x_off, base, S, mem_feature=0, mem_limit=0.8)
+    _, w_both = orc.score_pairs(x_on, x_off, pp, S, mem_feature=0, mem_limit=0.8, slow_limit=limit)
+    assert (w_mem == INF).any() and ((w_both == INF) == ((w_mem == INF) | (w == INF))).all()
