@@ -96,6 +96,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->theta = 24;
     ctx->max_rounds = 4000000000ll;
     ctx->tail_max = 1024;
+    ctx->round_lag = 1;
     ctx->phase_stop = 16;
     ctx->phase_keep = 4;
     ctx->phase_growth = 1;
@@ -179,6 +180,10 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->stats, 1));
     TRY(dev_alloc(&ctx->cert, 1));
     TRY(hipHostMalloc((void **)&ctx->h_stats, sizeof(mf_device_stats)));
+    for (int i = 0; i < 2; ++i) {
+        TRY(hipHostMalloc((void **)&ctx->h_stats_slot[i], sizeof(mf_device_stats)));
+        TRY(hipEventCreate(&ctx->ev_stats[i]));
+    }
     TRY(hipHostMalloc((void **)&ctx->h_cert, sizeof(mf_cert_out)));
     for (int i = 0; i < 10; ++i) TRY(hipEventCreate(&ctx->ev[i]));
 #undef TRY
@@ -201,6 +206,10 @@ int mf_destroy(mf_ctx *ctx)
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (ctx->h_stats) (void)hipHostFree(ctx->h_stats);
+    for (int i = 0; i < 2; ++i) {
+        if (ctx->h_stats_slot[i]) (void)hipHostFree(ctx->h_stats_slot[i]);
+        if (ctx->ev_stats[i]) (void)hipEventDestroy(ctx->ev_stats[i]);
+    }
     if (ctx->h_cert) (void)hipHostFree(ctx->h_cert);
     if (ctx->h_pairs_evaluated) (void)hipHostFree(ctx->h_pairs_evaluated);
     if (ctx->h_feasible_pairs) (void)hipHostFree(ctx->h_feasible_pairs);
@@ -355,6 +364,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "final_jump")) { if (value < 0 || value > (1 << 30)) return MF_ERR_ARG; ctx->final_jump = value; return MF_OK; }
     if (!strcmp(name, "phase_growth")) { if (value < 1 || value > 64) return MF_ERR_ARG; ctx->phase_growth = (int)value; return MF_OK; }
     if (!strcmp(name, "phase_stop")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->phase_stop = (int)value; return MF_OK; }
+    if (!strcmp(name, "round_lag")) { if (value < 0 || value > 1) return MF_ERR_ARG; ctx->round_lag = (int)value; return MF_OK; }
     if (!strcmp(name, "tail_max")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->tail_max = (int)value; return MF_OK; }
     if (!strcmp(name, "bulk_grid")) { if (value < 0 || value > 8192) return MF_ERR_ARG; ctx->bulk_grid = (int)value; return MF_OK; }
     if (!strcmp(name, "bulk_shape")) { if (value < 0 || value > 4) return MF_ERR_ARG; ctx->bulk_shape = (int)value; return MF_OK; }

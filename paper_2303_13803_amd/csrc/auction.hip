@@ -595,11 +595,50 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
     int idle_launches = 0;
     long long tail_steps = 0;               // dependent steps of the chain kernels of this run, longest workgroup of each
     *left_over = count;
+    // Bulk rounds do not wait for their own outcome: the next round is launched for at most as many
+    // bidders as the last count the host has seen (a round never leaves more bidders than it
+    // found: each bid displaces at most one holder), the kernel reads the true count on the
+    // device, and the host reads the count of a round while the one after it runs.  `unread` says
+    // that such a round is in flight; every other kind of launch waits for the exact count first.
+    bool unread = false;
+    int unread_ring = 0, unread_slot = 0, slot = 0;
+    bool counted_teams = false, chained = false;
+    unsigned long long bids_before = ctx->h_stats->bids;
+    // takes in the statistics copied after the launch that left the lists at position `at`
+    auto absorb = [&](int at) -> int {
+        if ((long long)ctx->h_stats->bids == (long long)bids_before && ctx->h_stats->cnt[at & 3] >= count) {
+            // a launch that neither evaluated a bid nor placed anybody must not repeat for ever
+            if (++idle_launches > 64) return MF_ERR_NOT_CONVERGED;
+        } else idle_launches = 0;
+        bids_before = ctx->h_stats->bids;
+        count = ctx->h_stats->cnt[at & 3];
+        if (counted_teams) team_steps += (long long)ctx->h_stats->launch_max;     // the longest any leader went
+        if (chained) tail_steps += (long long)ctx->h_stats->launch_max;
+        // a bounded wait ran out: one workgroup per chain, or no more searches, for the rest of this solve
+        if (ctx->h_stats->team_abort == 1) { ctx->team_off = true; ctx->fallbacks |= MF_FALLBACK_TEAMS; }
+        if (ctx->h_stats->team_abort == 2) { ctx->path_off = true; ctx->fallbacks |= MF_FALLBACK_SEARCHES; }
+        *left_over = count;
+        return MF_OK;
+    };
+    auto read_unread = [&]() -> int {
+        MF_HIP(hipEventSynchronize(ctx->ev_stats[unread_slot]));
+        *ctx->h_stats = *ctx->h_stats_slot[unread_slot];
+        unread = false;
+        return absorb(unread_ring);
+    };
     while (count > stop_at) {
         // a side that only prepares prices (stop_at > 0) does not follow chains for ever
         if (stop_at > 0 && tail_budget > 0 && tail_steps >= tail_budget) break;
-        bool timed = false, counted_teams = false, chained = false;
-        const unsigned long long bytes_before = ctx->h_stats->bytes + ctx->h_stats->round_bytes, bids_before = ctx->h_stats->bids;
+        const bool bulk = count > ctx->tail_max;
+        if (unread && !bulk) {
+            // chains, teams and searches are laid out for the exact number of bidders
+            const int rc = read_unread();
+            if (rc != MF_OK) return rc;
+            continue;
+        }
+        bool timed = false;
+        counted_teams = false; chained = false;
+        const unsigned long long bytes_before = ctx->h_stats->bytes + ctx->h_stats->round_bytes;
         const bool paths_ok = ctx->path_max > 0 && !ctx->path_off && ctx->n_cus > 0;
         const bool teams_ok = ctx->team_max > 0 && !ctx->team_off;
         const int cus = ctx->n_cus > 0 ? ctx->n_cus : 256;
@@ -611,7 +650,7 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
         if (team_from * 2 > cus) team_from = cus / 2;
         const long long left = ctx->max_rounds - (long long)ctx->h_stats->bids;
         if (left <= 0) return MF_ERR_NOT_CONVERGED;
-        if (count > ctx->tail_max) {
+        if (bulk) {
             const int batch = (count > 4096 || time_first) ? 1 : 3;     // the timed round stands alone
             for (int r = 0; r < batch; ++r) {
                 if (time_first && r == 0) { MF_HIP(hipEventRecord(ctx->ev[6], ctx->stream)); timed = true; }
@@ -670,8 +709,22 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
             ++ring;
         }
         MF_HIP(hipGetLastError());
+        if (bulk && !timed && ctx->round_lag && count > 4096) {     // (smaller rounds go three to a read, above)
+            MF_HIP(hipMemcpyAsync(ctx->h_stats_slot[slot], ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
+            MF_HIP(hipEventRecord(ctx->ev_stats[slot], ctx->stream));
+            if (unread) {
+                const int rc = read_unread();           // the round before this one, while this one runs
+                if (rc != MF_OK) return rc;
+            }
+            unread = true;
+            unread_ring = ring;
+            unread_slot = slot;
+            slot ^= 1;
+            continue;
+        }
         MF_HIP(hipMemcpyAsync(ctx->h_stats, ctx->stats, sizeof(mf_device_stats), hipMemcpyDeviceToHost, ctx->stream));
         MF_HIP(hipStreamSynchronize(ctx->stream));
+        unread = false;                                  // (a later copy on the same stream: it covers the round in flight too)
         if (timed) {
             float ms = 0.0f;
             MF_HIP(hipEventElapsedTime(&ms, ctx->ev[6], ctx->ev[7]));
@@ -680,17 +733,12 @@ int run_side(mf_ctx *ctx, const SideArgs &s, int count, bool time_first, int sto
             ctx->timings[T_BID_BULK_BYTES] += (float)((double)(ctx->h_stats->bytes + ctx->h_stats->round_bytes - bytes_before));
         }
         time_first = false;
-        // a launch that neither evaluated a bid nor placed anybody must not repeat for ever
-        if ((long long)ctx->h_stats->bids == (long long)bids_before && ctx->h_stats->cnt[ring & 3] >= count) {
-            if (++idle_launches > 64) return MF_ERR_NOT_CONVERGED;
-        } else idle_launches = 0;
-        count = ctx->h_stats->cnt[ring & 3];
-        if (counted_teams) team_steps += (long long)ctx->h_stats->launch_max;     // the longest any leader went
-        if (chained) tail_steps += (long long)ctx->h_stats->launch_max;
-        // a bounded wait ran out: one workgroup per chain, or no more searches, for the rest of this solve
-        if (ctx->h_stats->team_abort == 1) { ctx->team_off = true; ctx->fallbacks |= MF_FALLBACK_TEAMS; }
-        if (ctx->h_stats->team_abort == 2) { ctx->path_off = true; ctx->fallbacks |= MF_FALLBACK_SEARCHES; }
-        *left_over = count;
+        const int rc = absorb(ring);
+        if (rc != MF_OK) return rc;
+    }
+    if (unread) {
+        const int rc = read_unread();
+        if (rc != MF_OK) return rc;
     }
     return MF_OK;
 }

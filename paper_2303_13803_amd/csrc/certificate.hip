@@ -44,8 +44,12 @@ __global__ __launch_bounds__(NT) void duals_kernel(
 // (min reduced cost), primal and dual totals.
 // K32: K fits a signed 32-bit integer, so K*w is one 32 x 32 -> 64-bit multiply-add.
 // A workgroup takes CERT_ROWS rows at a time: each column dual (8 bytes, against 4 for a weight)
-// is loaded once for all of them.
-constexpr int CERT_ROWS = 4;
+// is loaded once for all of them.  The grid is capped at what the chip holds at once (8 workgroups
+// on each of 256 compute units) and every workgroup walks over its share of the rows: measured on
+// a 20,000 x 20,000 matrix the scan then runs at 0.70-0.73 of the HBM peak, against 0.60 with one
+// workgroup per group of rows.
+constexpr int CERT_ROWS = 8;
+constexpr int CERT_GRID = 2048;
 
 template <bool K32>
 __global__ __launch_bounds__(BID_THREADS) void certificate_kernel(
@@ -54,7 +58,7 @@ __global__ __launch_bounds__(BID_THREADS) void certificate_kernel(
     mf_cert_out *out)
 {
     __shared__ long long red[BID_THREADS / 64];
-    constexpr int UN = 2;               // column groups of four in flight per thread
+    constexpr int UN = 1;               // column groups of four in flight per thread
     long long dual_part = 0, primal_part = 0;
     int flags = 0, matched = 0;
     long long min_rc = INT64_MAX;
@@ -187,7 +191,7 @@ int mf_run_certificate(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ld
 {
     hipLaunchKernelGGL(init_cert_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->cert);
     hipLaunchKernelGGL(fill_int_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, ctx->colmark, m, 0);
-    const int groups = (n + CERT_ROWS - 1) / CERT_ROWS, grid = groups < MAX_GRID ? groups : MAX_GRID;
+    const int groups = (n + CERT_ROWS - 1) / CERT_ROWS, grid = groups < CERT_GRID ? groups : CERT_GRID;
     hipLaunchKernelGGL(K >= INT32_MIN && K <= INT32_MAX ? certificate_kernel<true> : certificate_kernel<false>,
                        dim3(grid), dim3(BID_THREADS), 0, ctx->stream, d_W, ldw, n, m,
                        d_row2col, d_u, d_v, (long long)K, ctx->colmark, ctx->cert);
@@ -294,7 +298,7 @@ extern "C" int mf_check_certificate_noalloc(void *hip_stream, const int32_t *d_W
     // the array keeps what the previous call left: both parts are cleared by a kernel (no
     // memset node, so the sequence can be captured into a graph)
     hipLaunchKernelGGL(noalloc_begin_kernel, dim3((m + 255) / 256), dim3(256), 0, stream, out, colmark, m);
-    const int groups = (n + CERT_ROWS - 1) / CERT_ROWS, grid = groups < MAX_GRID ? groups : MAX_GRID;
+    const int groups = (n + CERT_ROWS - 1) / CERT_ROWS, grid = groups < CERT_GRID ? groups : CERT_GRID;
     hipLaunchKernelGGL(K <= INT32_MAX ? certificate_kernel<true> : certificate_kernel<false>, dim3(grid),
                        dim3(BID_THREADS), 0, stream, d_W, ldw, n, m, d_row2col, d_u, d_v, (long long)K, colmark, out);
     hipLaunchKernelGGL(noalloc_finish_kernel, dim3(1), dim3(1), 0, stream, out, (long long)K, d_out);

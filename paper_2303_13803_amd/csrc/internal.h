@@ -130,6 +130,9 @@ struct mf_ctx {
     mf_cert_out *cert;
     // pinned host mirrors
     mf_device_stats *h_stats;
+    mf_device_stats *h_stats_slot[2];   // pinned: where the counts of bulk rounds land while the next round runs
+    hipEvent_t ev_stats[2];
+    int round_lag;                      // 1: bulk rounds are launched one ahead of the host's reads
     mf_cert_out *h_cert;
     // options
     int64_t theta, max_rounds;
