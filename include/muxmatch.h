@@ -293,6 +293,9 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
  *   "fit_prefix"       1 (default) / 0: allow mf_schedule_round to match on the context's
  *                      memory-ordered copy of the matrix, reading only each line's feasible prefix
  *   "fit_prefix_below" percent (default 50): ... when fewer of the pairs just scored can share; 0: never
+ *   "edge_lists_from"  rows (default 4096) from which mf_solve_assignment keeps a matrix with fewer
+ *                      than fit_prefix_below percent of feasible pairs also as per-row lists of
+ *                      them, which its bidding rounds then read instead of whole rows; 0: never
  *   "warm_eps_units"   0 (default): mf_schedule_round_update matches from scratch; > 0: from the
  *                      previous prices at that epsilon, in weight units
  *   "warm_reset_cols"  1 (default): such a start takes replaced columns at price 0
