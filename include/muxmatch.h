@@ -288,6 +288,10 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
  * STABLE (what they mean will not change):
  *   "theta"            epsilon divisor per phase of the matching, 2..1024, default 24
  *   "max_rounds"       limit on evaluated bids per solve (MF_ERR_NOT_CONVERGED beyond), default 4e9
+ *   "score_split"      1 (default): the scorer's hidden layer multiplies fp16 pieces of its fp32
+ *                      operands (two pieces each, three products, fp32 accumulation: the scores
+ *                      stay as close to an fp64 evaluation as with fp32 products, about 3e-7
+ *                      relative, at a third of the time); 0: fp32 products
  *   "fit_order"        1 (default): scoring walks workloads in order of memory fraction and runs no
  *                      MLP for pairs that cannot fit; 0: every pair goes through the MLP
  *   "fit_prefix"       1 (default) / 0: allow mf_schedule_round to match on the context's

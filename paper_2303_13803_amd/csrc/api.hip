@@ -97,6 +97,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->max_rounds = 4000000000ll;
     ctx->tail_max = 1024;
     ctx->round_lag = 1;
+    ctx->score_split = 1;
     ctx->phase_stop = 16;
     ctx->phase_keep = 4;
     ctx->phase_growth = 1;
@@ -179,6 +180,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->colmark, (size_t)max_m));
     TRY(dev_alloc(&ctx->stats, 1));
     TRY(dev_alloc(&ctx->cert, 1));
+    TRY(hipMalloc((void **)&ctx->score_range, 8 * sizeof(unsigned)));
     TRY(hipHostMalloc((void **)&ctx->h_stats, sizeof(mf_device_stats)));
     for (int i = 0; i < 2; ++i) {
         TRY(hipHostMalloc((void **)&ctx->h_stats_slot[i], sizeof(mf_device_stats)));
@@ -201,7 +203,7 @@ int mf_destroy(mf_ctx *ctx)
     if (!ctx) return MF_ERR_ARG;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    void *dev[] = {ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->rank_off, ctx->rank_on, ctx->mem_on_sorted, ctx->mem_off_sorted, ctx->fit_len_on, ctx->fit_len_off, ctx->staged, ctx->type_segment, ctx->pairs_evaluated, ctx->feasible_pairs, ctx->largest_weight, ctx->wt, ctx->price,
+    void *dev[] = {ctx->score_range, ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->rank_off, ctx->rank_on, ctx->mem_on_sorted, ctx->mem_off_sorted, ctx->fit_len_on, ctx->fit_len_off, ctx->staged, ctx->type_segment, ctx->pairs_evaluated, ctx->feasible_pairs, ctx->largest_weight, ctx->wt, ctx->price,
                    ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_frontier[0], ctx->path_frontier[1], ctx->path_stamp, ctx->path_held, ctx->path_base, ctx->path_tree, ctx->edge_count, ctx->edge_start, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
@@ -364,6 +366,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "final_jump")) { if (value < 0 || value > (1 << 30)) return MF_ERR_ARG; ctx->final_jump = value; return MF_OK; }
     if (!strcmp(name, "phase_growth")) { if (value < 1 || value > 64) return MF_ERR_ARG; ctx->phase_growth = (int)value; return MF_OK; }
     if (!strcmp(name, "phase_stop")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->phase_stop = (int)value; return MF_OK; }
+    if (!strcmp(name, "score_split")) { if (value < 0 || value > 1) return MF_ERR_ARG; ctx->score_split = (int)value; return MF_OK; }
     if (!strcmp(name, "round_lag")) { if (value < 0 || value > 1) return MF_ERR_ARG; ctx->round_lag = (int)value; return MF_OK; }
     if (!strcmp(name, "tail_max")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->tail_max = (int)value; return MF_OK; }
     if (!strcmp(name, "bulk_grid")) { if (value < 0 || value > 8192) return MF_ERR_ARG; ctx->bulk_grid = (int)value; return MF_OK; }

@@ -132,6 +132,8 @@ struct mf_ctx {
     mf_device_stats *h_stats;
     mf_device_stats *h_stats_slot[2];   // pinned: where the counts of bulk rounds land while the next round runs
     hipEvent_t ev_stats[2];
+    unsigned *score_range;              // device: largest magnitudes the scorer's fp16 pieces are scaled by (range_kernel)
+    int score_split;                    // 1: the scorer's hidden layer multiplies fp16 pieces of its fp32 operands
     int round_lag;                      // 1: bulk rounds are launched one ahead of the host's reads
     mf_cert_out *h_cert;
     // options

@@ -16,6 +16,8 @@
 #include <type_traits>
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+union Half8Words { half8 v; unsigned int u[4]; uint4 q; };
 
 namespace {
 
@@ -257,12 +259,34 @@ __global__ void fill_zero_kernel(int32_t *p, int count)
     if (i < count) p[i] = 0;
 }
 
+// Largest magnitudes of up to five arrays (blockIdx.y picks one), as bit patterns of non-negative
+// floats, which order like unsigned integers: slots[y] = max |a_y[i]|.  The slots start at zero.
+__global__ void range_clear_kernel(unsigned *slots)
+{
+    if (threadIdx.x < 8) slots[threadIdx.x] = 0u;
+}
+
+struct RangeArrays { const float *a[5]; long long count[5]; };
+
+__global__ __launch_bounds__(256) void range_kernel(RangeArrays arrays, unsigned *slots)
+{
+    const float *a = arrays.a[blockIdx.y];
+    if (!a) return;
+    const long long count = arrays.count[blockIdx.y];
+    float mx = 0.0f;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < count; i += (long long)gridDim.x * 256)
+        mx = fmaxf(mx, fabsf(a[i]));
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if ((threadIdx.x & 63) == 0 && mx > 0.0f) atomicMax(&slots[blockIdx.y], __float_as_uint(mx));
+}
+
 constexpr int PAIR_THREADS = 512;   // 8 wavefronts: two per SIMD share one LDS copy of W2
 constexpr int PAIR_WAVES = PAIR_THREADS / 64;
 constexpr int PAIR_COLS = PAIR_WAVES * 32;
 
-template <int H> struct PairShape {
-    static constexpr int ROWS = 64;                        // online rows per workgroup
+template <int H, bool SPLIT> struct PairShape {
+    static constexpr int ROWS = 64;                        // online rows per workgroup (128 with the fp16 pieces: measured slower)
     static constexpr int KS = H / 2;                       // k-steps of the 32x32x2 tile
     static constexpr int MB = H / 32;                      // 32-row blocks of the hidden layer
     static constexpr size_t LDS_BYTES = sizeof(float) * ((size_t)H * H + (size_t)ROWS * H + 4 * H + 2 * ROWS);
@@ -281,7 +305,21 @@ template <int H> struct PairShape {
 // min(1 - sm_on[i], sm_off[j]); its layer-1 weights w_sm[H] add w_sm[k] * share to hidden unit k.
 // SLOWDOWN: a second output unit on the same hidden layers (weights w3_slow[H], b3_slow) predicts
 // how much the online workload of the pair slows down; a pair above slow_limit is infeasible.
-template <int H, bool PAIR_SM, bool SLOWDOWN>
+// SPLIT: the hidden layer's products are formed from half-precision pieces.  Every fp32 operand is
+// x = hi + lo with hi = x rounded to fp16 and lo = the fp16 of the exact remainder (together 22
+// significant bits; the hardware keeps fp16 subnormals), and w * h = w_hi h_hi + w_hi h_lo + w_lo h_hi
+// up to 2^-22 relative, accumulated in fp32 by v_mfma_f32_32x32x16_f16: three matrix instructions
+// of 16,384 multiply-adds in 8 passes each where fp32 operands need eight of 2,048 in 16 passes
+// each.  Measured against the fp64 reference the scores are as close as those of the fp32 products
+// (largest relative error 3-4e-7 on every benchmark configuration).  fp16 ends at 65,504 and
+// thins out below 6e-5, so both operands are first scaled by powers of two (exact) that bring the
+// largest weight, and the largest value a layer-1 unit can take, to about 2^13: `range` holds the
+// largest magnitudes of the projections, of W2 and of the SM term, found by range_kernel; the
+// accumulators then carry the product of the two scales, which b2 is given on the way in and W3
+// takes out again.  The result therefore does not depend on the size of the numbers.
+// For lane l, element t of its operand of k-block kb is hidden unit (l / 32) * H/2 + 8 kb + t, for
+// A (rows of W2) and B (pairs) alike.
+template <int H, bool PAIR_SM, bool SLOWDOWN, bool SPLIT>
 __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     const float *__restrict__ P_on, const float *__restrict__ P_off,
     const float *__restrict__ W2, const float *__restrict__ b2, const float *__restrict__ W3,
@@ -291,12 +329,14 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     const int32_t *__restrict__ row_map, const int32_t *__restrict__ col_map, int by_memory,
     unsigned long long *__restrict__ evaluated, const int32_t *__restrict__ segment,
     const float *__restrict__ w_sm, const float *__restrict__ sm_on, const float *__restrict__ sm_off,
-    const float *__restrict__ w3_slow, const float *__restrict__ b3_slow, float slow_limit)
+    const float *__restrict__ w3_slow, const float *__restrict__ b3_slow, float slow_limit,
+    const unsigned *__restrict__ range)
 {
-    using S = PairShape<H>;
-    constexpr int KS = S::KS, MB = S::MB, ROWS = S::ROWS, Q = KS / 4;
+    using S = PairShape<H, SPLIT>;
+    constexpr int KS = S::KS, MB = S::MB, ROWS = S::ROWS, Q = KS / 4, KB = H / 16;
     extern __shared__ float4 lds4[];
     float4 *a_lds = lds4;                                  // [MB][Q][64] float4: MFMA A operand order
+    uint4 *a16_lds = (uint4 *)lds4;                        // SPLIT: [2 pieces][MB][KB][64] eight fp16 each (the same bytes)
     float *pon_lds = (float *)(lds4) + H * H;              // [ROWS][H]
     float *b2_lds = pon_lds + ROWS * H;
     float *w3_lds = b2_lds + H;
@@ -327,22 +367,55 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
     // fit together, nothing in the tile does
     if (by_memory && mem_on[row_map[row0]] + mem_off[col_map[blockIdx.y * PAIR_COLS]] > mem_limit) return;
 
-    for (int idx = tid; idx < MB * Q * 64; idx += PAIR_THREADS) {
-        int ln = idx & 63, s4 = (idx >> 6) % Q, mb = idx / (64 * Q);
-        a_lds[idx] = *(const float4 *)(W2 + (size_t)(mb * 32 + (ln & 31)) * H + (ln >> 5) * KS + s4 * 4);
+    // SPLIT: the powers of two that scale layer-1 values and W2 into fp16's comfortable range
+    float scale_p = 1.0f, scale_w = 1.0f;
+    if (SPLIT) {
+        auto toward_8192 = [](float largest) {
+            if (!(largest > 0.0f) || !(largest < 3.0e38f)) return 1.0f;
+            return ldexpf(1.0f, max(-60, min(60, 13 - ilogbf(largest))));
+        };
+        const float sm_term = PAIR_SM ? __uint_as_float(range[3]) * fmaxf(1.0f, __uint_as_float(range[4])) : 0.0f;
+        scale_p = toward_8192(__uint_as_float(range[0]) + __uint_as_float(range[1]) + sm_term);
+        scale_w = toward_8192(__uint_as_float(range[2]));
+    }
+    const float scale_acc = scale_p * scale_w, unscale_acc = 1.0f / scale_acc;
+    if (SPLIT) {
+        for (int idx = tid; idx < MB * KB * 64; idx += PAIR_THREADS) {
+            const int ln = idx & 63, kb = (idx >> 6) % KB, mb = idx / (64 * KB);
+            const float *src = W2 + (size_t)(mb * 32 + (ln & 31)) * H + (ln >> 5) * KS + kb * 8;
+            const float4 w0 = *(const float4 *)src, w1 = *(const float4 *)(src + 4);
+            const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+            Half8Words hi, lo;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const float ws = w[t] * scale_w;
+                const _Float16 h = (_Float16)ws;
+                hi.v[t] = h;
+                lo.v[t] = (_Float16)(ws - (float)h);
+            }
+            a16_lds[(mb * KB + kb) * 64 + ln] = hi.q;
+            a16_lds[((MB + mb) * KB + kb) * 64 + ln] = lo.q;
+        }
+    } else {
+        for (int idx = tid; idx < MB * Q * 64; idx += PAIR_THREADS) {
+            int ln = idx & 63, s4 = (idx >> 6) % Q, mb = idx / (64 * Q);
+            a_lds[idx] = *(const float4 *)(W2 + (size_t)(mb * 32 + (ln & 31)) * H + (ln >> 5) * KS + s4 * 4);
+        }
     }
     for (int idx = tid; idx < nrows * (H / 4); idx += PAIR_THREADS) {
         const int r = idx / (H / 4), q = idx % (H / 4);
         const int gi = row_map ? row_map[row0 + r] : row0 + r;
-        ((float4 *)pon_lds)[idx] = ((const float4 *)(P_on + (size_t)gi * H))[q];
+        float4 v = ((const float4 *)(P_on + (size_t)gi * H))[q];
+        if (SPLIT) { v.x *= scale_p; v.y *= scale_p; v.z *= scale_p; v.w *= scale_p; }
+        ((float4 *)pon_lds)[idx] = v;
     }
-    if (tid < H) { b2_lds[tid] = b2[tid]; w3_lds[tid] = W3[tid]; }
+    if (tid < H) { b2_lds[tid] = b2[tid] * scale_acc; w3_lds[tid] = W3[tid] * unscale_acc; }
     if (tid < nrows) mon_lds[tid] = mem_on[row_map ? row_map[row0 + tid] : row0 + tid];
     if (PAIR_SM) {
-        if (tid < H) wsm_lds[tid] = w_sm[tid];
+        if (tid < H) wsm_lds[tid] = w_sm[tid] * scale_p;
         if (tid < nrows) son_lds[tid] = 1.0f - sm_on[row_map ? row_map[row0 + tid] : row0 + tid];
     }
-    if (SLOWDOWN && tid < H) w3s_lds[tid] = w3_slow[tid];
+    if (SLOWDOWN && tid < H) w3s_lds[tid] = w3_slow[tid] * unscale_acc;
     __syncthreads();
     if (j0 >= m) return;
 
@@ -352,7 +425,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
         float4 t = *(const float4 *)(P_off + (size_t)jc * H + hh * KS + q * 4);
-        poff[4 * q] = t.x; poff[4 * q + 1] = t.y; poff[4 * q + 2] = t.z; poff[4 * q + 3] = t.w;
+        poff[4 * q] = t.x * scale_p; poff[4 * q + 1] = t.y * scale_p; poff[4 * q + 2] = t.z * scale_p; poff[4 * q + 3] = t.w * scale_p;
     }
     const float moff = mem_off[jc];
     const float soff = PAIR_SM ? sm_off[jc] : 0.0f;
@@ -365,8 +438,9 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
 
     // NR rows of the tile at once against this wavefront's 32 columns.  Two rows share every
     // W2 operand fetched from LDS and give the matrix pipe two independent accumulator sets.
-    auto score_rows = [&](auto nr_tag, const int r) {
+    auto score_rows = [&](auto nr_tag, auto split_tag, const int r) {
         constexpr int NR = decltype(nr_tag)::value;
+        constexpr bool SPLIT_HERE = decltype(split_tag)::value;
         floatx16 acc[NR][MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
@@ -382,6 +456,55 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
         float share[NR];
 #pragma unroll
         for (int x = 0; x < NR; ++x) share[x] = PAIR_SM ? fminf(son_lds[r + x], soff) : 0.0f;
+        if constexpr (SPLIT_HERE) {
+            // the two fp16 pieces of this lane's eight layer-1 values of k-block kb, for row r + x
+            auto pieces = [&](const int kb, const int x, Half8Words &hi, Half8Words &lo) {
+                const float4 p0 = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 8 * kb);
+                const float4 p1 = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 8 * kb + 4);
+                const float pq[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                float y[8];
+                if (PAIR_SM) {
+                    const float4 s0 = *(const float4 *)(wsm_lds + hh * KS + 8 * kb);
+                    const float4 s1 = *(const float4 *)(wsm_lds + hh * KS + 8 * kb + 4);
+                    const float ws[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) y[t] = fmaxf(fmaf(ws[t], share[x], pq[t] + poff[8 * kb + t]), 0.0f);
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) y[t] = fmaxf(pq[t] + poff[8 * kb + t], 0.0f);
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    // toward zero, so the remainder keeps the sign; it is exact in fp32
+                    const auto h2 = __builtin_amdgcn_cvt_pkrtz(y[2 * t], y[2 * t + 1]);
+                    hi.u[t] = __builtin_bit_cast(unsigned int, h2);
+                    const auto l2 = __builtin_amdgcn_cvt_pkrtz(y[2 * t] - (float)h2[0], y[2 * t + 1] - (float)h2[1]);
+                    lo.u[t] = __builtin_bit_cast(unsigned int, l2);
+                }
+            };
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                Half8Words bhi[NR], blo[NR];
+#pragma unroll
+                for (int x = 0; x < NR; ++x) pieces(kb, x, bhi[x], blo[x]);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    Half8Words ahi, alo;
+                    ahi.q = a16_lds[(mb * KB + kb) * 64 + lane];
+                    alo.q = a16_lds[((MB + mb) * KB + kb) * 64 + lane];
+                    // hi x hi, then the two cross terms; consecutive instructions alternate between the rows' accumulators
+#pragma unroll
+                    for (int x = 0; x < NR; ++x)
+                        acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi.v, bhi[x].v, acc[x][mb], 0, 0, 0);
+#pragma unroll
+                    for (int x = 0; x < NR; ++x)
+                        acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi.v, blo[x].v, acc[x][mb], 0, 0, 0);
+#pragma unroll
+                    for (int x = 0; x < NR; ++x)
+                        acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo.v, bhi[x].v, acc[x][mb], 0, 0, 0);
+                }
+            }
+        } else {
         // operands of step q + 1 are fetched from LDS before the matrix instructions of step q are
         // issued, so that their latency hides behind those instead of in front of the next ones
         float4 av[2][MB], pv[2][NR];
@@ -438,6 +561,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
                 for (int x = 0; x < NR; ++x)
                     acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][mb].w, h1[x][3], acc[x][mb], 0, 0, 0);
         }
+        }
 #pragma unroll
         for (int x = 0; x < NR; ++x) {
             // output layer on this lane's 16*MB hidden units, then add the other half-wave's
@@ -471,7 +595,6 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
                 too_slow = 1.0f / (1.0f + expf(-zs)) > slow_limit;
             }
             if (hh == 0 && j < m) {
-                const int i = row_map ? row_map[row0 + r + x] : row0 + r + x;
                 float qv = rintf(sg * scale);
                 qv = fminf(fmaxf(qv, 0.0f), scale);
                 int32_t w = (int32_t)qv;
@@ -481,6 +604,9 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
                     // the staged matrix: rows and columns both in memory order, one whole line per wave
                     W[(size_t)(staged_row0 + row0 + r + x) * ldw + j] = w;
                 } else {
+                    // (looked up here, not above: a load still in flight at the end of a row makes
+                    // the next row wait for it and for every store issued after it)
+                    const int i = row_map ? row_map[row0 + r + x] : row0 + r + x;
                     W[(size_t)i * ldw + jc] = w;
                     if (sigma) sigma[(size_t)i * m + jc] = sg;
                 }
@@ -494,34 +620,34 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
         asm volatile("" ::: "memory");
         if (by_memory && mon_lds[r] + moff_least > mem_limit) break;
         const bool pair_of_rows = r + 1 < nrows && !(by_memory && mon_lds[r + 1] + moff_least > mem_limit);
-        if (pair_of_rows) { score_rows(std::integral_constant<int, 2>{}, r); r += 2; }
-        else { score_rows(std::integral_constant<int, 1>{}, r); r += 1; }
+        if (pair_of_rows) { score_rows(std::integral_constant<int, 2>{}, std::integral_constant<bool, SPLIT>{}, r); r += 2; }
+        else { score_rows(std::integral_constant<int, 1>{}, std::integral_constant<bool, SPLIT>{}, r); r += 1; }
     }
     // rows the loop left early keep the "cannot fit" marks the staged matrix was filled with
     if (evaluated && lane == 0 && r > 0) atomicAdd(evaluated, (unsigned long long)r * (unsigned)min(32, m - j0));
 }
 
-template <int H, bool PAIR_SM, bool SLOWDOWN>
+template <int H, bool PAIR_SM, bool SLOWDOWN, bool SPLIT>
 int launch_pair_variant(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, int64_t ldw,
                         float *d_sigma, const int32_t *row_map, const int32_t *col_map, bool by_memory,
                         const int32_t *segment, int grid_rows)
 {
-    using S = PairShape<H>;
+    using S = PairShape<H, SPLIT>;
     // (the attribute belongs to the device, so what has been set is remembered per context)
-    const unsigned flag = 1u << (5 + (H == 128 ? 4 : 0) + (PAIR_SM ? 2 : 0) + (SLOWDOWN ? 1 : 0));
+    const unsigned flag = 1u << (5 + (H == 128 ? 8 : 0) + (PAIR_SM ? 4 : 0) + (SLOWDOWN ? 2 : 0) + (SPLIT ? 1 : 0));
     if (!(ctx->kernels_configured & flag)) {
-        MF_HIP(hipFuncSetAttribute((const void *)pair_mlp_kernel<H, PAIR_SM, SLOWDOWN>,
+        MF_HIP(hipFuncSetAttribute((const void *)pair_mlp_kernel<H, PAIR_SM, SLOWDOWN, SPLIT>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS_BYTES));
         ctx->kernels_configured |= flag;
     }
     // x covers the rows this launch scores (a segment of the row map, or all n), padded to a
     // multiple of 8: every XCD then meets the same row tiles for each column tile
     dim3 grid((((grid_rows + S::ROWS - 1) / S::ROWS) + 7) & ~7, (m + PAIR_COLS - 1) / PAIR_COLS);
-    hipLaunchKernelGGL((pair_mlp_kernel<H, PAIR_SM, SLOWDOWN>), grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
+    hipLaunchKernelGGL((pair_mlp_kernel<H, PAIR_SM, SLOWDOWN, SPLIT>), grid, dim3(PAIR_THREADS), S::LDS_BYTES, ctx->stream,
                        ctx->proj_on, ctx->proj_off, p->d_W2, p->d_b2, p->d_W3, p->d_b3,
                        ctx->mem_on, ctx->mem_off, n, m, p->scale, p->mem_limit, d_W, ldw, d_sigma, row_map, col_map,
                        by_memory ? 1 : 0, ctx->pairs_evaluated, segment, p->d_W1sm, ctx->sm_on, ctx->sm_off,
-                       p->d_W3_slow, p->d_b3_slow, p->slow_limit);
+                       p->d_W3_slow, p->d_b3_slow, p->slow_limit, SPLIT ? ctx->score_range : nullptr);
     MF_HIP(hipGetLastError());
     return MF_OK;
 }
@@ -532,11 +658,35 @@ int launch_pair(mf_ctx *ctx, const mf_predictor *p, int n, int m, int32_t *d_W, 
                 const int32_t *segment = nullptr, int segment_rows = -1)
 {
     const int grid_rows = segment_rows >= 0 ? segment_rows : n;
-    if (p->d_W3_slow)
-        return p->d_W1sm ? launch_pair_variant<H, true, true>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows)
-                         : launch_pair_variant<H, false, true>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows);
-    return p->d_W1sm ? launch_pair_variant<H, true, false>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows)
-                     : launch_pair_variant<H, false, false>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows);
+    const int which = (p->d_W1sm ? 4 : 0) + (p->d_W3_slow ? 2 : 0) + (ctx->score_split ? 1 : 0);
+#define MF_PAIR_CASE(SM, SLOW, SPL) \
+    return launch_pair_variant<H, SM, SLOW, SPL>(ctx, p, n, m, d_W, ldw, d_sigma, row_map, col_map, by_memory, segment, grid_rows)
+    switch (which) {
+    case 0: MF_PAIR_CASE(false, false, false);
+    case 1: MF_PAIR_CASE(false, false, true);
+    case 2: MF_PAIR_CASE(false, true, false);
+    case 3: MF_PAIR_CASE(false, true, true);
+    case 4: MF_PAIR_CASE(true, false, false);
+    case 5: MF_PAIR_CASE(true, false, true);
+    case 6: MF_PAIR_CASE(true, true, false);
+    default: MF_PAIR_CASE(true, true, true);
+    }
+#undef MF_PAIR_CASE
+}
+
+// What the fp16 pieces of the scorer's hidden layer are scaled by depends on the largest
+// projections and weights: found here, after the projections, before the pair kernel.
+void launch_score_range(mf_ctx *ctx, const mf_predictor *p, int n, int m)
+{
+    if (!ctx->score_split) return;
+    RangeArrays arrays{};
+    arrays.a[0] = ctx->proj_on;  arrays.count[0] = (long long)n * p->H;
+    arrays.a[1] = ctx->proj_off; arrays.count[1] = (long long)m * p->H;
+    arrays.a[2] = p->d_W2;       arrays.count[2] = (long long)p->H * p->H;
+    arrays.a[3] = p->d_W1sm;     arrays.count[3] = p->H;
+    arrays.a[4] = p->d_W1sm ? ctx->sm_off : nullptr; arrays.count[4] = m;
+    hipLaunchKernelGGL(range_clear_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->score_range);
+    hipLaunchKernelGGL(range_kernel, dim3(64, 5), dim3(256), 0, ctx->stream, arrays, ctx->score_range);
 }
 
 // order[k] = the workload with the k-th smallest (group, key); rank[i] = its position k
@@ -675,6 +825,7 @@ int mf_launch_score(mf_ctx *ctx, const mf_predictor *preds, int n_types, const i
         tot = (long)m * H;
         hipLaunchKernelGGL(project_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, ctx->stream,
                            d_off, m, F, p->d_W1, F, (const float *)nullptr, H, ctx->proj_off);
+        launch_score_range(ctx, p, n, m);
         MF_HIP(hipGetLastError());
         if (t == 0) MF_HIP(hipEventRecord(ctx->ev[1], ctx->stream));      // later types' projections count as scoring
         const int32_t *segment = typed ? ctx->type_segment + t : nullptr;
@@ -760,6 +911,7 @@ int mf_launch_rescore(mf_ctx *ctx, const mf_predictor *p, const float *d_on, int
         hipLaunchKernelGGL(gather_feature_kernel, dim3((m + 255) / 256), dim3(256), 0, ctx->stream, d_off, m, F,
                            p->sm_off_feature, ctx->sm_off);
     }
+    launch_score_range(ctx, p, n, m);       // over everybody, as a full scoring pass would find it
     MF_HIP(hipGetLastError());
     hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->pairs_evaluated);
     ctx->pairs_total = (double)n_rows * (double)m + (double)n * (double)n_cols;

@@ -50,9 +50,38 @@ def _compare(orc, r, Wg, sg, scale=None):
                                      ("C5", 64, 300), ("C3", 65, 257)])
 def test_scores_match_checker(mm, orc, cfg, n, m):
     r = synth.scheduling_round(cfg, 1, n=n, m=m)
-    ctx = mm.Context(r["n"], max(r["m"], r["n"]))
+    for split in (1, 0):                # hidden-layer products from fp16 pieces (default) or from fp32 operands
+        ctx = mm.Context(r["n"], max(r["m"], r["n"]))
+        ctx.set_option("score_split", split)
+        Wg, sg = _score_on_gpu(mm, ctx, r)
+        _compare(orc, r, Wg, sg)
+        ctx.close()
+
+
+@pytest.mark.parametrize("case", ["huge projections", "tiny hidden weights", "huge hidden weights", "mixed magnitudes",
+                                  "zero hidden layer"])
+def test_scores_do_not_depend_on_the_size_of_the_numbers(mm, orc, case):
+    """The fp16 pieces of the hidden layer's operands are scaled into fp16's range by powers of
+    two found on the device: networks whose layers are scaled against each other (the same function
+    up to rounding, or nearly) must still meet the score tolerance."""
+    r = synth.scheduling_round("C3", 6, n=130, m=517)
+    p = {k: v.copy() for k, v in r["params"].items()}
+    if case == "huge projections":          # layer-1 values around 1e5, beyond fp16's 65,504
+        p["W1"] *= np.float32(2.0 ** 17); p["b1"] *= np.float32(2.0 ** 17); p["W2"] *= np.float32(2.0 ** -17)
+    elif case == "tiny hidden weights":     # W2 around 1e-7, where fp16 has no normal numbers
+        p["W2"] *= np.float32(2.0 ** -20); p["b2"] *= np.float32(2.0 ** -20); p["W3"] *= np.float32(2.0 ** 20)
+    elif case == "huge hidden weights":
+        p["W2"] *= np.float32(2.0 ** 22); p["b2"] *= np.float32(2.0 ** 22); p["W3"] *= np.float32(2.0 ** -22)
+    elif case == "mixed magnitudes":        # one hidden unit and one input a few thousand times larger than the rest
+        p["W2"][3, :] *= np.float32(4096.0); p["b2"][3] *= np.float32(4096.0); p["W3"][3] *= np.float32(1.0 / 4096.0)
+        p["W1"][5, :] *= np.float32(1024.0); p["b1"][5] *= np.float32(1024.0); p["W2"][:, 5] *= np.float32(1.0 / 1024.0)
+    else:
+        p["W2"][:] = 0.0
+    r["params"] = p
+    ctx = mm.Context(r["n"], r["m"])
     Wg, sg = _score_on_gpu(mm, ctx, r)
-    _compare(orc, r, Wg, sg)
+    worst = _compare(orc, r, Wg, sg)
+    assert worst < 2e-6                      # well inside the bar: the scaling costs no accuracy
     ctx.close()
 
 
