@@ -15,13 +15,16 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_FP32_PEAK = 157.3e12      # MI355X dense fp32 matrix peak, flop/s
+MFMA_FP16_PEAK = 2.5e15        # MI355X dense fp16 matrix peak, flop/s
+SPLIT_PRODUCTS = 3             # fp16 matrix products the default scorer issues per product of two fp32 operands
 HBM_PEAK = 8.0e12              # byte/s
 
 # HBM bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
 # what the same counters read for a 1 GiB copy), valid for the named kernel at the named workload
 # only.  Set an entry to None when its kernel changes after the counters were taken.
 MEASURED_TRAFFIC = {
-    ("C4", "pair_mlp_kernel"): 2.058e9,
+    ("C4", "pair_mlp_kernel"): None,
+    ("C4", "pair_mlp_kernel, fp32 products"): 2.058e9,
     ("C4", "round_kernel"): 1.614e9,
 }
 
@@ -86,6 +89,8 @@ def main():
                     help="also time scoring with this many per-GPU-type predictors (0: skip)")
     ap.add_argument("--calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (reference for hardware byte counters)")
+    ap.add_argument("--no-fp32-products", dest="fp32_products", action="store_false",
+                    help="skip the extra rounds with fp32 products in the scorer (option score_split = 0)")
     ap.add_argument("--no-sm-input", dest="sm_input", action="store_false",
                     help="skip timing the scorer with the pair-dependent SM input")
     ap.add_argument("--opt", action="append", default=[], help="solver option name=value (repeatable)")
@@ -156,7 +161,8 @@ def main():
         "value": n * m / (ms_per_step * 1e-3), "unit": "pairs/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 (scoring, MFMA) / i32 weights with exact integer duals (matching)",
+        "dtype": "f16 pieces of f32 operands with f32 accumulation (scoring, MFMA: two pieces per operand, three "
+                 "products, scores as close to f64 as with f32 products) / i32 weights with exact integer duals (matching)",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {n} online x {m} offline, F={cfg.F}, MLP {2 * cfg.F}->{cfg.H}->{cfg.H}->1, "
                                f"S={cfg.scale:g}, {cfg.features} features, ~{cfg.masked} masked, seed {args.seed}; "
@@ -171,8 +177,14 @@ def main():
         "auction": {"phases": res.phases, "rounds": res.rounds, "bids": res.bids,
                     "bytes_scanned": res.bytes_scanned, "chain_bids": res.chain_bids, "chain_depth": res.chain_depth, "chain_retries": res.chain_retries, "team_bids": res.team_bids, "path_steps": res.path_steps, "path_scans": res.path_scans, "matched": res.matched,
                     "primal": res.primal, "cert_ok": res.cert_ok, "fallbacks": res.fallbacks},
-        "roofline": {"bound": "mfma", "kernel": "pair_mlp_kernel", "achieved": achieved / 1e12,
-                     "peak": MFMA_FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_FP32_PEAK,
+        # The dominant kernel.  Its contraction runs on the fp16 matrix pipe, so the peak is that
+        # pipe's; `achieved` counts the algorithmic flops (2 H^2 per scored pair), of which the kernel
+        # issues SPLIT_PRODUCTS times as many in fp16 (`issued_frac`).
+        "roofline": {"bound": "mfma", "kernel": "pair_mlp_kernel (fp16 pieces of fp32 operands, three products)",
+                     "achieved": achieved / 1e12,
+                     "peak": MFMA_FP16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_FP16_PEAK,
+                     "issued_frac": SPLIT_PRODUCTS * achieved / MFMA_FP16_PEAK,
+                     "times_fp32_matrix_peak": achieved / MFMA_FP32_PEAK,
                      "pairs_evaluated_fraction": evaluated,
                      "traffic": MEASURED_TRAFFIC.get((cfg.name, "pair_mlp_kernel"))},
         "roofline_bid_scan": {"bound": "hbm", "kernel": "round_kernel (first round of each phase: every row bids)",
@@ -191,8 +203,30 @@ def main():
     }
     # measured ceilings of this device next to the published peaks
     ceil = ctx.measure_ceilings(W)
-    out["roofline"]["measured_ceiling"] = ceil["mfma_f32_tflops"]
-    out["roofline"]["frac_of_measured_ceiling"] = achieved / 1e12 / ceil["mfma_f32_tflops"]
+    out["roofline"]["measured_ceiling"] = ceil["mfma_f16_tflops"]
+    out["roofline"]["issued_frac_of_measured_ceiling"] = SPLIT_PRODUCTS * achieved / 1e12 / ceil["mfma_f16_tflops"]
+    if args.fp32_products:
+        # the same rounds with fp32 products in the scorer (option score_split = 0): the matrix instruction,
+        # peak and roofline of the fp32 pipe
+        ctx.set_option("score_split", 0)
+        step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        plain = [step() for _ in range(max(2, args.steps // 2))]
+        torch.cuda.synchronize()
+        plain_ms = (time.perf_counter() - t0) * 1e3 / len(plain)
+        ctx.set_option("score_split", 1)
+        assert all(s[0].cert_ok == 1 and s[0].fallbacks == 0 for s in plain)
+        plain_pair_ms = float(np.mean([s[1]["pair_scoring_ms"] for s in plain]))
+        plain_achieved = flops / (plain_pair_ms * 1e-3)
+        out["fp32_products"] = {"schedule_round_ms": plain_ms, "pair_scoring_ms": plain_pair_ms,
+                                "value": n * m / (plain_ms * 1e-3), "unit": "pairs/s",
+                                "roofline": {"bound": "mfma", "kernel": "pair_mlp_kernel (fp32 products, v_mfma_f32_32x32x2_f32)",
+                                             "achieved": plain_achieved / 1e12, "peak": MFMA_FP32_PEAK / 1e12, "unit": "TFLOP/s",
+                                             "frac": plain_achieved / MFMA_FP32_PEAK,
+                                             "measured_ceiling": ceil["mfma_f32_tflops"],
+                                             "frac_of_measured_ceiling": plain_achieved / 1e12 / ceil["mfma_f32_tflops"],
+                                             "traffic": MEASURED_TRAFFIC.get((cfg.name, "pair_mlp_kernel, fp32 products"))}}
     out["roofline_bid_scan"]["measured_ceiling"] = ceil["read_gbps"]
     out["roofline_bid_scan"]["frac_of_measured_ceiling"] = bulk_bytes / (bulk_ms * 1e-3) / 1e9 / ceil["read_gbps"]
     if args.other_seeds:

@@ -349,10 +349,11 @@ int mf_last_timings(mf_ctx *ctx, float what[16]);
  * out[0] = TFLOP/s of a dependency-free stream of v_mfma_f32_32x32x2_f32 on
  * every compute unit (the matrix instruction of the scoring kernel), out[1] its
  * duration in ms; with d_buffer (device, 16-byte aligned, `bytes` long, only
- * read) out[2] = GB/s of a plain streaming read of it and out[3] its duration.
- * Waits for the stream.
+ * read) out[2] = GB/s of a plain streaming read of it and out[3] its duration;
+ * out[4], out[5] = the same as out[0], out[1] for v_mfma_f32_32x32x16_f16 (the
+ * instruction of the default scoring path); out[6], out[7] = 0.  Waits for the stream.
  */
-int mf_measure_ceilings(mf_ctx *ctx, const void *d_buffer, int64_t bytes, float out[4]);
+int mf_measure_ceilings(mf_ctx *ctx, const void *d_buffer, int64_t bytes, float out[8]);
 
 const char *mf_strerror(int code);
 const char *mf_last_hip_error(mf_ctx *ctx);

@@ -77,7 +77,7 @@ def load_library():
     lib.mf_score_pairs_typed.argtypes = [vp, C.POINTER(Predictor), i32, vp, vp, i32, vp, i32, vp, i64, vp]
     lib.mf_schedule_round_typed.argtypes = [vp, C.POINTER(Predictor), i32, vp, vp, i32, vp, i32, vp, i64, vp, vp, vp,
                                             C.POINTER(Result)]
-    lib.mf_measure_ceilings.argtypes = [vp, vp, i64, C.POINTER(C.c_float * 4)]
+    lib.mf_measure_ceilings.argtypes = [vp, vp, i64, C.POINTER(C.c_float * 8)]
     lib.mf_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.mf_last_timings.argtypes = [vp, C.POINTER(C.c_float * 16)]
     lib.mf_strerror.argtypes = [i32]
@@ -216,12 +216,12 @@ class Context:
         return res
 
     def measure_ceilings(self, buffer=None):
-        """Measured fp32 MFMA rate (TFLOP/s) and, with a device tensor, streaming read rate (GB/s)."""
-        arr = (C.c_float * 4)()
+        """Measured fp32 and fp16 MFMA rates (TFLOP/s) and, with a device tensor, streaming read rate (GB/s)."""
+        arr = (C.c_float * 8)()
         nbytes = 0 if buffer is None else buffer.numel() * buffer.element_size()
         self._check(_lib.mf_measure_ceilings(self._h, None if buffer is None else buffer.data_ptr(), nbytes,
                                              C.byref(arr)))
-        return {"mfma_f32_tflops": float(arr[0]), "read_gbps": float(arr[2])}
+        return {"mfma_f32_tflops": float(arr[0]), "read_gbps": float(arr[2]), "mfma_f16_tflops": float(arr[4])}
 
     def last_timings(self):
         arr = (C.c_float * 16)()
