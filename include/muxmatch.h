@@ -306,9 +306,10 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
  *
  * TUNING (defaults were measured on the benchmark rounds; names and meanings may change with
  * the kernels they steer; every setting leaves the result exactly optimal):
- *   phases   "phase_stop" (16) / "phase_keep" (4) / "phase_growth" (1): either side of a phase that
+ *   phases   "phase_stop" (16) / "phase_keep" (4) / "phase_growth" (2): either side of a phase that
  *            only prepares prices ends once at most phase_stop bidders are unplaced (times
- *            phase_growth per phase before; never more than one bidder in 64, at least path_max);
+ *            phase_growth per phase before, while fewer than "phase_growth_rest" (32) bidders have
+ *            given up in this solve; never more than one bidder in 64, at least path_max);
  *            the last phase_keep phases run until nobody is left to bid.  "phase_tail_steps" (64) /
  *            "phase_tail_sides" (1: rows bidding; 2: columns; 3: both) / "phase_tail_from" (8192
  *            lines): such a side also ends after that many dependent chain steps.  "final_jump" (0:

@@ -100,7 +100,8 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->score_split = 1;
     ctx->phase_stop = 16;
     ctx->phase_keep = 4;
-    ctx->phase_growth = 1;
+    ctx->phase_growth = 2;
+    ctx->phase_growth_rest = 32;
     ctx->final_jump = 0;
     ctx->phase_tail_steps = 64;
     ctx->phase_tail_sides = 1;
@@ -364,6 +365,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "phase_tail_from")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->phase_tail_from = (int)value; return MF_OK; }
     if (!strcmp(name, "phase_tail_sides")) { if (value < 0 || value > 3) return MF_ERR_ARG; ctx->phase_tail_sides = (int)value; return MF_OK; }
     if (!strcmp(name, "final_jump")) { if (value < 0 || value > (1 << 30)) return MF_ERR_ARG; ctx->final_jump = value; return MF_OK; }
+    if (!strcmp(name, "phase_growth_rest")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->phase_growth_rest = (int)value; return MF_OK; }
     if (!strcmp(name, "phase_growth")) { if (value < 1 || value > 64) return MF_ERR_ARG; ctx->phase_growth = (int)value; return MF_OK; }
     if (!strcmp(name, "phase_stop")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->phase_stop = (int)value; return MF_OK; }
     if (!strcmp(name, "score_split")) { if (value < 0 || value > 1) return MF_ERR_ARG; ctx->score_split = (int)value; return MF_OK; }

@@ -551,7 +551,7 @@ __global__ void init_solver_kernel(int n, int m, double *price, double *profit, 
     if (i < m + 4 && (!keep_prices || i >= m)) price[i] = 0.0;
     if (i == 0) {
         stats->rounds = 0; stats->bids = 0; stats->bytes = 0; stats->round_bytes = 0; stats->head = 0;
-        stats->chain_bids = 0; stats->chain_depth = 0; stats->launch_max = 0; stats->chain_retries = 0; stats->team_bids = 0; stats->path_steps = 0; stats->path_scans = 0; stats->team_abort = 0; stats->active = 0; stats->max_weight = 0;
+        stats->chain_bids = 0; stats->chain_depth = 0; stats->launch_max = 0; stats->chain_retries = 0; stats->team_bids = 0; stats->path_steps = 0; stats->path_scans = 0; stats->team_abort = 0; stats->rested = 0; stats->active = 0; stats->max_weight = 0;
         stats->cnt[0] = 0; stats->cnt[1] = 0; stats->cnt[2] = 0; stats->cnt[3] = 0;
     }
 }
@@ -836,10 +836,10 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
     const double feasible = staged ? (double)*ctx->h_feasible_pairs : (double)n * (double)m;
     SideArgs fwd{A, (long long)lda, rm, ctx->price, ctx->colword, 0.0, Kd, flip ? len_cols : len_rows,
                  (int)(feasible / (double)rn), nullptr, (long long)ldat, rn, flip ? len_rows : len_cols,
-                 nullptr, nullptr, nullptr};
+                 nullptr, nullptr, nullptr, &ctx->stats->rested};
     SideArgs rev{At, (long long)ldat, rn, ctx->profit, ctx->roword, 0.0, Kd, flip ? len_rows : len_cols,
                  (int)(feasible / (double)rm), A, (long long)lda, rm, flip ? len_cols : len_rows,
-                 nullptr, nullptr, nullptr};
+                 nullptr, nullptr, nullptr, nullptr};
     if (flip) fwd.T = At;                       // (the other copy of the matrix: made on demand unless it is the one solved on)
     if (lists_possible && (double)*ctx->h_feasible_pairs * 100.0 < (double)ctx->fit_prefix_below * (double)n * (double)m &&
         *ctx->h_feasible_pairs + 4ull * (unsigned long long)n <= (unsigned long long)mf_edge_capacity(ctx)) {
@@ -886,7 +886,11 @@ int mf_run_solver(mf_ctx *ctx, const int32_t *d_W, int n, int m, int64_t ldw,
         long long stop_ll = 0;
         if (phases_after >= ctx->phase_keep) {
             stop_ll = ctx->phase_stop;
-            for (int k = ctx->phase_keep; k < phases_after && stop_ll < rn; ++k) stop_ll *= ctx->phase_growth;
+            // ... unless bidders have been giving up (best value at most epsilon) in this solve: then
+            // workloads stay unmatched at the optimum, the bidders left over would be the ones that
+            // end up resting, and the finer the epsilon at which they fight it out the longer it takes
+            const int growth = ctx->h_stats->rested < ctx->phase_growth_rest ? ctx->phase_growth : 1;
+            for (int k = ctx->phase_keep; k < phases_after && stop_ll < rn; ++k) stop_ll *= growth;
             // the searches are for the phases that have to finish: a coarse one ends at the latest
             // where they would take over
             if (ctx->path_max > 0 && !ctx->path_off && stop_ll > 0 && stop_ll < ctx->path_max) stop_ll = ctx->path_max;

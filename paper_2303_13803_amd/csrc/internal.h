@@ -41,6 +41,7 @@ struct mf_device_stats {            // lives in device memory, cleared per solve
     int head;                       // next unclaimed entry of the list a chain kernel works through
     int active;                     // workgroups of the running chain kernel still following a chain
     int team_abort;                 // a bounded wait between cooperating workgroups ran out (1: chain teams, 2: path search)
+    int rested;                     // bidders of the side on which rows bid that gave up with best value <= eps, this solve
     // weight bytes the rounds with many bidders read: every workgroup of such a round adds to it as
     // it leaves, so it sits on a cache line of its own, away from the list counters above
     alignas(128) unsigned long long round_bytes;
@@ -92,6 +93,7 @@ struct mf_ctx {
     int64_t warm_eps_units;         // first epsilon of a warm-started solve, in weight units
     int phase_stop;                 // unplaced bidders at or below which a phase that only prepares prices ends
     int phase_growth;               // ... times this for every phase further from the ones that run to the end
+    int phase_growth_rest;               // bidders that may have given up before coarse phases stop leaving more
     int phase_keep;                 // the last so many phases always run to the end
     long long phase_tail_steps;     // dependent chain steps after which a side that only prepares prices ends (0: no limit)
     int phase_tail_from;            // ... for problems with at least this many bidding lines
@@ -165,6 +167,7 @@ struct SideArgs {
     const long long *edge_start;
     const int *edge_col;
     const int32_t *edge_weight;
+    int *rested;                        // optional: counts the bidders that rest (best value at most eps)
 };
 
 // score.hip

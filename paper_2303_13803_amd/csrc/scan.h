@@ -284,7 +284,10 @@ __device__ __forceinline__ void block_scan_rows(const int32_t *const (&rows)[RB]
 template <bool LOOK_FIRST = false>
 __device__ inline int decide_and_bid(const SideArgs &s, int b, const Top2 &t)
 {
-    if (t.b1 <= s.eps) return -1;
+    if (t.b1 <= s.eps) {
+        if (s.rested) atomicAdd(s.rested, 1);
+        return -1;
+    }
     const double keep = fmax(t.b2 - s.eps, 0.0);
     const double offer = s.Kd * (double)t.w - keep;
     const unsigned long long mine = pack_word(offer, b + 1);

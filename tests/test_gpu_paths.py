@@ -135,6 +135,7 @@ def test_chain_kernel_with_fewer_workgroups_than_it_hands_back_at(mm, orc, chain
                                      {"phase_tail_steps": 1, "phase_tail_from": 0, "phase_tail_sides": 3},
                                      {"phase_tail_steps": 8, "phase_tail_from": 0, "phase_tail_sides": 2, "phase_stop": 64},
                                      {"phase_tail_steps": 4, "phase_tail_from": 0, "phase_tail_sides": 1, "phase_keep": 1},
+                                     {"phase_growth": 4, "phase_growth_rest": 0}, {"phase_growth": 3, "phase_growth_rest": 1 << 20},
                                      {"round_lag": 0}, {"round_lag": 1, "tail_max": 16},
                                      {"round_lag": 1, "tail_max": 0, "phase_stop": 64}])
 def test_phases_that_end_early_leave_the_optimum_alone(mm, orc, options):
