@@ -186,7 +186,10 @@ def main():
                      "issued_frac": SPLIT_PRODUCTS * achieved / MFMA_FP16_PEAK,
                      "times_fp32_matrix_peak": achieved / MFMA_FP32_PEAK,
                      "pairs_evaluated_fraction": evaluated,
-                     "traffic": MEASURED_TRAFFIC.get((cfg.name, "pair_mlp_kernel"))},
+                     "traffic": MEASURED_TRAFFIC.get((cfg.name, "pair_mlp_kernel")),
+                     "note": "frac counts one product per pair of fp32 operands against the fp16 matrix peak; the kernel "
+                             "issues three fp16 products for it (issued_frac).  The same layer with fp32 products "
+                             "(fp32_products.roofline) runs at 0.84 of the fp32 matrix peak and takes three times as long"},
         "roofline_bid_scan": {"bound": "hbm", "kernel": "round_kernel (first round of each phase: every row bids)",
                               "achieved": bulk_bytes / (bulk_ms * 1e-3) / 1e9, "peak": HBM_PEAK / 1e9,
                               "unit": "GB/s", "frac": bulk_bytes / (bulk_ms * 1e-3) / HBM_PEAK,
