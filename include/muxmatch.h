@@ -316,7 +316,9 @@ int mf_schedule_round_typed(mf_ctx *ctx, const mf_predictor *preds, int n_types,
  *            off): epsilon in weight units at or below which the next phase is the last.
  *   rounds   "tail_max" (1024 bidders: below, one kernel follows the eviction chains), "bulk_shape"
  *            (0..4: threads x lines per workgroup with many bidders: 256x1, 64x4 (default), 64x2,
- *            128x4, 256x4), "bulk_grid" (0: ten workgroups per compute unit), "round_lag" (1: the host
+ *            128x4, 256x4), "bulk_share" (95: "many" is at least that share, in percent, of the
+ *            side's lines and at least 2048; other rounds take one line per workgroup),
+ *            "bulk_grid" (0: ten workgroups per compute unit), "round_lag" (1: the host
  *            reads a round's bidder count while the next round already runs; 0: after every round)
  *   chains   "chain_grid" (256 workgroups), "team_wide" (64) / "team_max" (8) / "team_size" (16) /
  *            "team_threads" (1024) / "team_regroup" (128): several workgroups per chain once so few

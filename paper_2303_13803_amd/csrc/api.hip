@@ -111,6 +111,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     ctx->chain_grid = 256;
     ctx->bulk_shape = 1;
     ctx->bulk_grid = 0;
+    ctx->bulk_share = 95;
     ctx->team_max = 8;
     ctx->team_size = 16;
     ctx->team_wide = 64;
@@ -372,6 +373,7 @@ int mf_set_option(mf_ctx *ctx, const char *name, int64_t value)
     if (!strcmp(name, "round_lag")) { if (value < 0 || value > 1) return MF_ERR_ARG; ctx->round_lag = (int)value; return MF_OK; }
     if (!strcmp(name, "tail_max")) { if (value < 0 || value > (1 << 20)) return MF_ERR_ARG; ctx->tail_max = (int)value; return MF_OK; }
     if (!strcmp(name, "bulk_grid")) { if (value < 0 || value > 8192) return MF_ERR_ARG; ctx->bulk_grid = (int)value; return MF_OK; }
+    if (!strcmp(name, "bulk_share")) { if (value < 0 || value > 100) return MF_ERR_ARG; ctx->bulk_share = (int)value; return MF_OK; }
     if (!strcmp(name, "bulk_shape")) { if (value < 0 || value > 4) return MF_ERR_ARG; ctx->bulk_shape = (int)value; return MF_OK; }
     if (!strcmp(name, "warm_reset_cols")) { ctx->warm_reset_cols = value != 0; return MF_OK; }
     if (!strcmp(name, "warm_eps_units")) { if (value < 0 || value > (1 << 30)) return MF_ERR_ARG; ctx->warm_eps_units = value; return MF_OK; }

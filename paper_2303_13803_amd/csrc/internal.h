@@ -102,6 +102,7 @@ struct mf_ctx {
     int tail_max;                   // bidder count at or below which chains are followed in one kernel
     int bulk_grid;                  // most workgroups of such a round (0: one per group of lines, up to 8192)
     int bulk_shape;                 // workgroup shape of rounds with many bidders (see launch_round)
+    int bulk_share;                 // ... "many": at least 2048 and this share (percent) of the side's lines
     int team_max;                   // chains at or below which several workgroups share each chain (0: never)
     int team_size, team_threads;    // most workgroups per chain, threads per such workgroup
     int team_wide;                  // chains at or below which smaller teams already take over from chain_kernel

@@ -457,6 +457,8 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
 #pragma unroll
         for (int x = 0; x < NR; ++x) share[x] = PAIR_SM ? fminf(son_lds[r + x], soff) : 0.0f;
         if constexpr (SPLIT_HERE) {
+            float minus_one = -1.0f;
+            asm volatile("" : "+s"(minus_one));             // no instruction: only hides the constant from the optimiser
             // the two fp16 pieces of this lane's eight layer-1 values of k-block kb, for row r + x
             auto pieces = [&](const int kb, const int x, Half8Words &hi, Half8Words &lo) {
                 const float4 p0 = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 8 * kb);
@@ -478,7 +480,12 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
                     // toward zero, so the remainder keeps the sign; it is exact in fp32
                     const auto h2 = __builtin_amdgcn_cvt_pkrtz(y[2 * t], y[2 * t + 1]);
                     hi.u[t] = __builtin_bit_cast(unsigned int, h2);
-                    const auto l2 = __builtin_amdgcn_cvt_pkrtz(y[2 * t] - (float)h2[0], y[2 * t + 1] - (float)h2[1]);
+                    // y - hi written as a fused multiply-add by a -1 the optimiser cannot see: it is then
+                    // selected as the mixed-precision instruction that reads the fp16 piece itself, one
+                    // instruction per value instead of a conversion and a subtraction (same value: the
+                    // remainder is exact either way)
+                    const auto l2 = __builtin_amdgcn_cvt_pkrtz(__builtin_fmaf((float)h2[0], minus_one, y[2 * t]),
+                                                               __builtin_fmaf((float)h2[1], minus_one, y[2 * t + 1]));
                     lo.u[t] = __builtin_bit_cast(unsigned int, l2);
                 }
             };

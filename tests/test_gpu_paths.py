@@ -152,3 +152,26 @@ def test_phases_that_end_early_leave_the_optimum_alone(mm, orc, options):
             ctx.set_option(k, val)
         _solve_and_verify(ctx, orc, W, _optimum(orc, W))
         ctx.close()
+
+
+_BULK = {}
+
+
+@pytest.mark.parametrize("options", [{}, {"bulk_shape": 0}, {"bulk_shape": 2, "bulk_share": 0},
+                                     {"bulk_shape": 3, "bulk_share": 50}, {"bulk_shape": 4, "bulk_grid": 64},
+                                     {"bulk_share": 100, "round_lag": 0}, {"bulk_share": 0, "bulk_grid": 8192}])
+def test_workgroup_shapes_of_the_bidding_rounds(mm, orc, options):
+    """Rounds with at least 2048 bidders choose among several workgroup shapes (lines in groups
+    per wavefront when nearly every line bids, one line per workgroup otherwise); which one runs
+    when changes the order in which bids land, never the optimum.  Two matrices just large enough
+    for such rounds, the exact CPU solver run once for all settings."""
+    if not _BULK:
+        for name, W in [("square", synth.uniform_matrix(61, 2200, 2200, 2 ** 20, 0.2)),
+                        ("wide, few levels", synth.threshold_matrix(62, 2100, 2600, 256, 0.8))]:
+            _BULK[name] = (W, _optimum(orc, W))
+    for name, (W, expect) in _BULK.items():
+        ctx = mm.Context(*W.shape)
+        for k, val in options.items():
+            ctx.set_option(k, val)
+        _solve_and_verify(ctx, orc, W, expect)
+        ctx.close()
