@@ -166,7 +166,7 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->col2row, nm));
     TRY(hipMalloc(&ctx->team_ctl, 128 * 1024));
     TRY(hipMalloc(&ctx->path_ctl, 32768));
-    TRY(dev_alloc(&ctx->path_label, nm));
+    TRY(dev_alloc(&ctx->path_label, nm + 8));      // (read in groups of four, like the duals)
     TRY(dev_alloc(&ctx->path_expanded, nm));
     for (int k = 0; k < 2; ++k) {
         TRY(dev_alloc(&ctx->path_frontier[k], nm * 16));

@@ -113,7 +113,7 @@ struct mf_ctx {
     void *path_ctl;                 // control block of the shortest-path search
     unsigned long long *path_label, *path_expanded;   // [max(max_n, max_m)] each
     unsigned int *path_stamp;
-    int *path_frontier[2];          // 16 segments of max(max_n, max_m) columns each
+    unsigned long long *path_frontier[2];   // 16 segments of max(max_n, max_m) entries (column, holder) each
     int *path_held;
     double *path_base;              // per bidding line: length of the shortest path to it plus what it would pay, or +inf
     int *path_tree;                 // columns of the tree being served

@@ -79,7 +79,9 @@ struct PathBuffers {
     unsigned long long *label;      // [len] length << 20 | predecessor row
     unsigned long long *expanded;   // [len] label at which the column's holder was last scanned
     unsigned int *stamp;            // [len] last step in which the column was put on a frontier
-    int *fr_col[2];                 // frontiers (by step parity): PATH_SEGMENTS segments of len columns each
+    unsigned long long *fr_col[2];  // frontiers (by step parity): PATH_SEGMENTS segments of len entries each; an entry
+                                    // is a column and, in the upper half, the row that holds it (holders change only
+                                    // between searches' re-assignments, and no frontier outlives one)
     int *held;                      // [rows] column a frontier row holds (-1 - index for a bidder)
     double *base;                   // [rows + 8] for a row that has been scanned: its path length + its profit + eps
                                     // (a column's label through that row is base - K w + the column's dual); else PATH_FAR
@@ -159,9 +161,10 @@ __device__ inline int tree_root(const PathBuffers &buf, int k, int guard)
 
 // Lowers label[k] to `mine` if that is a strictly shorter length (a tie keeps the predecessor
 // it has: swapping predecessors at equal length could close a cycle of zero-length edges).
-__device__ inline bool lower_label(unsigned long long *word, unsigned long long mine)
+// `seen` is what the caller has read of the word, possibly outdated but never below the true word:
+// a safe first test.
+__device__ inline bool lower_label(unsigned long long *word, unsigned long long seen, unsigned long long mine)
 {
-    unsigned long long seen = *word;        // possibly outdated, never below the true word: a safe first test
     while ((mine >> MF_ID_BITS) < (seen >> MF_ID_BITS)) {
         const unsigned long long was = atomicCAS(word, seen, mine);
         if (was == seen) return true;
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
     __shared__ Top2 red[PATH_THREADS / 64];
     __shared__ unsigned s_pushes, s_base, s_first[PATH_SEGMENTS + 1];
     __shared__ unsigned long long s_sink, s_low;
-    __shared__ int s_list[PATH_PUSH_BUFFER];
+    __shared__ unsigned long long s_list[PATH_PUSH_BUFFER];
     __shared__ double s_profit[PATH_MAX_SOURCES];       // of each bidder: best value - eps
     __shared__ int s_row[PATH_MAX_SOURCES];
     __shared__ int s_alive[PATH_MAX_SOURCES], s_n_alive, s_root;
@@ -342,7 +345,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                             if (holder >= 0)
                                 store_through((unsigned long long *)&buf.base[holder], (unsigned long long)__double_as_longlong(PATH_FAR));
                             const unsigned slot = atomicAdd(&s_pushes, 1u);
-                            if (slot < (unsigned)PATH_PUSH_BUFFER) s_list[slot] = k;
+                            if (slot < (unsigned)PATH_PUSH_BUFFER) s_list[slot] = (unsigned long long)k;
                             else __hip_atomic_store(&buf.tree[atomicAdd(&ctl->tree_count, 1u)], k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
                     }
@@ -353,7 +356,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                     if (tid == 0) s_base = mine ? atomicAdd(&ctl->tree_count, mine) : 0u;
                     __syncthreads();
                     for (unsigned t = tid; t < mine; t += PATH_THREADS)
-                        __hip_atomic_store(&buf.tree[s_base + t], s_list[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_store(&buf.tree[s_base + t], (int)s_list[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if (gtid == 0)          // the bidder itself is no root any more
                         store_through((unsigned long long *)&buf.base[s_row[root]], (unsigned long long)__double_as_longlong(PATH_FAR));
                 }
@@ -477,17 +480,18 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         if (gtid < PATH_SEGMENTS)
             __hip_atomic_store(&ctl->seg[z][gtid].count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (gtid == 0) { store_through(&ctl->low[z], PATH_INF); store_through(&ctl->sink_found[z], PATH_INF); }
-        const int *frontier = buf.fr_col[step & 1u];
-        int *next_frontier = buf.fr_col[(step + 1u) & 1u];
+        const unsigned long long *frontier = buf.fr_col[step & 1u];
+        unsigned long long *next_frontier = buf.fr_col[(step + 1u) & 1u];
 
-        // puts column k on the next frontier (through the workgroup's LDS list while it has room)
-        auto push = [&](int k) {
+        // puts column k, held by row `holder`, on the next frontier (through the workgroup's LDS
+        // list while it has room)
+        auto push = [&](int k, int holder) {
+            const unsigned long long entry = ((unsigned long long)(unsigned)holder << 32) | (unsigned long long)(unsigned)k;
             const unsigned slot = atomicAdd(&s_pushes, 1u);
-            if (slot < (unsigned)PATH_PUSH_BUFFER) s_list[slot] = k;
+            if (slot < (unsigned)PATH_PUSH_BUFFER) s_list[slot] = entry;
             else {
                 const unsigned pos = atomicAdd(&ctl->seg[p][segment].count, 1u);
-                __hip_atomic_store(&next_frontier[(size_t)segment * s.len + pos], k, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+                store_through(&next_frontier[(size_t)segment * s.len + pos], entry);
             }
         };
 
@@ -504,22 +508,53 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
             const int items = nf * slices;
             for (int it = wave_id; it < items; it += total_waves) {
                 const int e = it / slices, sl = it - e * slices;
-                int i, mine_col;
-                double dist, profit;
+                int i, mine_col = -1;
                 if (from_bidders) {
-                    const int j = s_alive[e];
-                    i = s_row[j]; mine_col = -1; dist = 0.0; profit = s_profit[j];
+                    i = s_row[s_alive[e]];
                 } else {
                     int g = 0;
                     while ((unsigned)e >= s_first[g + 1]) ++g;
-                    mine_col = __hip_atomic_load(&frontier[(size_t)g * s.len + (e - s_first[g])], __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT);
-                    const unsigned long long lw = load_fresh_u64(&buf.label[mine_col]);
+                    // the entry names the column and the row that holds it: everything else the
+                    // scan needs can be requested at once, one memory round trip after this one
+                    const unsigned long long entry = load_fresh_u64(&frontier[(size_t)g * s.len + (e - s_first[g])]);
+                    mine_col = (int)(unsigned)(entry & 0xffffffffull);
+                    i = (int)(unsigned)(entry >> 32);
+                }
+                const int32_t *row = s.A + (size_t)i * s.pitch;
+                const int from = sl * span, reach = min(s.len, from + span);
+                // requested together: the column's label, what its holder pays for it, the line's
+                // length and the first entries of the slice (a line is allocated to its full
+                // length; what lies beyond its feasible part is marked infeasible)
+                unsigned long long lw = 0ull;
+                int32_t w_held = 0;
+                double p_held = 0.0;
+                if (!from_bidders) {
+                    lw = load_fresh_u64(&buf.label[mine_col]);
+                    w_held = row[mine_col];
+                    p_held = s.other_dual[mine_col];
+                }
+                const int k0 = from + lane * 4;
+                // (the labels of the slice's columns as well: whether a candidate improves one is then
+                // known without a further load per candidate)
+                int4 w4 = make_int4(MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE, MF_INFEASIBLE);
+                double2 p01 = make_double2(0.0, 0.0), p23 = make_double2(0.0, 0.0);
+                ulonglong2 l01 = make_ulonglong2(0ull, 0ull), l23 = make_ulonglong2(0ull, 0ull);
+                if (k0 < reach) {
+                    w4 = *(const int4 *)(row + k0);
+                    p01 = *(const double2 *)(s.other_dual + k0);
+                    p23 = *(const double2 *)(s.other_dual + k0 + 2);
+                    l01 = *(const ulonglong2 *)(buf.label + k0);
+                    l23 = *(const ulonglong2 *)(buf.label + k0 + 2);
+                }
+                const int to = min(line_length(s, i), reach);
+                double dist, profit;
+                if (from_bidders) {
+                    dist = 0.0; profit = s_profit[s_alive[e]];
+                } else {
                     if (lw == PATH_INF) continue;               // (cannot be: a column on a frontier has a label)
-                    i = word_id(load_fresh_u64(&s.otherword[mine_col]));
                     dist = (double)(long long)(lw >> MF_ID_BITS);
                     // the row's profit: what it holds minus that column's dual
-                    profit = s.Kd * (double)s.A[(size_t)i * s.pitch + mine_col] - s.other_dual[mine_col];
+                    profit = s.Kd * (double)w_held - p_held;
                     if (sl == 0 && lane == 0) {
                         store_through(&buf.expanded[mine_col], lw >> MF_ID_BITS);
                         __hip_atomic_store(&buf.held[i], mine_col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -532,30 +567,36 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                         }
                     }
                 }
-                const int32_t *row = s.A + (size_t)i * s.pitch;
                 const double base = dist + profit + s.eps;
-                const int from = sl * span, to = min(line_length(s, i), from + span);
-#pragma unroll 2
-                for (int k = from + lane * 4; k < to; k += 256) {
-                    const int4 w4 = *(const int4 *)(row + k);
-                    const double2 p01 = *(const double2 *)(s.other_dual + k);
-                    const double2 p23 = *(const double2 *)(s.other_dual + k + 2);
+                for (int k = k0; k < to; k += 256) {
+                    if (k != k0) {
+                        w4 = *(const int4 *)(row + k);
+                        p01 = *(const double2 *)(s.other_dual + k);
+                        p23 = *(const double2 *)(s.other_dual + k + 2);
+                        l01 = *(const ulonglong2 *)(buf.label + k);
+                        l23 = *(const ulonglong2 *)(buf.label + k + 2);
+                    }
                     const int32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
                     const double pr[4] = {p01.x, p01.y, p23.x, p23.y};
+                    const unsigned long long seen[4] = {l01.x, l01.y, l23.x, l23.y};
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const double cand = base - fma(s.Kd, (double)w[q], -pr[q]);
                         if (k + q < to && w[q] != MF_INFEASIBLE && cand < bound) {
                             const unsigned long long mine = ((unsigned long long)(long long)cand << MF_ID_BITS) |
                                                             (unsigned long long)i;
-                            if (lower_label(&buf.label[k + q], mine) && cand < limit &&
-                                atomicExch(&buf.stamp[k + q], step) != step) {
-                                if (word_id(load_fresh_u64(&s.otherword[k + q])) < 0) {  // a column nobody holds ends a path
-                                    const unsigned long long ends = (unsigned long long)(long long)cand << 21 |
-                                                                    (unsigned long long)(k + q);
-                                    atomicMin(&ctl->sink, ends);
-                                    atomicMin(&ctl->sink_found[p], ends);
-                                } else push(k + q);
+                            if (lower_label(&buf.label[k + q], seen[q], mine) && cand < limit) {
+                                // (both requested before either is looked at)
+                                const unsigned stamped = atomicExch(&buf.stamp[k + q], step);
+                                const int holder = word_id(load_fresh_u64(&s.otherword[k + q]));
+                                if (stamped != step) {
+                                    if (holder < 0) {                      // a column nobody holds ends a path
+                                        const unsigned long long ends = (unsigned long long)(long long)cand << 21 |
+                                                                        (unsigned long long)(k + q);
+                                        atomicMin(&ctl->sink, ends);
+                                        atomicMin(&ctl->sink_found[p], ends);
+                                    } else push(k + q, holder);
+                                }
                             }
                         }
                     }
@@ -580,7 +621,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                         if (holder < 0)
                             atomicMin(&s_sink, (d_int << 21) | (unsigned long long)k);
                         else if (d >= limit) atomicMin(&s_low, d_int);
-                        else push(k);
+                        else push(k, holder);
                     }
                     // a row that has been scanned may also give its column up and rest (found when it was
                     // scanned, but path ends found before a re-assignment are forgotten with it)
@@ -602,8 +643,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
         }
         __syncthreads();
         for (unsigned t = tid; t < pushed; t += PATH_THREADS)
-            __hip_atomic_store(&next_frontier[(size_t)segment * s.len + s_base + t], s_list[t], __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+            store_through(&next_frontier[(size_t)segment * s.len + s_base + t], s_list[t]);
         ++my_steps;
         if (!grid_barrier(ctl, G, generation, spin_limit)) { ok = false; break; }
     }
