@@ -176,6 +176,8 @@ int mf_create(mf_ctx **out, int device, void *hip_stream, int max_n, int max_m)
     TRY(dev_alloc(&ctx->edge_count, nm));
     TRY(dev_alloc(&ctx->edge_start, nm + 1));
     TRY(dev_alloc(&ctx->path_tree, nm));
+    TRY(dev_alloc(&ctx->path_parent, nm));
+    TRY(dev_alloc(&ctx->path_jump, nm));
     TRY(dev_alloc(&ctx->path_stamp, nm));
     TRY(dev_alloc(&ctx->list[0], nm));
     TRY(dev_alloc(&ctx->list[1], nm));
@@ -206,7 +208,7 @@ int mf_destroy(mf_ctx *ctx)
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     void *dev[] = {ctx->score_range, ctx->proj_on, ctx->proj_off, ctx->mem_on, ctx->mem_off, ctx->sm_on, ctx->sm_off, ctx->order_on, ctx->order_off, ctx->rank_off, ctx->rank_on, ctx->mem_on_sorted, ctx->mem_off_sorted, ctx->fit_len_on, ctx->fit_len_off, ctx->staged, ctx->type_segment, ctx->pairs_evaluated, ctx->feasible_pairs, ctx->largest_weight, ctx->wt, ctx->price,
-                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_frontier[0], ctx->path_frontier[1], ctx->path_stamp, ctx->path_held, ctx->path_base, ctx->path_tree, ctx->edge_count, ctx->edge_start, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
+                   ctx->profit, ctx->colword, ctx->roword, ctx->row2col, ctx->col2row, ctx->team_ctl, ctx->path_ctl, ctx->path_label, ctx->path_expanded, ctx->path_frontier[0], ctx->path_frontier[1], ctx->path_stamp, ctx->path_held, ctx->path_base, ctx->path_tree, ctx->path_parent, ctx->path_jump, ctx->edge_count, ctx->edge_start, ctx->list[0], ctx->list[1], ctx->colmark, ctx->stats,
                    ctx->cert};
     for (void *p : dev) if (p) (void)hipFree(p);
     if (ctx->h_stats) (void)hipHostFree(ctx->h_stats);

@@ -117,6 +117,7 @@ struct mf_ctx {
     int *path_held;
     double *path_base;              // per bidding line: length of the shortest path to it plus what it would pay, or +inf
     int *path_tree;                 // columns of the tree being served
+    int *path_parent, *path_jump;   // [max(max_n, max_m)] each: predecessor columns while a tree is served
     int path_max;                   // bidders at or below which shortest-path searches place them (0: never)
     long long path_after;           // chain steps per run after which the searches take over
     int path_grid;                  // workgroups of a search (0: one per compute unit)

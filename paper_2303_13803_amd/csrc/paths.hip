@@ -3,6 +3,7 @@
 // searches are the successive-shortest-path step of the Hungarian method the paper uses,
 // applied to the few bidders whose chains of bids would otherwise go on for thousands of steps).
 #include "scan.h"
+#include <limits.h>
 
 namespace {
 
@@ -48,6 +49,8 @@ constexpr int PATH_SEGMENTS = 16, PATH_PUSH_BUFFER = 4096;
 constexpr unsigned long long PATH_INF = ~0ull;
 constexpr int PATH_MAX_SOURCES = 64;                      // bidders one search places
 constexpr unsigned PATH_IN_TREE = 0xffffffffu;            // stamp of a column of the tree being served
+constexpr int PATH_NO_LABEL = INT_MIN;                    // in PathBuffers::jump: the column has no label
+constexpr int PATH_JUMP_HOPS = 4, PATH_JUMP_PASSES = 48;  // hops a column follows per pass; passes before the search gives up
 
 struct alignas(128) PathCtl {
     unsigned long long sink;        // nearest end of a path found so far: length << 21 | kind << 20 | id (kind 1: row id gives up)
@@ -66,6 +69,8 @@ struct alignas(128) PathCtl {
     alignas(128) unsigned long long steps;
     unsigned long long scans, entries;
     alignas(128) unsigned int tree_count;                     // columns of the tree being served (list in PathBuffers::tree)
+    // pass q of finding every column's root left some column short of it (zero between uses)
+    alignas(128) unsigned int jump_pending[PATH_JUMP_PASSES + 1];
     struct alignas(128) { unsigned int arrive; } group[PATH_MAX_GROUPS];
     // Frontier lengths: one counter per segment (a segment collects the pushes of sixteen
     // workgroups, so no counter is hit by more than sixteen atomics per step), in three slots:
@@ -86,6 +91,9 @@ struct PathBuffers {
     double *base;                   // [rows + 8] for a row that has been scanned: its path length + its profit + eps
                                     // (a column's label through that row is base - K w + the column's dual); else PATH_FAR
     int *tree;                      // [len] columns of the tree being served
+    int *parent;                    // [len] while a tree is served: the column whose holder gave this column its label
+                                    // (-1 - index of a bidder if that row is a bidder)
+    int *jump;                      // [len] ... and a column further up the same chain, in the end the bidder at its root
 };
 constexpr double PATH_FAR = 1.0e300;
 
@@ -131,6 +139,7 @@ __device__ inline bool grid_barrier(PathCtl *ctl, unsigned workgroups, unsigned 
 __global__ void path_begin_kernel(mf_device_stats *stats, PathCtl *ctl, int ring)
 {
     ctl->arrive.count = 0u; ctl->open.number = 0u; ctl->steps = 0ull; ctl->scans = 0ull; ctl->entries = 0ull; ctl->tree_count = 0u;
+    for (int q = 0; q <= PATH_JUMP_PASSES; ++q) ctl->jump_pending[q] = 0u;
     for (int g = 0; g < PATH_MAX_GROUPS; ++g) ctl->group[g].arrive = 0u;
     stats->cnt[(ring + 1) & 3] = 0;
     stats->cnt[(ring + 2) & 3] = 0;
@@ -143,20 +152,6 @@ __device__ inline void store_dual(const SideArgs &s, int k, double dual, int hol
 {
     store_through(&s.otherword[k], pack_word(dual, holder_plus_one));
     store_through((unsigned long long *)&s.other_dual[k], (unsigned long long)__double_as_longlong(dual));
-}
-
-// Root of the tree column k belongs to: follow the predecessors back to a bidder (its index in
-// the list; bidders are marked in held[] by -1 - index).  -1 if the chain does not end within
-// `guard` hops, which sound labels rule out.  Labels stand still while this runs.
-__device__ inline int tree_root(const PathBuffers &buf, int k, int guard)
-{
-    while (guard-- > 0) {
-        const int i = (int)(load_fresh_u64(&buf.label[k]) & MF_ID_MASK);
-        const int h = __hip_atomic_load(&buf.held[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (h < 0) return -1 - h;
-        k = h;
-    }
-    return -1;
 }
 
 // Lowers label[k] to `mine` if that is a strictly shorter length (a tie keeps the predecessor
@@ -184,7 +179,7 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
     __shared__ unsigned long long s_list[PATH_PUSH_BUFFER];
     __shared__ double s_profit[PATH_MAX_SOURCES];       // of each bidder: best value - eps
     __shared__ int s_row[PATH_MAX_SOURCES];
-    __shared__ int s_alive[PATH_MAX_SOURCES], s_n_alive, s_root;
+    __shared__ int s_alive[PATH_MAX_SOURCES], s_n_alive;
     const unsigned G = gridDim.x;
     const int wg = blockIdx.x, tid = threadIdx.x;
     const int gtid = wg * PATH_THREADS + tid, gsize = (int)G * PATH_THREADS;
@@ -320,24 +315,54 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                 const unsigned long long sink = agreed_sink, d_star = sink >> 21;
                 const int sink_id = (int)(sink & 0xfffffull);
                 const bool gives_up = ((sink >> 20) & 1ull) != 0;
-                if (tid == 0) {
-                    int root;
-                    if (gives_up) {
-                        const int h = __hip_atomic_load(&buf.held[sink_id], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        root = h < 0 ? -1 - h : tree_root(buf, h, rows + 1);
-                    } else {
-                        root = tree_root(buf, sink_id, rows + 1);
-                    }
-                    s_root = root;
+                // Which bidder's tree is it, and which columns belong to that tree?  A column's root
+                // lies at the end of its chain of predecessors, dozens to hundreds of hops away,
+                // every hop two dependent loads; instead of every column walking its chain, all
+                // columns shorten their pointers together (pointer jumping): first every labelled
+                // column notes the column above it (or the bidder, if its predecessor is one), then
+                // in every pass it moves its pointer up to the pointer of the column it points to, a
+                // few hops at a time, until all point at bidders.  Labels stand still meanwhile.
+                for (int k = gtid; k < s.len; k += gsize) {
+                    const unsigned long long lw = load_fresh_u64(&buf.label[k]);
+                    int up = PATH_NO_LABEL;
+                    if (lw != PATH_INF)
+                        up = __hip_atomic_load(&buf.held[(int)(lw & MF_ID_MASK)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&buf.parent[k], up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&buf.jump[k], up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
-                __syncthreads();
-                const int root = s_root;
+                if (!grid_barrier(ctl, G, generation, spin_limit)) { ok = false; break; }
+                int passes = 0;
+                for (;;) {
+                    bool short_of_it = false;
+                    for (int k = gtid; k < s.len; k += gsize) {
+                        int up = __hip_atomic_load(&buf.jump[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (up < 0) continue;                       // a bidder, or no label
+                        for (int hop = 0; hop < PATH_JUMP_HOPS && up >= 0; ++hop)
+                            up = __hip_atomic_load(&buf.jump[up], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        // (a pointer to a column without a label cannot be, with sound labels: it stays
+                        // as it is and reads as "no bidder" below)
+                        __hip_atomic_store(&buf.jump[k], up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        short_of_it |= up >= 0;
+                    }
+                    if (__syncthreads_or(short_of_it) && tid == 0) atomicOr(&ctl->jump_pending[passes], 1u);
+                    if (!grid_barrier(ctl, G, generation, spin_limit)) { ok = false; break; }
+                    if (load_fresh_u32(&ctl->jump_pending[passes]) == 0u) break;
+                    if (++passes >= PATH_JUMP_PASSES) { ok = false; break; }        // (the same in every workgroup)
+                }
+                if (!ok) break;
+                int root = -1;
+                {
+                    // where the path ends: a free column, or the column its last row gives up (none: the bidder itself rests)
+                    int at = sink_id;
+                    if (gives_up) at = __hip_atomic_load(&buf.held[sink_id], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (at >= 0) at = __hip_atomic_load(&buf.jump[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (at < 0 && at != PATH_NO_LABEL) root = -1 - at;
+                }
                 if (root < 0 || root >= count) { ok = false; break; }          // (the same in every workgroup)
                 if (tid == 0) s_pushes = 0u;
                 __syncthreads();
                 for (int k = gtid; k < s.len; k += gsize) {
-                    const unsigned long long lw = load_fresh_u64(&buf.label[k]);
-                    if (lw != PATH_INF && tree_root(buf, k, rows + 1) == root) {
+                    if (__hip_atomic_load(&buf.jump[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == -1 - root) {
                         __hip_atomic_store(&buf.stamp[k], PATH_IN_TREE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         if (pull) {
                             // its holder's scan no longer counts (workgroup 0 is about to change what it holds and pays)
@@ -381,11 +406,14 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
                         }
                         int guard = 0;
                         while (k >= 0 && guard++ <= rows) {
+                            // (the three loads of a hop go out together; the next hop needs `before` alone)
+                            const int before = __hip_atomic_load(&buf.parent[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             const int i = (int)(load_fresh_u64(&buf.label[k]) & MF_ID_MASK);
-                            const int before = __hip_atomic_load(&buf.held[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             store_dual(s, k, word_dual(load_fresh_u64(&s.otherword[k])) + s.eps, i + 1);
                             k = before;                     // negative: i is the bidder, the path is done
                         }
+                        for (int q = 0; q <= PATH_JUMP_PASSES; ++q)
+                            __hip_atomic_store(&ctl->jump_pending[q], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         // path ends found so far may belong to the tree that is gone: start again from
                         // "a bidder rests"; the pass over all columns below finds the others again
                         store_through(&ctl->sink, PATH_INF);
@@ -677,7 +705,8 @@ __global__ __launch_bounds__(PATH_THREADS) void path_kernel(SideArgs s, const in
 int mf_launch_path_search(mf_ctx *ctx, const SideArgs &s, int ring)
 {
     PathBuffers buf{ctx->path_label, ctx->path_expanded, ctx->path_stamp,
-                    {ctx->path_frontier[0], ctx->path_frontier[1]}, ctx->path_held, ctx->path_base, ctx->path_tree};
+                    {ctx->path_frontier[0], ctx->path_frontier[1]}, ctx->path_held, ctx->path_base, ctx->path_tree,
+                    ctx->path_parent, ctx->path_jump};
     hipLaunchKernelGGL(path_begin_kernel, dim3(1), dim3(1), 0, ctx->stream, ctx->stats, (PathCtl *)ctx->path_ctl, ring);
     const int path_wgs = ctx->path_grid > 0 && ctx->path_grid < ctx->n_cus ? ctx->path_grid : ctx->n_cus;
     SideArgs side = s;
