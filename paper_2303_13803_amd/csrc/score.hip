@@ -569,6 +569,14 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
                     acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][mb].w, h1[x][3], acc[x][mb], 0, 0, 0);
         }
         }
+        // max(v, 0) as the median of (v, 0, +inf): one instruction.  fmaxf costs two on values that
+        // come out of the matrix pipe, because the compiler first has to make sure of a quiet NaN
+        // (same result: the median of a NaN, 0 and +inf is 0 as well).
+        // The +inf is hidden from the optimiser (an empty asm, no instruction), or it would turn the
+        // median back into fmaxf.
+        float plus_inf = __builtin_inff();
+        asm volatile("" : "+s"(plus_inf));
+        auto relu = [plus_inf](const float v) { return __builtin_amdgcn_fmed3f(v, 0.0f, plus_inf); };
 #pragma unroll
         for (int x = 0; x < NR; ++x) {
             // output layer on this lane's 16*MB hidden units, then add the other half-wave's
@@ -578,10 +586,10 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     float4 wv = *(const float4 *)(w3_lds + mb * 32 + 8 * g + 4 * hh);
-                    zp = fmaf(wv.x, fmaxf(acc[x][mb][4 * g], 0.0f), zp);
-                    zp = fmaf(wv.y, fmaxf(acc[x][mb][4 * g + 1], 0.0f), zp);
-                    zp = fmaf(wv.z, fmaxf(acc[x][mb][4 * g + 2], 0.0f), zp);
-                    zp = fmaf(wv.w, fmaxf(acc[x][mb][4 * g + 3], 0.0f), zp);
+                    zp = fmaf(wv.x, relu(acc[x][mb][4 * g]), zp);
+                    zp = fmaf(wv.y, relu(acc[x][mb][4 * g + 1]), zp);
+                    zp = fmaf(wv.z, relu(acc[x][mb][4 * g + 2]), zp);
+                    zp = fmaf(wv.w, relu(acc[x][mb][4 * g + 3]), zp);
                 }
             const float z = zp + __shfl_xor(zp, 32) + bias3;
             const float sg = 1.0f / (1.0f + expf(-z));
@@ -593,10 +601,10 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         float4 wv = *(const float4 *)(w3s_lds + mb * 32 + 8 * g + 4 * hh);
-                        sp = fmaf(wv.x, fmaxf(acc[x][mb][4 * g], 0.0f), sp);
-                        sp = fmaf(wv.y, fmaxf(acc[x][mb][4 * g + 1], 0.0f), sp);
-                        sp = fmaf(wv.z, fmaxf(acc[x][mb][4 * g + 2], 0.0f), sp);
-                        sp = fmaf(wv.w, fmaxf(acc[x][mb][4 * g + 3], 0.0f), sp);
+                        sp = fmaf(wv.x, relu(acc[x][mb][4 * g]), sp);
+                        sp = fmaf(wv.y, relu(acc[x][mb][4 * g + 1]), sp);
+                        sp = fmaf(wv.z, relu(acc[x][mb][4 * g + 2]), sp);
+                        sp = fmaf(wv.w, relu(acc[x][mb][4 * g + 3]), sp);
                     }
                 const float zs = sp + __shfl_xor(sp, 32) + bias3_slow;
                 too_slow = 1.0f / (1.0f + expf(-zs)) > slow_limit;
