@@ -460,9 +460,7 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
             float minus_one = -1.0f;
             asm volatile("" : "+s"(minus_one));             // no instruction: only hides the constant from the optimiser
             // the two fp16 pieces of this lane's eight layer-1 values of k-block kb, for row r + x
-            auto pieces = [&](const int kb, const int x, Half8Words &hi, Half8Words &lo) {
-                const float4 p0 = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 8 * kb);
-                const float4 p1 = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 8 * kb + 4);
+            auto pieces = [&](const int kb, const int x, const float4 &p0, const float4 &p1, Half8Words &hi, Half8Words &lo) {
                 const float pq[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
                 float y[8];
                 if (PAIR_SM) {
@@ -489,26 +487,51 @@ __global__ __launch_bounds__(PAIR_THREADS) void pair_mlp_kernel(
                     lo.u[t] = __builtin_bit_cast(unsigned int, l2);
                 }
             };
+            // W2's pieces for step (kb, mb) + 1 are requested from LDS before the matrix instructions of
+            // step (kb, mb) are issued, so that their latency passes behind those instructions (the
+            // scheduling fences keep the compiler from moving the requests back next to their use)
+            Half8Words ahi[2], alo[2];
+            ahi[0].q = a16_lds[lane];
+            alo[0].q = a16_lds[(MB * KB) * 64 + lane];
+            // ... and the rows' projections for k-block kb + 1 before the last step of k-block kb
+            float4 pn[NR][2];
+#pragma unroll
+            for (int x = 0; x < NR; ++x) {
+                pn[x][0] = *(const float4 *)(pon_lds + (r + x) * H + hh * KS);
+                pn[x][1] = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 4);
+            }
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
                 Half8Words bhi[NR], blo[NR];
 #pragma unroll
-                for (int x = 0; x < NR; ++x) pieces(kb, x, bhi[x], blo[x]);
+                for (int x = 0; x < NR; ++x) pieces(kb, x, pn[x][0], pn[x][1], bhi[x], blo[x]);
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
-                    Half8Words ahi, alo;
-                    ahi.q = a16_lds[(mb * KB + kb) * 64 + lane];
-                    alo.q = a16_lds[((MB + mb) * KB + kb) * 64 + lane];
+                    const int step = kb * MB + mb, cur = step & 1, nxt = cur ^ 1;
+                    if (step + 1 < KB * MB) {
+                        const int kb1 = (step + 1) / MB, mb1 = (step + 1) % MB;
+                        ahi[nxt].q = a16_lds[(mb1 * KB + kb1) * 64 + lane];
+                        alo[nxt].q = a16_lds[((MB + mb1) * KB + kb1) * 64 + lane];
+                        if (mb == MB - 1) {
+#pragma unroll
+                            for (int x = 0; x < NR; ++x) {
+                                pn[x][0] = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 8 * (kb + 1));
+                                pn[x][1] = *(const float4 *)(pon_lds + (r + x) * H + hh * KS + 8 * (kb + 1) + 4);
+                            }
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                     // hi x hi, then the two cross terms; consecutive instructions alternate between the rows' accumulators
 #pragma unroll
                     for (int x = 0; x < NR; ++x)
-                        acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi.v, bhi[x].v, acc[x][mb], 0, 0, 0);
+                        acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[cur].v, bhi[x].v, acc[x][mb], 0, 0, 0);
 #pragma unroll
                     for (int x = 0; x < NR; ++x)
-                        acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi.v, blo[x].v, acc[x][mb], 0, 0, 0);
+                        acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[cur].v, blo[x].v, acc[x][mb], 0, 0, 0);
 #pragma unroll
                     for (int x = 0; x < NR; ++x)
-                        acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo.v, bhi[x].v, acc[x][mb], 0, 0, 0);
+                        acc[x][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[cur].v, bhi[x].v, acc[x][mb], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         } else {
